@@ -1,0 +1,329 @@
+"""Pins for the CPU oracle: closed forms, invariants, a library special case, brute
+force on tiny inputs, and planted mistakes that the pins must catch.
+
+Passages (arXiv 2409.15012): Section 1 (causal attention over the cached context),
+Section 3 "Sliding Window Attention Layers" (last s keys), Section 3 "KV cache reuse"
+(a layer reads an earlier layer's cache), Section 3 last paragraph (GQA).
+"""
+
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import mixattn_oracle as mo
+from oracle.mixattn_oracle import FULL, SLIDING, LayerSpec, OracleStack
+
+RNG = np.random.default_rng(20240915)
+
+
+def _stack(layers, B=1, Hq=2, Hkv=2, d=8, **kw):
+    return OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d, **kw)
+
+
+def _feed(st, layer, n, B, Hkv, d, rng):
+    ks, vs = [], []
+    for _ in range(n):
+        k = rng.standard_normal((B, Hkv, d))
+        v = rng.standard_normal((B, Hkv, d))
+        st.append(layer, k, v)
+        ks.append(k)
+        vs.append(v)
+    return np.stack(ks, 1), np.stack(vs, 1)  # [B, n, Hkv, d]
+
+
+# ------------------------------------------------------------------ closed forms
+def test_single_key_returns_its_value():
+    st = _stack([(FULL, 0, 0)])
+    k = RNG.standard_normal((1, 2, 8))
+    v = RNG.standard_normal((1, 2, 8))
+    st.append(0, k, v)
+    out = st.decode(0, RNG.standard_normal((1, 2, 8)))
+    np.testing.assert_allclose(out, v, rtol=0, atol=1e-15)
+
+
+def test_constant_keys_give_mean_of_values_full_and_window():
+    # equal keys => equal scores => uniform weights over the attended set
+    B, H, d, n, W = 1, 2, 8, 23, 5
+    st = _stack([(FULL, 0, 0), (SLIDING, W, 1)], B, H, H, d)
+    kc = RNG.standard_normal((1, H, d))
+    vs = []
+    for _ in range(n):
+        v = RNG.standard_normal((B, H, d))
+        st.append(0, kc, v)
+        st.append(1, kc, v)
+        vs.append(v)
+    V = np.stack(vs, 1)
+    q = RNG.standard_normal((B, H, d))
+    np.testing.assert_allclose(st.decode(0, q), V.mean(axis=1), atol=1e-13)
+    np.testing.assert_allclose(st.decode(1, q), V[:, n - W:].mean(axis=1), atol=1e-13)
+
+
+@pytest.mark.parametrize("W", [1, 2, 4, 7])
+def test_window_is_exactly_W_keys_including_self(W):
+    # constant keys, value at position p equals p  =>  output = mean(max(0,i-W+1) .. i),
+    # a hand-countable number that moves if the window is W+1 keys or excludes the query's token.
+    d = 4
+    st = _stack([(SLIDING, W, 0)], 1, 1, 1, d)
+    kc = np.ones((1, 1, d))
+    for i in range(12):
+        st.append(0, kc, np.full((1, 1, d), float(i)))
+        out = st.decode(0, np.ones((1, 1, d)))
+        lo = max(0, i - W + 1)
+        expect = (lo + i) / 2.0
+        np.testing.assert_allclose(out, expect, atol=1e-13)
+
+
+def test_two_key_logistic_closed_form_pins_scale_and_sign():
+    # two keys a*e0 and b*e0, query c*e0: weight of key 0 is sigmoid(scale*c*(a-b))
+    d = 16
+    a, b, c = 1.5, -0.25, 2.0
+    st = _stack([(FULL, 0, 0)], 1, 1, 1, d)
+    e0 = np.zeros((1, 1, d)); e0[..., 0] = 1.0
+    v0 = RNG.standard_normal((1, 1, d)); v1 = RNG.standard_normal((1, 1, d))
+    st.append(0, a * e0, v0)
+    st.append(0, b * e0, v1)
+    out = st.decode(0, c * e0)
+    w0 = 1.0 / (1.0 + math.exp(-(c * (a - b)) / math.sqrt(d)))
+    np.testing.assert_allclose(out, w0 * v0 + (1 - w0) * v1, atol=1e-14)
+    # an explicit scale replaces 1/sqrt(d)
+    st2 = _stack([(FULL, 0, 0)], 1, 1, 1, d, scale=0.7)
+    st2.append(0, a * e0, v0); st2.append(0, b * e0, v1)
+    w0 = 1.0 / (1.0 + math.exp(-0.7 * c * (a - b)))
+    np.testing.assert_allclose(st2.decode(0, c * e0), w0 * v0 + (1 - w0) * v1, atol=1e-14)
+
+
+def test_dominant_key_selects_its_value():
+    d, n = 8, 9
+    st = _stack([(FULL, 0, 0)], 1, 1, 1, d)
+    K, V = _feed(st, 0, n, 1, 1, d, RNG)
+    q = RNG.standard_normal((1, 1, d))
+    big = 1e4 * q / np.linalg.norm(q)
+    vb = RNG.standard_normal((1, 1, d))
+    st.append(0, big, vb)
+    K2, V2 = _feed(st, 0, 3, 1, 1, d, RNG)
+    np.testing.assert_allclose(st.decode(0, q), vb, atol=1e-12)
+
+
+# -------------------------------------------------------------------- invariants
+def test_key_shift_invariance_and_linearity_in_values():
+    B, H, d, n = 2, 2, 8, 17
+    rng = np.random.default_rng(5)
+    K = rng.standard_normal((B, n, H, d)); V = rng.standard_normal((B, n, H, d))
+    V2 = rng.standard_normal((B, n, H, d))
+    q = rng.standard_normal((B, H, d))
+    delta = rng.standard_normal((1, 1, 1, d))
+
+    def run(Kx, Vx):
+        st = _stack([(FULL, 0, 0)], B, H, H, d)
+        for p in range(n):
+            st.append(0, Kx[:, p], Vx[:, p])
+        return st.decode(0, q)
+
+    base = run(K, V)
+    np.testing.assert_allclose(run(K + delta, V), base, atol=1e-12)
+    np.testing.assert_allclose(run(K, 2.0 * V - 3.0 * V2), 2.0 * base - 3.0 * run(K, V2), atol=1e-12)
+
+
+def test_window_at_least_context_equals_full():
+    B, H, d, n = 2, 2, 8, 19
+    for W in (n, n + 1, 1000):
+        rng = np.random.default_rng(6)
+        st = _stack([(FULL, 0, 0), (SLIDING, W, 1)], B, H, H, d)
+        for _ in range(n):
+            k = rng.standard_normal((B, H, d)); v = rng.standard_normal((B, H, d))
+            st.append(0, k, v); st.append(1, k, v)
+        q = rng.standard_normal((B, H, d))
+        np.testing.assert_array_equal(st.decode(0, q), st.decode(1, q))
+
+
+def test_shared_cache_equals_duplicated_cache():
+    B, Hq, Hkv, d, W = 2, 4, 2, 8, 6
+    layers = [(FULL, 0, 0), (SLIDING, W, 1), (SLIDING, W, 1), (FULL, 0, 0)]
+    sh = _stack(layers, B, Hq, Hkv, d)
+    du = _stack(layers, B, Hq, Hkv, d, duplicate=True)
+    rng = np.random.default_rng(7)
+    S = 9
+    kv = {w: (rng.standard_normal((B, S, Hkv, d)), rng.standard_normal((B, S, Hkv, d))) for w in (0, 1)}
+    wr = {0: 0, 1: 1, 2: 1, 3: 0}
+    for li in range(4):
+        q = rng.standard_normal((B, S, Hq, d))
+        k, v = kv[wr[li]]
+        a = sh.prefill(li, q, k if sh.is_writer(li) else None, v if sh.is_writer(li) else None)
+        b = du.prefill(li, q, k, v)
+        np.testing.assert_array_equal(a, b)
+    for step in range(11):
+        new = {w: (rng.standard_normal((B, Hkv, d)), rng.standard_normal((B, Hkv, d))) for w in (0, 1)}
+        for li in range(4):
+            if sh.is_writer(li):
+                sh.append(li, *new[wr[li]])
+            du.append(li, *new[wr[li]])
+            q = rng.standard_normal((B, Hq, d))
+            np.testing.assert_array_equal(sh.decode(li, q), du.decode(li, q))
+    with pytest.raises(ValueError):
+        sh.append(2, *new[1])  # a reader appends nothing
+
+
+def test_permuting_positions_inside_the_window_changes_nothing():
+    # the softmax-weighted mean is a sum over the attended set: the order keys are visited in is irrelevant
+    d, n, W = 8, 40, 16
+    rng = np.random.default_rng(8)
+    st = _stack([(SLIDING, W, 0)], 1, 1, 1, d)
+    K, V = _feed(st, 0, n, 1, 1, d, rng)
+    q = rng.standard_normal((1, 1, d))
+    ref = st.decode(0, q)
+    perm = rng.permutation(W)
+    Kw = K[0, n - W:, 0][perm]; Vw = V[0, n - W:, 0][perm]
+    np.testing.assert_allclose(mo.attend_row(q[0, 0], Kw, Vw, st.scale), ref[0, 0], atol=1e-14)
+    # ring order: slot s holds position p = s mod W; reading slots 0..W-1 is one such permutation
+    view = mo.ring_view(SLIDING, W, n)
+    Kr = np.stack([K[0, p, 0] for p in view]); Vr = np.stack([V[0, p, 0] for p in view])
+    np.testing.assert_allclose(mo.attend_row(q[0, 0], Kr, Vr, st.scale), ref[0, 0], atol=1e-14)
+
+
+def test_gqa_equals_replicated_kv_heads():
+    B, Hq, Hkv, d, n = 2, 8, 2, 8, 13
+    G = Hq // Hkv
+    rng = np.random.default_rng(9)
+    a = _stack([(FULL, 0, 0)], B, Hq, Hkv, d)
+    b = _stack([(FULL, 0, 0)], B, Hq, Hq, d)
+    for _ in range(n):
+        k = rng.standard_normal((B, Hkv, d)); v = rng.standard_normal((B, Hkv, d))
+        a.append(0, k, v)
+        b.append(0, np.repeat(k, G, axis=1), np.repeat(v, G, axis=1))
+    q = rng.standard_normal((B, Hq, d))
+    np.testing.assert_array_equal(a.decode(0, q), b.decode(0, q))
+
+
+def test_prefill_row_equals_decode_after_that_many_appends():
+    B, Hq, Hkv, d, S, W = 2, 4, 2, 8, 21, 5
+    rng = np.random.default_rng(10)
+    q = rng.standard_normal((B, S, Hq, d))
+    k = rng.standard_normal((B, S, Hkv, d)); v = rng.standard_normal((B, S, Hkv, d))
+    for layers in ([(FULL, 0, 0)], [(SLIDING, W, 0)]):
+        pf = _stack(layers, B, Hq, Hkv, d).prefill(0, q, k, v)
+        st = _stack(layers, B, Hq, Hkv, d)
+        for i in range(S):
+            st.append(0, k[:, i], v[:, i])
+            np.testing.assert_array_equal(st.decode(0, q[:, i]), pf[:, i])
+
+
+def test_ragged_batch_mates_are_independent():
+    B, H, d = 3, 2, 8
+    lens = [5, 1, 12]
+    rng = np.random.default_rng(11)
+    st = _stack([(SLIDING, 4, 0)], B, H, H, d)
+    k = rng.standard_normal((sum(lens), H, d)); v = rng.standard_normal((sum(lens), H, d))
+    st.load(0, k, v, lens)
+    q = rng.standard_normal((B, H, d))
+    out = st.decode(0, q)
+    off = 0
+    for b, n in enumerate(lens):
+        solo = _stack([(SLIDING, 4, 0)], 1, H, H, d)
+        solo.load(0, k[off:off + n], v[off:off + n], [n])
+        np.testing.assert_array_equal(solo.decode(0, q[b:b + 1])[0], out[b])
+        off += n
+
+
+# ------------------------------------------------------- library special case
+@pytest.mark.parametrize("kind,W", [(FULL, 0), (SLIDING, 7), (SLIDING, 1)])
+def test_against_torch_cpu_fp64_sdpa_with_explicit_mask(kind, W):
+    B, Hq, Hkv, d, S = 2, 4, 2, 16, 33
+    G = Hq // Hkv
+    rng = np.random.default_rng(12)
+    q = rng.standard_normal((B, S, Hq, d)); k = rng.standard_normal((B, S, Hkv, d)); v = rng.standard_normal((B, S, Hkv, d))
+    mine = _stack([(kind, W, 0)], B, Hq, Hkv, d).prefill(0, q, k, v)
+    i = torch.arange(S)[:, None]; j = torch.arange(S)[None, :]
+    mask = j <= i
+    if kind == SLIDING:
+        mask = mask & (j > i - W)
+    tq = torch.from_numpy(q).permute(0, 2, 1, 3)
+    tk = torch.from_numpy(np.repeat(k, G, axis=2)).permute(0, 2, 1, 3)
+    tv = torch.from_numpy(np.repeat(v, G, axis=2)).permute(0, 2, 1, 3)
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask).permute(0, 2, 1, 3).numpy()
+    np.testing.assert_allclose(mine, ref, rtol=1e-12, atol=1e-13)
+
+
+# ------------------------------------------------------- brute force, tiny inputs
+def test_brute_force_python_loops_tiny():
+    B, Hq, Hkv, d, S, W = 1, 2, 1, 3, 7, 3
+    rng = np.random.default_rng(13)
+    q = rng.standard_normal((B, S, Hq, d)); k = rng.standard_normal((B, S, Hkv, d)); v = rng.standard_normal((B, S, Hkv, d))
+    for kind in (FULL, SLIDING):
+        mine = _stack([(kind, W, 0)], B, Hq, Hkv, d).prefill(0, q, k, v)
+        for i in range(S):
+            for jh in range(Hq):
+                num = [0.0] * d; den = 0.0
+                for p in range(S):
+                    allowed = p <= i and (kind == FULL or i - p < W)
+                    if not allowed:
+                        continue
+                    s = sum(q[0, i, jh, e] * k[0, p, jh // 2, e] for e in range(d)) / math.sqrt(d)
+                    w = math.exp(s)
+                    den += w
+                    for e in range(d):
+                        num[e] += w * v[0, p, jh // 2, e]
+                for e in range(d):
+                    assert abs(mine[0, i, jh, e] - num[e] / den) < 1e-12
+
+
+# ------------------------------------------------------------- ring bookkeeping
+def test_ring_slots_against_a_simulated_ring():
+    for W in (1, 3, 8):
+        ring = [None] * W
+        for n in range(1, 30):
+            p = n - 1
+            assert mo.ring_slot(SLIDING, W, p) == p % W
+            ring[p % W] = p
+            view = mo.ring_view(SLIDING, W, n)
+            assert view == [x for x in ring[:min(n, W)]]
+            assert sorted(view) == list(range(max(0, n - W), n))
+    assert mo.ring_view(FULL, 0, 5) == [0, 1, 2, 3, 4]
+    assert mo.ring_slot(FULL, 0, 123456789012) == 123456789012
+
+
+def test_kv_accounting_matches_the_section3_ratios():
+    # every l layers sharing one cache => 1/l of the caches; a sliding cache holds min(n, s) tokens
+    n = 5000
+    full = [LayerSpec(FULL, 0, i) for i in range(24)]
+    shared4 = [LayerSpec(FULL, 0, i // 4) for i in range(24)]
+    assert mo.resident_kv_tokens(shared4, [n]) * 4 == mo.resident_kv_tokens(full, [n])
+    slid = [LayerSpec(SLIDING, 1024, i) for i in range(24)]
+    assert mo.resident_kv_tokens(slid, [n]) == 24 * 1024
+    assert mo.resident_kv_tokens(slid, [100]) == 24 * 100
+    assert mo.step_read_tokens(shared4, [n]) == 24 * n
+    assert mo.kv_bytes_per_token(8, 128, 2) == 4096
+
+
+# ----------------------------------------------------------- planted mistakes
+class _WindowPlusOne(OracleStack):
+    def _attend(self, layer, b, q_row, j, i, K, V):
+        sp = self.layers[layer]
+        h = j // self.G
+        lo = max(0, i - sp.window) if sp.kind == SLIDING else 0  # W+1 keys: wrong
+        return mo.attend_row(q_row, K[lo:i + 1, h, :], V[lo:i + 1, h, :], self.scale)
+
+
+class _WrongHeadMap(OracleStack):
+    def _attend(self, layer, b, q_row, j, i, K, V):
+        h = j % self.Hkv  # interleaved instead of grouped: wrong
+        return mo.attend_row(q_row, K[:i + 1, h, :], V[:i + 1, h, :], self.scale)
+
+
+def test_pins_catch_planted_mistakes():
+    d = 4
+    st = _WindowPlusOne([LayerSpec(SLIDING, 3, 0)], 1, 1, 1, d)
+    for i in range(6):
+        st.append(0, np.ones((1, 1, d)), np.full((1, 1, d), float(i)))
+    assert abs(st.decode(0, np.ones((1, 1, d)))[0, 0, 0] - 4.0) > 0.4  # right answer is mean(3,4,5) = 4
+
+    rng = np.random.default_rng(14)
+    B, Hq, Hkv, n = 1, 4, 2, 6
+    good = OracleStack([LayerSpec(FULL, 0, 0)], B, Hq, Hkv, d)
+    bad = _WrongHeadMap([LayerSpec(FULL, 0, 0)], B, Hq, Hkv, d)
+    for _ in range(n):
+        k = rng.standard_normal((B, Hkv, d)); v = rng.standard_normal((B, Hkv, d))
+        good.append(0, k, v); bad.append(0, k, v)
+    q = rng.standard_normal((B, Hq, d))
+    assert np.abs(good.decode(0, q) - bad.decode(0, q)).max() > 1e-3
