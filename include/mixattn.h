@@ -1,0 +1,177 @@
+/*
+ * mixattn.h - C ABI of the MixAttention KV-cache attention library for MI355X (gfx950).
+ *
+ * The library runs the inference-time attention of a layer stack that mixes
+ * standard (full, causal) attention layers with sliding-window layers, where
+ * groups of layers read one KV cache written by the first layer of the group
+ * (arXiv 2409.15012, Section 3: "Sliding Window Attention Layers", "Standard
+ * Attention Layers", "KV cache reuse"; Section 1 for why the KV cache is the
+ * cost of long-context decoding).
+ *
+ * Conventions
+ *  - Every function returns MIXATTN_OK (0) or a negative mixattn_status.  Nothing
+ *    throws or aborts; on error no output buffer is written and no length changes.
+ *  - "device" pointers are HIP device memory owned by the caller (for example a
+ *    torch tensor's data_ptr()); "host" pointers are ordinary process memory.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every
+ *    call that takes a stream only enqueues work on it; calls on one layout must
+ *    be issued on one stream (or be ordered by the caller), in layer order.
+ *  - One layout is used by one host thread at a time.
+ *  - The layout owns its caches and scratch; they are allocated in
+ *    mixattn_create_layout and freed in mixattn_destroy_layout.
+ *  - Sequence lengths live on the device and are mirrored on the host without any
+ *    device-to-host copy: every append advances every sequence by exactly one.
+ *
+ * Tensor layouts (row-major, contiguous, element type = config.kv_dtype unless noted)
+ *  decode   q   [batch, n_q_heads, head_dim]
+ *           out [batch, n_q_heads, head_dim]            (config.out_dtype)
+ *  append   k,v [batch, n_kv_heads, head_dim]
+ *  prefill  q   [batch, seq, n_q_heads, head_dim]
+ *           k,v [batch, seq, n_kv_heads, head_dim]
+ *           out [batch, seq, n_q_heads, head_dim]       (config.out_dtype)
+ *  load_kv  k,v [sum(seq_lens), n_kv_heads, head_dim]   sequences back to back
+ *
+ * Query head j reads KV head j / (n_q_heads / n_kv_heads) (grouped-query attention,
+ * Section 3, last paragraph).
+ *
+ * The physical arrangement of a cache in device memory is private to the library
+ * (bf16 caches with head_dim 128 are stored in MFMA-operand tile order); the
+ * contract for cache contents is mixattn_read_cache, which returns the row a
+ * logical slot holds, and mixattn_slot_of / mixattn_slot_for for slot arithmetic.
+ */
+#ifndef MIXATTN_H
+#define MIXATTN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mixattn_layout mixattn_layout; /* opaque */
+
+typedef enum { MIXATTN_FULL = 0, MIXATTN_SLIDING = 1 } mixattn_kind;
+typedef enum { MIXATTN_F32 = 0, MIXATTN_BF16 = 1 } mixattn_dtype;
+
+typedef enum {
+  MIXATTN_OK = 0,
+  MIXATTN_ERR_NULL = -1,       /* a required pointer is NULL */
+  MIXATTN_ERR_LAYOUT = -2,     /* invalid descriptor: bad kind, window < 1, sharers of one cache differ in
+                                  kind/window, heads not divisible, unsupported head_dim or dtype, batch < 1 */
+  MIXATTN_ERR_LAYER = -3,      /* layer / cache / sequence / head / slot index out of range */
+  MIXATTN_ERR_NOT_WRITER = -4, /* append, load or k/v commit on a layer that only reads a shared cache */
+  MIXATTN_ERR_CAPACITY = -5,   /* a full cache would exceed capacity[b] */
+  MIXATTN_ERR_ORDER = -6,      /* decode on an empty cache; prefill/load on a non-empty cache; reader prefill
+                                  before its writer's; bad seq_len */
+  MIXATTN_ERR_ALLOC = -7,      /* device or host allocation failed */
+  MIXATTN_ERR_HIP = -8,        /* a HIP runtime call failed (see mixattn_last_hip_error) */
+  MIXATTN_ERR_PARAM = -9       /* unknown tuning parameter or value out of range */
+} mixattn_status;
+
+/* One layer (Section 3): its attention kind, its window (tokens, >= 1, SLIDING only; the query attends the
+   last `window` keys including its own token), and the id of the KV cache it reads.  The lowest-index layer
+   using a cache id is that cache's writer; later layers with the same id read it and store nothing.  Cache ids
+   are arbitrary non-negative integers; sharers need not be consecutive layers (Section 5.1).  All layers of
+   one cache must have the same kind and window. */
+typedef struct {
+  int32_t kind;     /* mixattn_kind */
+  int32_t window;   /* SLIDING: window size in tokens; FULL: ignored */
+  int32_t cache_id; /* >= 0 */
+} mixattn_layer_desc;
+
+typedef struct {
+  int32_t n_layers;
+  const mixattn_layer_desc* layers; /* host, [n_layers], borrowed for the call */
+  int32_t batch;
+  int32_t n_q_heads;
+  int32_t n_kv_heads; /* divides n_q_heads */
+  int32_t head_dim;   /* bf16: multiple of 8, <= 256 (128 takes the MFMA path when n_q_heads/n_kv_heads <= 8);
+                         f32: 1..256 */
+  const int32_t* capacity; /* host, [batch]: most tokens sequence b will ever hold in a FULL cache
+                              (caches are packed, so capacities may differ).  May be NULL when no layer is
+                              FULL.  Ring caches always hold `window` slots. */
+  int32_t kv_dtype;  /* mixattn_dtype of q, k, v and the caches */
+  int32_t out_dtype; /* mixattn_dtype of `out`; accumulation is fp32 either way */
+  float softmax_scale; /* 0 => 1/sqrt(head_dim) */
+} mixattn_config;
+
+/* Pure host check of a descriptor (what mixattn_create_layout runs first).  Touches no device. */
+int mixattn_validate_config(const mixattn_config* cfg);
+
+/* Builds the layout: resolves cache ids to caches and writers, allocates zero-filled caches, length arrays and
+   split-K scratch with hipMalloc on the current device.  *out receives the handle (untouched on error). */
+int mixattn_create_layout(const mixattn_config* cfg, mixattn_layout** out);
+int mixattn_destroy_layout(mixattn_layout* L);
+
+/* Empties every cache (lengths to zero; cache bytes are left as they are and never read again before being
+   overwritten).  Enqueued on `stream`. */
+int mixattn_reset(mixattn_layout* L, void* stream);
+
+/* Appends one token per sequence to the cache `layer` writes (Section 3: a sliding cache keeps the past
+   `window` tokens).  k, v: device [batch, n_kv_heads, head_dim].  Token at absolute position p = n_b goes to
+   slot p (FULL) or p mod window (SLIDING); n_b becomes n_b + 1.  Errors: NOT_WRITER, CAPACITY. */
+int mixattn_append_kv(mixattn_layout* L, int layer, const void* k, const void* v, void* stream);
+
+/* Decode-step attention of `layer` (Sections 1 and 3).  q: device [batch, n_q_heads, head_dim].  For sequence
+   b holding n_b tokens the query sits at position n_b - 1 (its group's writer has already appended this step's
+   token) and attends positions 0 .. n_b-1 (FULL) or max(0, n_b-window) .. n_b-1 (SLIDING):
+   out = sum_p softmax_p(scale * q.k_p) v_p.  out: device [batch, n_q_heads, head_dim].  Errors: ORDER if any
+   sequence is empty. */
+int mixattn_decode(mixattn_layout* L, int layer, const void* q, void* out, void* stream);
+
+/* Prompt attention on empty caches (causal; SLIDING layers also mask keys more than window-1 tokens back).
+   Writer layer: k, v are its prompt keys/values; they are attended over and committed to its cache (FULL: all
+   seq_len positions; SLIDING: the last min(seq_len, window) positions, each at slot p mod window) and every
+   n_b becomes seq_len.  Reader layer: pass the writer's prompt k, v again (attended over, not stored); the
+   writer's prefill must have run (n_b == seq_len).  Errors: ORDER, CAPACITY, NULL. */
+int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, const void* v, void* out,
+                    int seq_len, void* stream);
+
+/* Bulk fill of an empty cache without attention (sets up decode workloads and ragged batches).  Writer layers
+   only.  k, v: device, packed [sum(seq_lens), n_kv_heads, head_dim]; seq_lens: host [batch], each >= 0.  n_b
+   becomes seq_lens[b]; the cache ends in exactly the state seq_lens[b] appends would leave.  The host array is
+   copied before the call returns. */
+int mixattn_load_kv(mixattn_layout* L, int layer, const void* k, const void* v, const int32_t* seq_lens,
+                    void* stream);
+
+/* ---- introspection (host side, no device sync unless stated) ---- */
+int mixattn_n_caches(const mixattn_layout* L);
+/* cache index (0-based, in order of first use) and writer flag of a layer */
+int mixattn_cache_of(const mixattn_layout* L, int layer, int* cache_index, int* is_writer);
+/* tokens sequence b holds in a cache (host mirror) */
+int mixattn_seq_len(const mixattn_layout* L, int cache_index, int b, int64_t* n);
+/* slot that holds absolute position pos in this cache: pos (FULL) or pos mod window (SLIDING) */
+int mixattn_slot_of(const mixattn_layout* L, int cache_index, int64_t pos, int64_t* slot);
+/* the same arithmetic without a layout */
+int mixattn_slot_for(int kind, int window, int64_t pos, int64_t* slot);
+/* Debug read-back of one logical cache row.  Synchronises the device.  k_row, v_row: host buffers of head_dim
+   elements of kv_dtype (either may be NULL).  slot must be < capacity[b] (FULL) or < window (SLIDING). */
+int mixattn_read_cache(mixattn_layout* L, int cache_index, int b, int kv_head, int64_t slot, void* k_row,
+                       void* v_row);
+/* device lengths of one cache copied to host [batch]; synchronises (test helper) */
+int mixattn_read_device_lens(mixattn_layout* L, int cache_index, int32_t* lens);
+/* bytes of K+V storage resident for all caches (allocated) and bytes holding live tokens right now */
+int64_t mixattn_kv_bytes_allocated(const mixattn_layout* L);
+int64_t mixattn_kv_bytes_live(const mixattn_layout* L);
+/* K+V bytes a decode of `layer` streams right now: sum_b min(n_b, window or inf) * 2*n_kv_heads*head_dim*elem */
+int64_t mixattn_step_read_bytes(const mixattn_layout* L, int layer);
+
+/* ---- tuning knobs (defaults are chosen per call from the shapes) ---- */
+typedef enum {
+  MIXATTN_PARAM_CHUNK_KEYS = 0, /* split-K chunk length in keys for decode (multiple of 32; 0 = automatic) */
+  MIXATTN_PARAM_FUSED_COMBINE = 1, /* 1: the last workgroup of a (sequence, kv head) merges the split-K partials
+                                      itself; 0: separate combine launch */
+  MIXATTN_PARAM_PREFILL_SIMPLE = 2 /* 1: force the scalar prefill kernel (testing) */
+} mixattn_param;
+int mixattn_set_param(mixattn_layout* L, int param, int64_t value);
+int mixattn_get_param(const mixattn_layout* L, int param, int64_t* value);
+
+const char* mixattn_strerror(int status);
+/* hipError_t of the most recent HIP failure seen by this thread's calls (0 if none) */
+int mixattn_last_hip_error(void);
+const char* mixattn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MIXATTN_H */

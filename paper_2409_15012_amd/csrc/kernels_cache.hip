@@ -1,0 +1,219 @@
+// Cache-side kernels: single-token append, bulk commit of prompt / packed K,V, row gather, int fill.
+//
+// arXiv 2409.15012, Section 3: a sliding-window layer keeps the K/V of the past `window` tokens only;
+// here position p of such a cache lives in ring slot p mod window, a standard-attention cache keeps
+// position p in slot p.  Both are pure integer maps, so cache contents are a function of the token count.
+#include "mixattn_internal.h"
+
+namespace mixattn {
+
+__global__ void fill_i32_kernel(int32_t* p, int32_t v, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+hipError_t launch_fill_i32(int32_t* p, int32_t value, int64_t n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, value, n);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Append one token per sequence.  One workgroup per sequence so that the length is read once, used by
+// every thread, and bumped by one thread after all stores of this workgroup were issued.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void append_tiled_kernel(AppendLaunch a) {
+  const int b = blockIdx.x;
+  const int n = a.d_lens[b];
+  const int slot = a.window > 0 ? n % a.window : n;
+  if (slot >= a.d_slots[b]) return;  // host checks capacity first; never taken for a consistent layout
+  const int blk = slot >> 5, key = slot & 31;
+  const int64_t nblk = a.d_slots[b] >> 5;
+  const uint16_t* ks = (const uint16_t*)a.k + (int64_t)b * a.Hkv * kTiledDim;
+  const uint16_t* vs = (const uint16_t*)a.v + (int64_t)b * a.Hkv * kTiledDim;
+  uint16_t* Kd = (uint16_t*)a.K;
+  uint16_t* Vd = (uint16_t*)a.V;
+  // K: 16-byte pieces (8 dims of one key stay together)
+  for (int i = threadIdx.x; i < a.Hkv * 16; i += blockDim.x) {
+    const int h = i >> 4, c = i & 15;
+    const int64_t blk_elem = (a.d_base[b] + (int64_t)h * nblk + blk) * kBlockElems;
+    const uint4 val = *(const uint4*)(ks + h * kTiledDim + c * 8);
+    *(uint4*)(Kd + blk_elem + k_tile_offset(key, c * 8)) = val;
+  }
+  // V: single elements (the 8 neighbours of an element in memory are other keys)
+  for (int i = threadIdx.x; i < a.Hkv * kTiledDim; i += blockDim.x) {
+    const int h = i >> 7, d = i & 127;
+    const int64_t blk_elem = (a.d_base[b] + (int64_t)h * nblk + blk) * kBlockElems;
+    Vd[blk_elem + v_tile_offset(key, d)] = vs[h * kTiledDim + d];
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) a.d_lens[b] = n + 1;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void append_rowmajor_kernel(AppendLaunch a) {
+  const int b = blockIdx.x;
+  const int n = a.d_lens[b];
+  const int slot = a.window > 0 ? n % a.window : n;
+  const int slots = a.d_slots[b];
+  if (slot >= slots) return;
+  const T* ks = (const T*)a.k + (int64_t)b * a.Hkv * a.D;
+  const T* vs = (const T*)a.v + (int64_t)b * a.Hkv * a.D;
+  for (int i = threadIdx.x; i < a.Hkv * a.D; i += blockDim.x) {
+    const int h = i / a.D, d = i - h * a.D;
+    const int64_t row = a.d_base[b] + (int64_t)h * slots + slot;
+    ((T*)a.K)[row * a.D + d] = ks[i];
+    ((T*)a.V)[row * a.D + d] = vs[i];
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) a.d_lens[b] = n + 1;
+}
+
+hipError_t launch_append_tiled(const AppendLaunch& a, hipStream_t s) {
+  hipLaunchKernelGGL(append_tiled_kernel, dim3(a.batch), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t launch_append_rowmajor(const AppendLaunch& a, hipStream_t s) {
+  if (a.elem == 4)
+    hipLaunchKernelGGL(append_rowmajor_kernel<float>, dim3(a.batch), dim3(256), 0, s, a);
+  else
+    hipLaunchKernelGGL(append_rowmajor_kernel<uint16_t>, dim3(a.batch), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Bulk commit.  Destination driven: a workgroup owns one 32-slot block of one (sequence, kv head) and
+// fetches, for each slot, the source token that ends up there:
+//   window == 0 : slot s <- position s                      (valid while s < len)
+//   window  > 0 : slot s <- largest position p < len with p = s (mod window)   (valid while s < min(len, window))
+// Slots of the block that receive nothing are zero-filled so that later MFMA reads see finite data.
+// ------------------------------------------------------------------------------------------------
+__device__ inline int64_t source_position(int slot, int len, int window) {
+  if (window == 0) return slot < len ? slot : -1;
+  if (slot >= window || slot >= len) return -1;
+  return (int64_t)slot + (int64_t)((len - 1 - slot) / window) * window;
+}
+
+__global__ __launch_bounds__(256) void store_tiled_kernel(StoreLaunch a) {
+  __shared__ __attribute__((aligned(16))) uint16_t sK[kBlockKeys][kTiledDim + 8];
+  __shared__ __attribute__((aligned(16))) uint16_t sV[kBlockKeys][kTiledDim + 8];
+  const int blk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int slots = a.d_slots[b];
+  if (blk * kBlockKeys >= slots) return;
+  const int len = a.d_src_len ? a.d_src_len[b] : a.uniform_len;
+  const int64_t first = a.d_src_first ? a.d_src_first[b] : (int64_t)b * a.uniform_len;
+  if (a.d_lens_out && blk == 0 && h == 0 && threadIdx.x == 0) a.d_lens_out[b] = len;
+  // a block no source token maps to is left untouched (never read: it lies beyond the length)
+  const int live = a.window > 0 ? (len < a.window ? len : a.window) : len;
+  if (blk * kBlockKeys >= live) return;
+
+  const uint16_t* ksrc = (const uint16_t*)a.k_src;
+  const uint16_t* vsrc = (const uint16_t*)a.v_src;
+  for (int i = threadIdx.x; i < kBlockKeys * 16; i += blockDim.x) {
+    const int key = i >> 4, c = i & 15;
+    const int64_t p = source_position(blk * kBlockKeys + key, len, a.window);
+    uint4 kq = make_uint4(0, 0, 0, 0), vq = make_uint4(0, 0, 0, 0);
+    if (p >= 0) {
+      const int64_t off = ((first + p) * a.Hkv + h) * kTiledDim + c * 8;
+      kq = *(const uint4*)(ksrc + off);
+      vq = *(const uint4*)(vsrc + off);
+    }
+    *(uint4*)&sK[key][c * 8] = kq;
+    *(uint4*)&sV[key][c * 8] = vq;
+  }
+  __syncthreads();
+  const int64_t nblk = slots >> 5;
+  const int64_t blk_elem = (a.d_base[b] + (int64_t)h * nblk + blk) * kBlockElems;
+  uint16_t* Kd = (uint16_t*)a.K + blk_elem;
+  uint16_t* Vd = (uint16_t*)a.V + blk_elem;
+  for (int o = threadIdx.x; o < kBlockElems / 8; o += blockDim.x) {
+    // K piece o = t*256 + c*16 + r  holds key t*16+r, dims c*8..c*8+7
+    {
+      const int t = o >> 8, c = (o >> 4) & 15, r = o & 15;
+      *(uint4*)(Kd + o * 8) = *(const uint4*)&sK[t * 16 + r][c * 8];
+    }
+    // V piece o = nn*64 + g*16 + c  holds dim nn*16+c of keys 16*(j/4) + 4g + j%4, j = 0..7
+    {
+      const int nn = o >> 6, g = (o >> 4) & 3, c = o & 15;
+      const int d = nn * 16 + c;
+      uint16_t e[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) e[j] = sV[16 * (j >> 2) + 4 * g + (j & 3)][d];
+      uint4 val;
+      val.x = e[0] | ((uint32_t)e[1] << 16);
+      val.y = e[2] | ((uint32_t)e[3] << 16);
+      val.z = e[4] | ((uint32_t)e[5] << 16);
+      val.w = e[6] | ((uint32_t)e[7] << 16);
+      *(uint4*)(Vd + o * 8) = val;
+    }
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void store_rowmajor_kernel(StoreLaunch a) {
+  const int slot = blockIdx.x * 4 + (threadIdx.x >> 6), h = blockIdx.y, b = blockIdx.z;
+  const int lane = threadIdx.x & 63;
+  const int slots = a.d_slots[b];
+  const int len = a.d_src_len ? a.d_src_len[b] : a.uniform_len;
+  const int64_t first = a.d_src_first ? a.d_src_first[b] : (int64_t)b * a.uniform_len;
+  if (a.d_lens_out && blockIdx.x == 0 && h == 0 && threadIdx.x == 0) a.d_lens_out[b] = len;
+  if (slot >= slots) return;
+  const int64_t p = source_position(slot, len, a.window);
+  if (p < 0) return;
+  const int64_t src = ((first + p) * a.Hkv + h) * a.D;
+  const int64_t dst = (a.d_base[b] + (int64_t)h * slots + slot) * a.D;
+  for (int d = lane; d < a.D; d += 64) {
+    ((T*)a.K)[dst + d] = ((const T*)a.k_src)[src + d];
+    ((T*)a.V)[dst + d] = ((const T*)a.v_src)[src + d];
+  }
+}
+
+hipError_t launch_store_tiled(const StoreLaunch& a, hipStream_t s) {
+  const int nblk = (a.max_slots + kBlockKeys - 1) / kBlockKeys;
+  if (nblk <= 0) return hipSuccess;
+  hipLaunchKernelGGL(store_tiled_kernel, dim3(nblk, a.Hkv, a.batch), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t launch_store_rowmajor(const StoreLaunch& a, hipStream_t s) {
+  const int nb = (a.max_slots + 3) / 4;
+  if (nb <= 0) return hipSuccess;
+  if (a.elem == 4)
+    hipLaunchKernelGGL(store_rowmajor_kernel<float>, dim3(nb, a.Hkv, a.batch), dim3(256), 0, s, a);
+  else
+    hipLaunchKernelGGL(store_rowmajor_kernel<uint16_t>, dim3(nb, a.Hkv, a.batch), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Read one logical row back (debug): dst[0..D) = K row, dst[D..2D) = V row, element size `elem`.
+// ------------------------------------------------------------------------------------------------
+__global__ void gather_row_kernel(const void* K, const void* V, int64_t base, int32_t slots, int kv_head,
+                                  int64_t slot, int D, int elem, bool tiled, void* dst) {
+  const int d = threadIdx.x;
+  if (d >= D) return;
+  int64_t koff, voff;
+  if (tiled) {
+    const int64_t nblk = slots >> 5;
+    const int64_t blk_elem = (base + (int64_t)kv_head * nblk + (slot >> 5)) * kBlockElems;
+    koff = blk_elem + k_tile_offset((int)(slot & 31), d);
+    voff = blk_elem + v_tile_offset((int)(slot & 31), d);
+  } else {
+    koff = voff = (base + (int64_t)kv_head * slots + slot) * D + d;
+  }
+  if (elem == 4) {
+    ((float*)dst)[d] = ((const float*)K)[koff];
+    ((float*)dst)[D + d] = ((const float*)V)[voff];
+  } else {
+    ((uint16_t*)dst)[d] = ((const uint16_t*)K)[koff];
+    ((uint16_t*)dst)[D + d] = ((const uint16_t*)V)[voff];
+  }
+}
+
+hipError_t launch_gather_row(const void* K, const void* V, int64_t base, int32_t slots, int kv_head, int64_t slot,
+                             int D, int elem, bool tiled, void* dst, hipStream_t s) {
+  hipLaunchKernelGGL(gather_row_kernel, dim3(1), dim3(256), 0, s, K, V, base, slots, kv_head, slot, D, elem, tiled,
+                     dst);
+  return hipGetLastError();
+}
+
+}  // namespace mixattn

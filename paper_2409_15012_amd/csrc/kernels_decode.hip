@@ -1,0 +1,400 @@
+// Decode-step attention over a KV cache (arXiv 2409.15012, Section 1: for long inputs the decode step is
+// dominated by moving the KV cache out of HBM; Section 3: standard layers read the whole cache, sliding-window
+// layers the last `window` tokens, grouped-query attention shares one KV head among several query heads).
+//
+// Tiled path (bf16, head_dim 128): a workgroup of 4 wavefronts streams the 32-key blocks of one split-K chunk of
+// one (sequence, kv head).  K and V blocks arrive as 16-byte-per-lane loads that already are MFMA operands:
+//   scores^T[key, head]   = K_block (A, 16 keys x 32 dims) x Q^T (B, 32 dims x 16 head columns), 4 k-steps, 2 key tiles
+//   out^T[dim, head]     += V_block^T (A, 16 dims x 32 keys) x P^T (B, 32 keys x 16 head columns), 8 dim tiles
+// The 16 head columns hold the G query heads of the KV head twice: columns 0..G-1 carry the bf16-rounded
+// probabilities, columns G..2G-1 carry the bf16-rounded remainders, so that P enters the second product with
+// about 16 significant bits at no extra MFMA cost (the columns would otherwise be padding).  Scores, softmax
+// state and accumulators are fp32.  The online-softmax state of a head lives in the lanes of its column, so
+// rescaling the accumulator is lane-local; the only cross-lane traffic per block is two shuffles for the maximum.
+#include "mixattn_internal.h"
+
+namespace mixattn {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4_t;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+__device__ inline uint32_t bf16_bits_rn(float f) {  // f finite, round to nearest even
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <typename OutT>
+__device__ inline void store_out(OutT* p, float v);
+template <>
+__device__ inline void store_out<float>(float* p, float v) { *p = v; }
+template <>
+__device__ inline void store_out<uint16_t>(uint16_t* p, float v) { *p = (uint16_t)bf16_bits_rn(v); }
+
+constexpr int kDecodeWaves = 4;
+
+struct TiledDecodeParams {
+  const uint16_t* K; const uint16_t* V;
+  const int64_t* d_base; const int32_t* d_slots; const int32_t* d_lens;
+  int window;
+  const uint16_t* q; void* out;
+  int Hq, Hkv, G;
+  float scale_log2;  // softmax scale times log2(e)
+  int chunk_blocks, n_chunks;
+  int fused_combine;
+  float* p_acc; float* p_ml; uint32_t* counters;
+};
+
+// merges the split-K partials of one (sequence, query head): thread d handles one output dim
+template <typename OutT>
+__device__ inline void merge_partials(const float* p_acc, const float* p_ml, int n_chunks_b, int d, OutT* out) {
+  float M = -INFINITY;
+  for (int c = 0; c < n_chunks_b; ++c) M = fmaxf(M, p_ml[2 * c]);
+  float L = 0.f, acc = 0.f;
+  for (int c = 0; c < n_chunks_b; ++c) {
+    const float w = fast_exp2(p_ml[2 * c] - M);
+    L += p_ml[2 * c + 1] * w;
+    acc += p_acc[(int64_t)c * kTiledDim + d] * w;
+  }
+  store_out<OutT>(out + d, acc / L);
+}
+
+template <typename OutT>
+__global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(TiledDecodeParams a) {
+  const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  int n = a.d_lens[b];
+  if (a.window > 0 && n > a.window) n = a.window;
+  const int nb_total = (n + kBlockKeys - 1) / kBlockKeys;
+  const int blk0 = c * a.chunk_blocks;
+  if (blk0 >= nb_total) return;  // uniform for the workgroup
+  const int blk1 = min(blk0 + a.chunk_blocks, nb_total);
+  const int n_chunks_b = (nb_total + a.chunk_blocks - 1) / a.chunk_blocks;
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int col = lane & 15, g = lane >> 4;
+  const int G = a.G;
+  const bool is_hi = col < G, is_lo = (col >= G) && (col < 2 * G);
+  const int head = is_hi ? col : col - G;  // meaningful when is_hi || is_lo
+
+  // Q^T fragments: lane (col, g) holds dims kk*32 + g*8 .. +7 of its head, zeros in padding columns
+  bf16x8_t qf[4];
+  {
+    const uint16_t* qp = a.q + ((int64_t)b * a.Hq + (int64_t)h * G + head) * kTiledDim + g * 8;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      u32x4_t raw = {0u, 0u, 0u, 0u};
+      if (is_hi || is_lo) raw = *(const u32x4_t*)(qp + kk * 32);
+      qf[kk] = __builtin_bit_cast(bf16x8_t, raw);
+    }
+  }
+
+  const int64_t nblk = a.d_slots[b] >> 5;
+  const int64_t first_blk = a.d_base[b] + (int64_t)h * nblk;
+  const u32x4_t* Kb = (const u32x4_t*)(a.K + first_blk * kBlockElems) + lane;
+  const u32x4_t* Vb = (const u32x4_t*)(a.V + first_blk * kBlockElems) + lane;
+
+  floatx4_t o[8];
+#pragma unroll
+  for (int nn = 0; nn < 8; ++nn) o[nn] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+  float m = -INFINITY, lsum = 0.f;
+
+  u32x4_t kr[2][8], vr[2][8];
+  auto load_block = [&](int blk, u32x4_t* kd, u32x4_t* vd) {
+    const u32x4_t* kp = Kb + (int64_t)blk * (kBlockElems / 8);
+    const u32x4_t* vp = Vb + (int64_t)blk * (kBlockElems / 8);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) kd[i] = __builtin_nontemporal_load(kp + i * 64);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) vd[i] = __builtin_nontemporal_load(vp + i * 64);
+  };
+
+  auto compute_block = [&](int blk, u32x4_t* kd, u32x4_t* vd) {
+    floatx4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kd[kk]), qf[kk], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kd[4 + kk]), qf[kk], s1, 0, 0, 0);
+    }
+    float sv[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      sv[i] = s0[i] * a.scale_log2;      // key 4g + i of the block
+      sv[4 + i] = s1[i] * a.scale_log2;  // key 16 + 4g + i
+    }
+    if (blk == nb_total - 1 && (n & 31)) {  // ragged tail: drop keys >= n and clear their V entries
+      const int valid = n - blk * kBlockKeys;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int key = 16 * (j >> 2) + 4 * g + (j & 3);
+        if (key >= valid) {
+          sv[j] = -INFINITY;
+          const uint32_t keep = (j & 1) ? 0x0000ffffu : 0xffff0000u;
+#pragma unroll
+          for (int nn = 0; nn < 8; ++nn) vd[nn][j >> 1] &= keep;
+        }
+      }
+    }
+    float mx = sv[0];
+#pragma unroll
+    for (int j = 1; j < 8; ++j) mx = fmaxf(mx, sv[j]);
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m, mx);  // finite: every block holds at least one valid key
+    const float alpha = fast_exp2(m - m_new);
+    m = m_new;
+    float p[8], psum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      p[j] = fast_exp2(sv[j] - m_new);
+      psum += p[j];
+    }
+    lsum = lsum * alpha + psum;
+    uint32_t pb[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const uint32_t hi = bf16_bits_rn(p[j]);
+      const float rem = p[j] - __uint_as_float(hi << 16);
+      pb[j] = is_lo ? bf16_bits_rn(rem) : hi;
+    }
+    u32x4_t pw = {pb[0] | (pb[1] << 16), pb[2] | (pb[3] << 16), pb[4] | (pb[5] << 16), pb[6] | (pb[7] << 16)};
+    const bf16x8_t pf = __builtin_bit_cast(bf16x8_t, pw);
+#pragma unroll
+    for (int nn = 0; nn < 8; ++nn) {
+      o[nn] *= alpha;
+      o[nn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vd[nn]), pf, o[nn], 0, 0, 0);
+    }
+  };
+
+  // software pipeline over this wave's blocks: blk0 + wave, + 4, ...
+  int blk = blk0 + wave;
+  if (blk < blk1) load_block(blk, kr[0], vr[0]);
+  while (blk < blk1) {
+    const int nxt = blk + kDecodeWaves;
+    if (nxt < blk1) load_block(nxt, kr[1], vr[1]);
+    compute_block(blk, kr[0], vr[0]);
+    if (nxt >= blk1) break;
+    const int nxt2 = nxt + kDecodeWaves;
+    if (nxt2 < blk1) load_block(nxt2, kr[0], vr[0]);
+    compute_block(nxt, kr[1], vr[1]);
+    blk = nxt2;
+  }
+
+  // ---- wave epilogue: total sum over the 4 lane groups, remainder columns folded into their head's column
+  lsum += __shfl_xor(lsum, 16);
+  lsum += __shfl_xor(lsum, 32);
+#pragma unroll
+  for (int nn = 0; nn < 8; ++nn)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[nn][i] += __shfl_down(o[nn][i], G);  // lane col+G of the same 16-lane row
+
+  __shared__ float s_o[kDecodeWaves][kMaxGroup][kTiledDim];
+  __shared__ float s_m[kDecodeWaves][kMaxGroup];
+  __shared__ float s_l[kDecodeWaves][kMaxGroup];
+  __shared__ int s_last;
+  if (is_hi) {
+#pragma unroll
+    for (int nn = 0; nn < 8; ++nn)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) s_o[wave][col][nn * 16 + 4 * g + i] = o[nn][i];
+    if (g == 0) {
+      s_m[wave][col] = m;
+      s_l[wave][col] = lsum;
+    }
+  }
+  __syncthreads();
+
+  const bool direct = (a.n_chunks == 1);
+  for (int idx = tid; idx < G * kTiledDim; idx += kDecodeWaves * 64) {
+    const int hd = idx >> 7, d = idx & 127;
+    float M = s_m[0][hd];
+#pragma unroll
+    for (int w = 1; w < kDecodeWaves; ++w) M = fmaxf(M, s_m[w][hd]);
+    float L = 0.f, acc = 0.f;
+#pragma unroll
+    for (int w = 0; w < kDecodeWaves; ++w) {
+      const float wgt = fast_exp2(s_m[w][hd] - M);  // a wave without blocks has m = -inf, weight 0
+      L += s_l[w][hd] * wgt;
+      acc += s_o[w][hd][d] * wgt;
+    }
+    const int64_t row = (int64_t)b * a.Hq + (int64_t)h * G + hd;
+    if (direct) {
+      store_out<OutT>((OutT*)a.out + row * kTiledDim + d, acc / L);
+    } else {
+      const int64_t pr = row * kMaxChunks + c;
+      a.p_acc[pr * kTiledDim + d] = acc;
+      if (d == 0) {
+        a.p_ml[2 * pr] = M;
+        a.p_ml[2 * pr + 1] = L;
+      }
+    }
+  }
+  if (direct || !a.fused_combine) return;
+
+  // ---- fused combine: the workgroup that arrives last for this (sequence, kv head) merges all chunks
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    const uint32_t prev = atomicAdd(&a.counters[b * a.Hkv + h], 1u);
+    s_last = (prev == (uint32_t)(n_chunks_b - 1));
+    if (s_last) a.counters[b * a.Hkv + h] = 0u;  // ready for the next launch on this stream
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  for (int idx = tid; idx < G * kTiledDim; idx += kDecodeWaves * 64) {
+    const int hd = idx >> 7, d = idx & 127;
+    const int64_t row = (int64_t)b * a.Hq + (int64_t)h * G + hd;
+    merge_partials<OutT>(a.p_acc + row * kMaxChunks * kTiledDim, a.p_ml + row * kMaxChunks * 2, n_chunks_b, d,
+                         (OutT*)a.out + row * kTiledDim);
+  }
+}
+
+template <typename OutT>
+__global__ __launch_bounds__(kTiledDim) void combine_kernel(TiledDecodeParams a) {
+  const int hq = blockIdx.x, b = blockIdx.y;
+  int n = a.d_lens[b];
+  if (a.window > 0 && n > a.window) n = a.window;
+  const int nb_total = (n + kBlockKeys - 1) / kBlockKeys;
+  const int n_chunks_b = (nb_total + a.chunk_blocks - 1) / a.chunk_blocks;
+  const int64_t row = (int64_t)b * a.Hq + hq;
+  merge_partials<OutT>(a.p_acc + row * kMaxChunks * kTiledDim, a.p_ml + row * kMaxChunks * 2, n_chunks_b,
+                       threadIdx.x, (OutT*)a.out + row * kTiledDim);
+}
+
+hipError_t launch_decode_tiled(const DecodeLaunch& L, hipStream_t s) {
+  TiledDecodeParams p;
+  p.K = (const uint16_t*)L.K; p.V = (const uint16_t*)L.V;
+  p.d_base = L.d_base; p.d_slots = L.d_slots; p.d_lens = L.d_lens;
+  p.window = L.window;
+  p.q = (const uint16_t*)L.q; p.out = L.out;
+  p.Hq = L.Hq; p.Hkv = L.Hkv; p.G = L.G;
+  p.scale_log2 = L.scale * kLog2e;
+  p.chunk_blocks = L.chunk_blocks; p.n_chunks = L.n_chunks;
+  p.fused_combine = L.fused_combine;
+  p.p_acc = L.scratch.acc; p.p_ml = L.scratch.ml; p.counters = L.scratch.counters;
+  const dim3 grid(L.n_chunks, L.Hkv, L.batch), block(kDecodeWaves * 64);
+  if (L.out_dtype == MIXATTN_F32)
+    hipLaunchKernelGGL(decode_tiled_kernel<float>, grid, block, 0, s, p);
+  else
+    hipLaunchKernelGGL(decode_tiled_kernel<uint16_t>, grid, block, 0, s, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (L.n_chunks > 1 && !L.fused_combine) {
+    const dim3 cgrid(L.Hq, L.batch), cblock(kTiledDim);
+    if (L.out_dtype == MIXATTN_F32)
+      hipLaunchKernelGGL(combine_kernel<float>, cgrid, cblock, 0, s, p);
+    else
+      hipLaunchKernelGGL(combine_kernel<uint16_t>, cgrid, cblock, 0, s, p);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Row-major path (fp32 caches, or bf16 shapes outside the MFMA path): one workgroup per (sequence, query
+// head); each wavefront walks every 4th key, lanes split the head dimension.  Plain fp32 arithmetic.
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__device__ inline float load_as_float(const T* p);
+template <>
+__device__ inline float load_as_float<float>(const float* p) { return *p; }
+template <>
+__device__ inline float load_as_float<uint16_t>(const uint16_t* p) { return __uint_as_float((uint32_t)*p << 16); }
+
+__device__ inline float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+  return x;
+}
+
+struct RowDecodeParams {
+  const void* K; const void* V;
+  const int64_t* d_base; const int32_t* d_slots; const int32_t* d_lens;
+  int window;
+  const void* q; void* out;
+  int Hq, G, D;
+  float scale;
+};
+
+template <typename T, typename OutT>
+__global__ __launch_bounds__(256) void decode_rowmajor_kernel(RowDecodeParams a) {
+  const int hq = blockIdx.x, b = blockIdx.y;
+  const int h = hq / a.G;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  int n = a.d_lens[b];
+  if (a.window > 0 && n > a.window) n = a.window;
+  const int slots = a.d_slots[b];
+  const int D = a.D;
+  const T* Kp = (const T*)a.K + (a.d_base[b] + (int64_t)h * slots) * D;
+  const T* Vp = (const T*)a.V + (a.d_base[b] + (int64_t)h * slots) * D;
+  const T* qp = (const T*)a.q + ((int64_t)b * a.Hq + hq) * D;
+  float qv[4], acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int d = lane + 64 * i;
+    qv[i] = d < D ? load_as_float<T>(qp + d) : 0.f;
+    acc[i] = 0.f;
+  }
+  float m = -INFINITY, l = 0.f;
+  for (int s = wave; s < n; s += 4) {
+    float part = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int d = lane + 64 * i;
+      if (d < D) part += qv[i] * load_as_float<T>(Kp + (int64_t)s * D + d);
+    }
+    const float sc = wave_sum(part) * a.scale;
+    const float m_new = fmaxf(m, sc);
+    const float alpha = expf(m - m_new);
+    const float p = expf(sc - m_new);
+    l = l * alpha + p;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int d = lane + 64 * i;
+      if (d < D) acc[i] = acc[i] * alpha + p * load_as_float<T>(Vp + (int64_t)s * D + d);
+    }
+    m = m_new;
+  }
+  __shared__ float s_acc[4][kMaxHeadDim];
+  __shared__ float s_m[4], s_l[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int d = lane + 64 * i;
+    if (d < D) s_acc[wave][d] = acc[i];
+  }
+  if (lane == 0) {
+    s_m[wave] = m;
+    s_l[wave] = l;
+  }
+  __syncthreads();
+  for (int d = tid; d < D; d += 256) {
+    float M = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+    float L = 0.f, o = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float wgt = (s_m[w] == -INFINITY) ? 0.f : expf(s_m[w] - M);
+      L += s_l[w] * wgt;
+      o += s_acc[w][d] * wgt;
+    }
+    store_out<OutT>((OutT*)a.out + ((int64_t)b * a.Hq + hq) * D + d, o / L);
+  }
+}
+
+hipError_t launch_decode_rowmajor(const DecodeLaunch& L, hipStream_t s) {
+  RowDecodeParams p;
+  p.K = L.K; p.V = L.V; p.d_base = L.d_base; p.d_slots = L.d_slots; p.d_lens = L.d_lens;
+  p.window = L.window; p.q = L.q; p.out = L.out; p.Hq = L.Hq; p.G = L.G; p.D = L.D; p.scale = L.scale;
+  const dim3 grid(L.Hq, L.batch), block(256);
+  const bool f32 = L.kv_dtype == MIXATTN_F32, of32 = L.out_dtype == MIXATTN_F32;
+  if (f32 && of32) hipLaunchKernelGGL((decode_rowmajor_kernel<float, float>), grid, block, 0, s, p);
+  else if (f32) hipLaunchKernelGGL((decode_rowmajor_kernel<float, uint16_t>), grid, block, 0, s, p);
+  else if (of32) hipLaunchKernelGGL((decode_rowmajor_kernel<uint16_t, float>), grid, block, 0, s, p);
+  else hipLaunchKernelGGL((decode_rowmajor_kernel<uint16_t, uint16_t>), grid, block, 0, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace mixattn

@@ -1,0 +1,316 @@
+// Prompt (prefill) attention: causal, and for sliding-window layers restricted to the last `window` keys
+// including the query's own token (arXiv 2409.15012, Section 3, "Sliding Window Attention Layers"; Section 1 for
+// the causal standard layer).
+//
+// Tiled path (bf16, head_dim 128): flash-attention forward on 32x32x16 bf16 MFMA.  K and V are read in the same
+// 32-key block format the decode caches use (the full cache itself, or a staging copy of the prompt for sliding
+// layers), so a block is copied verbatim into LDS and every operand fragment is one 16-byte LDS read per lane.
+// A workgroup of 4 wavefronts owns 128 query rows of one query head (32 rows per wavefront) and walks the 64-key
+// tiles its rows can see, skipping tiles that are masked for all of them:
+//   scores^T[key, row]  = K (A, 32 keys x 16 dims) x Q^T (B, 16 dims x 32 rows),  8 k-steps per 32-key block
+//   out^T[dim, row]    += V^T (A, 32 dims x 16 keys) x P^T (B, 16 keys x 32 rows), P split into bf16 head + remainder
+// Lane l holds query row l%32 in both products, so the online-softmax state and the accumulator rescale are
+// lane-local; the row maximum needs one exchange with lane l^32.
+#include "mixattn_internal.h"
+
+namespace mixattn {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4_t;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kPfWaves = 4;
+constexpr int kPfRows = 32 * kPfWaves;  // query rows per workgroup
+constexpr int kPfKeys = 64;             // keys per iteration (two 32-key blocks)
+
+__device__ inline uint32_t pf_bf16_bits_rn(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+struct TiledPrefillParams {
+  const uint16_t* q; void* out;
+  const uint16_t* Kt; const uint16_t* Vt;
+  const int64_t* d_base; const int32_t* d_slots;
+  int window, S, Hq, G;
+  float scale_log2;
+};
+
+// MFMA row m of a 32-key block holds key pi(m): bits 3 and 4 of m swapped, so that the 8 scores a lane owns per
+// 16-key slab are exactly the 8 keys of one 16-byte V fragment.
+__device__ inline int pf_key_of_row(int m) { return (m & 7) | ((m & 8) << 1) | ((m & 16) >> 1); }
+
+template <typename OutT>
+__global__ __launch_bounds__(kPfWaves * 64) void prefill_tiled_kernel(TiledPrefillParams a) {
+  __shared__ __attribute__((aligned(16))) uint16_t sK[2 * kBlockElems];
+  __shared__ __attribute__((aligned(16))) uint16_t sV[2 * kBlockElems];
+
+  const int n_qt = (a.S + kPfRows - 1) / kPfRows;
+  const int qt = n_qt - 1 - blockIdx.x;  // longest rows first
+  const int hq = blockIdx.y, b = blockIdx.z;
+  const int h = hq / a.G;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int col = lane & 31, hh = lane >> 5;
+  const int q0 = qt * kPfRows;
+  const int r0 = q0 + wave * 32;  // first row of this wavefront
+  const int row = r0 + col;
+  const int S = a.S, W = a.window;
+
+  // Q^T fragments: lane (row, hh) holds dims kk*16 + hh*8 .. +7
+  bf16x8_t qf[8];
+  {
+    const uint16_t* qp = a.q + (((int64_t)b * S + row) * a.Hq + hq) * kTiledDim + hh * 8;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      u32x4_t raw = {0u, 0u, 0u, 0u};
+      if (row < S) raw = *(const u32x4_t*)(qp + kk * 16);
+      qf[kk] = __builtin_bit_cast(bf16x8_t, raw);
+    }
+  }
+
+  const int64_t nblk_alloc = a.d_slots[b] >> 5;
+  const int nblk_valid = (S + kBlockKeys - 1) / kBlockKeys;
+  const int64_t first_blk = a.d_base[b] + (int64_t)h * nblk_alloc;
+  const u32x4_t* Kg = (const u32x4_t*)(a.Kt + first_blk * kBlockElems);
+  const u32x4_t* Vg = (const u32x4_t*)(a.Vt + first_blk * kBlockElems);
+
+  const int last_row = min(q0 + kPfRows, S) - 1;
+  const int jt_hi = last_row / kPfKeys;
+  const int jt_lo = W > 0 ? max(0, q0 - W + 1) / kPfKeys : 0;
+
+  floatx16_t o[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
+  float m = -INFINITY, lsum = 0.f;
+
+  // global -> register prefetch of one 64-key tile: 2 blocks x 512 pieces of 16 B for K and for V
+  u32x4_t pk[4], pv[4];
+  auto fetch = [&](int jt) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int piece = tid + 256 * i;  // 0..1023 ; block = piece / 512
+      const int kb = jt * 2 + (piece >> 9);
+      u32x4_t kz = {0u, 0u, 0u, 0u}, vz = {0u, 0u, 0u, 0u};
+      if (kb < nblk_valid) {
+        kz = Kg[(int64_t)kb * 512 + (piece & 511)];
+        vz = Vg[(int64_t)kb * 512 + (piece & 511)];
+      }
+      pk[i] = kz;
+      pv[i] = vz;
+    }
+  };
+  auto stash = [&]() {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int piece = tid + 256 * i;
+      ((u32x4_t*)sK)[piece] = pk[i];
+      ((u32x4_t*)sV)[piece] = pv[i];
+    }
+  };
+
+  const int key_row = pf_key_of_row(col);  // key (within a block) this lane feeds as MFMA row `col`
+  fetch(jt_lo);
+  for (int jt = jt_lo; jt <= jt_hi; ++jt) {
+    __syncthreads();
+    stash();
+    __syncthreads();
+    if (jt < jt_hi) fetch(jt + 1);
+
+    const int k0 = jt * kPfKeys;
+    // whole tile masked for every row of this wavefront?
+    if (k0 > r0 + 31) continue;
+    if (W > 0 && k0 + kPfKeys - 1 < r0 - W + 1) continue;
+    const bool need_mask = (k0 + kPfKeys - 1 > r0) || (W > 0 && k0 < r0 + 31 - W + 1);
+
+    floatx16_t s[2];
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[sub][i] = 0.f;
+      const uint16_t* kb = sK + sub * kBlockElems + (key_row >> 4) * 2048 + (key_row & 15) * 8;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        const bf16x8_t kf = *(const bf16x8_t*)(kb + (2 * kk + hh) * 128);
+        s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[sub], 0, 0, 0);
+      }
+    }
+    // scale, mask, row maximum
+    float mx = -INFINITY;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        float v = s[sub][i] * a.scale_log2;
+        if (need_mask) {
+          // register i is MFMA row 8*(i/4) + 4*hh + i%4, which holds key pi(row)
+          const int key = k0 + sub * 32 + pf_key_of_row(8 * (i >> 2) + 4 * hh + (i & 3));
+          const bool ok = (key <= row) && (W == 0 || key > row - W);
+          v = ok ? v : -INFINITY;
+        }
+        s[sub][i] = v;
+        mx = fmaxf(mx, v);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m, mx);
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;  // row with nothing visible yet
+    const float alpha = __builtin_amdgcn_exp2f(m - m_use);
+    m = m_new;
+    float psum = 0.f;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        uint32_t hi[8], lo[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const float p = __builtin_amdgcn_exp2f(s[sub][8 * u + j] - m_use);
+          psum += p;
+          hi[j] = pf_bf16_bits_rn(p);
+          lo[j] = pf_bf16_bits_rn(p - __uint_as_float(hi[j] << 16));
+        }
+        const u32x4_t hw = {hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16)};
+        const u32x4_t lw = {lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16)};
+        const bf16x8_t ph = __builtin_bit_cast(bf16x8_t, hw), pl = __builtin_bit_cast(bf16x8_t, lw);
+        // V fragment of this slab: dims 32*db + col, keys of piece g = 2u + hh
+        const uint16_t* vb = sV + sub * kBlockElems + (col >> 4) * 512 + ((2 * u + hh) * 16 + (col & 15)) * 8;
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+          const bf16x8_t vf = *(const bf16x8_t*)(vb + db * 1024);
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, ph, o[db], 0, 0, 0);
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pl, o[db], 0, 0, 0);
+        }
+      }
+    }
+    lsum = lsum * alpha + psum;
+  }
+
+  lsum += __shfl_xor(lsum, 32);
+  if (row < S) {
+    const float inv = 1.f / lsum;
+    OutT* op = (OutT*)a.out + (((int64_t)b * S + row) * a.Hq + hq) * kTiledDim;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int d = 32 * db + 8 * q4 + 4 * hh;
+        const float v0 = o[db][4 * q4] * inv, v1 = o[db][4 * q4 + 1] * inv, v2 = o[db][4 * q4 + 2] * inv,
+                    v3 = o[db][4 * q4 + 3] * inv;
+        if constexpr (sizeof(OutT) == 4) {
+          *(floatx4_t*)((float*)op + d) = floatx4_t{v0, v1, v2, v3};
+        } else {
+          uint2 w;
+          w.x = pf_bf16_bits_rn(v0) | (pf_bf16_bits_rn(v1) << 16);
+          w.y = pf_bf16_bits_rn(v2) | (pf_bf16_bits_rn(v3) << 16);
+          *(uint2*)((uint16_t*)op + d) = w;
+        }
+      }
+  }
+}
+
+hipError_t launch_prefill_tiled(const PrefillLaunch& L, hipStream_t s) {
+  TiledPrefillParams p;
+  p.q = (const uint16_t*)L.q; p.out = L.out;
+  p.Kt = (const uint16_t*)L.Kt; p.Vt = (const uint16_t*)L.Vt;
+  p.d_base = L.d_base; p.d_slots = L.d_slots;
+  p.window = L.window; p.S = L.S; p.Hq = L.Hq; p.G = L.G;
+  p.scale_log2 = L.scale * kLog2e;
+  const dim3 grid((L.S + kPfRows - 1) / kPfRows, L.Hq, L.batch), block(kPfWaves * 64);
+  if (L.out_dtype == MIXATTN_F32)
+    hipLaunchKernelGGL(prefill_tiled_kernel<float>, grid, block, 0, s, p);
+  else
+    hipLaunchKernelGGL(prefill_tiled_kernel<uint16_t>, grid, block, 0, s, p);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Row-major path: one wavefront per (query row, query head), keys visited one by one from the caller's
+// prompt tensors.  Plain fp32 arithmetic; used for fp32 and for shapes outside the MFMA path.
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__device__ inline float pf_load(const T* p);
+template <>
+__device__ inline float pf_load<float>(const float* p) { return *p; }
+template <>
+__device__ inline float pf_load<uint16_t>(const uint16_t* p) { return __uint_as_float((uint32_t)*p << 16); }
+
+struct RowPrefillParams {
+  const void* q; const void* k; const void* v; void* out;
+  int window, S, Hq, Hkv, G, D;
+  float scale;
+};
+
+template <typename T, typename OutT>
+__global__ __launch_bounds__(256) void prefill_rowmajor_kernel(RowPrefillParams a) {
+  const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int hq = blockIdx.y, b = blockIdx.z;
+  const int lane = threadIdx.x & 63;
+  if (i >= a.S) return;
+  const int h = hq / a.G, D = a.D;
+  const T* qp = (const T*)a.q + (((int64_t)b * a.S + i) * a.Hq + hq) * D;
+  float qv[4], acc[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int d = lane + 64 * t;
+    qv[t] = d < D ? pf_load<T>(qp + d) : 0.f;
+    acc[t] = 0.f;
+  }
+  const int lo = a.window > 0 ? max(0, i - a.window + 1) : 0;
+  float m = -INFINITY, l = 0.f;
+  for (int p = lo; p <= i; ++p) {
+    const int64_t off = (((int64_t)b * a.S + p) * a.Hkv + h) * D;
+    float part = 0.f;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int d = lane + 64 * t;
+      if (d < D) part += qv[t] * pf_load<T>((const T*)a.k + off + d);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o);
+    const float sc = part * a.scale;
+    const float m_new = fmaxf(m, sc);
+    const float alpha = expf(m - m_new);
+    const float pr = expf(sc - m_new);
+    l = l * alpha + pr;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int d = lane + 64 * t;
+      if (d < D) acc[t] = acc[t] * alpha + pr * pf_load<T>((const T*)a.v + off + d);
+    }
+    m = m_new;
+  }
+  OutT* op = (OutT*)a.out + (((int64_t)b * a.S + i) * a.Hq + hq) * D;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int d = lane + 64 * t;
+    if (d < D) {
+      const float v = acc[t] / l;
+      if constexpr (sizeof(OutT) == 4) ((float*)op)[d] = v;
+      else ((uint16_t*)op)[d] = (uint16_t)pf_bf16_bits_rn(v);
+    }
+  }
+}
+
+hipError_t launch_prefill_rowmajor(const PrefillLaunch& L, hipStream_t s) {
+  RowPrefillParams p;
+  p.q = L.q; p.k = L.k_src; p.v = L.v_src; p.out = L.out;
+  p.window = L.window; p.S = L.S; p.Hq = L.Hq; p.Hkv = L.Hkv; p.G = L.G; p.D = L.D; p.scale = L.scale;
+  const dim3 grid((L.S + 3) / 4, L.Hq, L.batch), block(256);
+  const bool f32 = L.kv_dtype == MIXATTN_F32, of32 = L.out_dtype == MIXATTN_F32;
+  if (f32 && of32) hipLaunchKernelGGL((prefill_rowmajor_kernel<float, float>), grid, block, 0, s, p);
+  else if (f32) hipLaunchKernelGGL((prefill_rowmajor_kernel<float, uint16_t>), grid, block, 0, s, p);
+  else if (of32) hipLaunchKernelGGL((prefill_rowmajor_kernel<uint16_t, float>), grid, block, 0, s, p);
+  else hipLaunchKernelGGL((prefill_rowmajor_kernel<uint16_t, uint16_t>), grid, block, 0, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace mixattn

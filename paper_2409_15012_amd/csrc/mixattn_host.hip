@@ -1,0 +1,533 @@
+// Host side of libmixattn: descriptor validation, cache/writer resolution, length bookkeeping, launch planning.
+// Public interface and argument contracts: include/mixattn.h.
+#include <math.h>
+#include <string.h>
+
+#include <algorithm>
+#include <map>
+#include <new>
+
+#include "mixattn_internal.h"
+
+using namespace mixattn;
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+inline bool hip_ok(hipError_t e) {
+  if (e == hipSuccess) return true;
+  g_last_hip = (int)e;
+  return false;
+}
+#define HIP_TRY(expr)                          \
+  do {                                         \
+    if (!hip_ok(expr)) return MIXATTN_ERR_HIP; \
+  } while (0)
+
+inline int elem_bytes(int dt) { return dt == MIXATTN_F32 ? 4 : 2; }
+
+inline bool use_tiled(int kv_dtype, int D, int G) { return kv_dtype == MIXATTN_BF16 && D == kTiledDim && G <= kMaxGroup; }
+
+int dev_alloc(void** p, size_t bytes) {
+  *p = nullptr;
+  if (bytes == 0) bytes = 16;
+  hipError_t e = hipMalloc(p, bytes);
+  if (e == hipErrorOutOfMemory) {
+    g_last_hip = (int)e;
+    (void)hipGetLastError();
+    return MIXATTN_ERR_ALLOC;
+  }
+  if (!hip_ok(e)) return MIXATTN_ERR_HIP;
+  return MIXATTN_OK;
+}
+
+int upload(void* dst, const void* src, size_t bytes) {
+  HIP_TRY(hipMemcpy(dst, src, bytes, hipMemcpyHostToDevice));
+  return MIXATTN_OK;
+}
+
+void free_layout(mixattn_layout* L) {
+  if (!L) return;
+  for (auto& c : L->caches) {
+    if (c.K) (void)hipFree(c.K);
+    if (c.V) (void)hipFree(c.V);
+    if (c.d_base) (void)hipFree(c.d_base);
+    if (c.d_slots) (void)hipFree(c.d_slots);
+  }
+  void* ptrs[] = {L->d_lens_all, L->scratch.acc, L->scratch.ml, L->scratch.counters, L->stageK, L->stageV,
+                  L->d_stage_lens, L->d_stage_src, L->d_readback, L->d_stage_base, L->d_stage_slots};
+  for (void* p : ptrs)
+    if (p) (void)hipFree(p);
+  delete L;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* mixattn_version(void) { return "mixattn 0.1 (gfx950)"; }
+int mixattn_last_hip_error(void) { return g_last_hip; }
+
+const char* mixattn_strerror(int st) {
+  switch (st) {
+    case MIXATTN_OK: return "ok";
+    case MIXATTN_ERR_NULL: return "required pointer is NULL";
+    case MIXATTN_ERR_LAYOUT: return "invalid layout descriptor";
+    case MIXATTN_ERR_LAYER: return "index out of range";
+    case MIXATTN_ERR_NOT_WRITER: return "layer reads a shared cache and cannot write it";
+    case MIXATTN_ERR_CAPACITY: return "full cache capacity exceeded";
+    case MIXATTN_ERR_ORDER: return "call not valid in the current cache state";
+    case MIXATTN_ERR_ALLOC: return "allocation failed";
+    case MIXATTN_ERR_HIP: return "HIP runtime error";
+    case MIXATTN_ERR_PARAM: return "bad tuning parameter";
+    default: return "unknown status";
+  }
+}
+
+int mixattn_slot_for(int kind, int window, int64_t pos, int64_t* slot) {
+  if (!slot) return MIXATTN_ERR_NULL;
+  if (pos < 0) return MIXATTN_ERR_LAYER;
+  if (kind == MIXATTN_FULL) {
+    *slot = pos;
+    return MIXATTN_OK;
+  }
+  if (kind != MIXATTN_SLIDING || window < 1) return MIXATTN_ERR_LAYOUT;
+  *slot = pos % window;
+  return MIXATTN_OK;
+}
+
+int mixattn_validate_config(const mixattn_config* cfg) {
+  if (!cfg || !cfg->layers) return MIXATTN_ERR_NULL;
+  if (cfg->n_layers < 1 || cfg->batch < 1 || cfg->n_q_heads < 1 || cfg->n_kv_heads < 1) return MIXATTN_ERR_LAYOUT;
+  if (cfg->n_q_heads % cfg->n_kv_heads != 0) return MIXATTN_ERR_LAYOUT;
+  if (cfg->kv_dtype != MIXATTN_F32 && cfg->kv_dtype != MIXATTN_BF16) return MIXATTN_ERR_LAYOUT;
+  if (cfg->out_dtype != MIXATTN_F32 && cfg->out_dtype != MIXATTN_BF16) return MIXATTN_ERR_LAYOUT;
+  if (cfg->head_dim < 1 || cfg->head_dim > kMaxHeadDim) return MIXATTN_ERR_LAYOUT;
+  if (cfg->kv_dtype == MIXATTN_BF16 && (cfg->head_dim % 8) != 0) return MIXATTN_ERR_LAYOUT;
+  if (!(cfg->softmax_scale >= 0.f) || isinf(cfg->softmax_scale)) return MIXATTN_ERR_LAYOUT;
+  bool any_full = false;
+  std::map<int, std::pair<int, int>> seen;  // cache id -> (kind, window)
+  for (int i = 0; i < cfg->n_layers; ++i) {
+    const mixattn_layer_desc& d = cfg->layers[i];
+    if (d.kind != MIXATTN_FULL && d.kind != MIXATTN_SLIDING) return MIXATTN_ERR_LAYOUT;
+    if (d.cache_id < 0) return MIXATTN_ERR_LAYOUT;
+    if (d.kind == MIXATTN_SLIDING && d.window < 1) return MIXATTN_ERR_LAYOUT;
+    const int w = d.kind == MIXATTN_SLIDING ? d.window : 0;
+    auto it = seen.find(d.cache_id);
+    if (it == seen.end()) seen[d.cache_id] = {d.kind, w};
+    else if (it->second != std::make_pair((int)d.kind, w)) return MIXATTN_ERR_LAYOUT;
+    any_full |= d.kind == MIXATTN_FULL;
+  }
+  if (any_full) {
+    if (!cfg->capacity) return MIXATTN_ERR_NULL;
+    for (int b = 0; b < cfg->batch; ++b)
+      if (cfg->capacity[b] < 1) return MIXATTN_ERR_LAYOUT;
+  }
+  return MIXATTN_OK;
+}
+
+int mixattn_create_layout(const mixattn_config* cfg, mixattn_layout** out) {
+  if (!out) return MIXATTN_ERR_NULL;
+  int st = mixattn_validate_config(cfg);
+  if (st != MIXATTN_OK) return st;
+  mixattn_layout* L = new (std::nothrow) mixattn_layout();
+  if (!L) return MIXATTN_ERR_ALLOC;
+  if (!hip_ok(hipGetDevice(&L->device))) {
+    delete L;
+    return MIXATTN_ERR_HIP;
+  }
+  L->n_layers = cfg->n_layers;
+  L->batch = cfg->batch;
+  L->Hq = cfg->n_q_heads;
+  L->Hkv = cfg->n_kv_heads;
+  L->G = L->Hq / L->Hkv;
+  L->D = cfg->head_dim;
+  L->kv_dtype = cfg->kv_dtype;
+  L->out_dtype = cfg->out_dtype;
+  L->elem = elem_bytes(cfg->kv_dtype);
+  L->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)cfg->head_dim);
+  L->tiled = use_tiled(L->kv_dtype, L->D, L->G);
+  L->fused_combine = 1;
+  L->layers.assign(cfg->layers, cfg->layers + cfg->n_layers);
+  if (cfg->capacity) L->capacity.assign(cfg->capacity, cfg->capacity + cfg->batch);
+
+  // caches in order of first use; the first user is the writer (Section 3, "KV cache reuse")
+  std::map<int, int> id2cache;
+  L->layer_cache.resize(L->n_layers);
+  for (int i = 0; i < L->n_layers; ++i) {
+    const auto& d = L->layers[i];
+    auto it = id2cache.find(d.cache_id);
+    if (it == id2cache.end()) {
+      Cache c;
+      c.kind = d.kind;
+      c.window = d.kind == MIXATTN_SLIDING ? d.window : 0;
+      c.writer = i;
+      id2cache[d.cache_id] = (int)L->caches.size();
+      L->layer_cache[i] = (int)L->caches.size();
+      L->caches.push_back(c);
+    } else {
+      L->layer_cache[i] = it->second;
+    }
+  }
+  const int B = L->batch;
+  const int nc = (int)L->caches.size();
+  st = dev_alloc((void**)&L->d_lens_all, sizeof(int32_t) * (size_t)nc * B);
+  if (st == MIXATTN_OK && !hip_ok(hipMemset(L->d_lens_all, 0, sizeof(int32_t) * (size_t)nc * B))) st = MIXATTN_ERR_HIP;
+  for (int ci = 0; ci < nc && st == MIXATTN_OK; ++ci) {
+    Cache& c = L->caches[ci];
+    c.base.resize(B);
+    c.slots.resize(B);
+    c.len.assign(B, 0);
+    c.d_lens = L->d_lens_all + (size_t)ci * B;
+    int64_t run = 0;  // blocks (tiled) or rows (row-major) before sequence b
+    for (int b = 0; b < B; ++b) {
+      const int64_t want = c.kind == MIXATTN_SLIDING ? c.window : L->capacity[b];
+      const int64_t slots = L->tiled ? (want + kBlockKeys - 1) / kBlockKeys * kBlockKeys : want;
+      if (slots > INT32_MAX) st = MIXATTN_ERR_LAYOUT;
+      c.slots[b] = (int32_t)slots;
+      c.base[b] = run;
+      run += (int64_t)L->Hkv * (L->tiled ? slots / kBlockKeys : slots);
+    }
+    if (st != MIXATTN_OK) break;
+    c.total_elems = L->tiled ? run * kBlockElems : run * L->D;
+    const size_t bytes = (size_t)c.total_elems * L->elem;
+    if ((st = dev_alloc(&c.K, bytes)) != MIXATTN_OK) break;
+    if ((st = dev_alloc(&c.V, bytes)) != MIXATTN_OK) break;
+    if (!hip_ok(hipMemset(c.K, 0, bytes)) || !hip_ok(hipMemset(c.V, 0, bytes))) {
+      st = MIXATTN_ERR_HIP;
+      break;
+    }
+    if ((st = dev_alloc((void**)&c.d_base, sizeof(int64_t) * B)) != MIXATTN_OK) break;
+    if ((st = dev_alloc((void**)&c.d_slots, sizeof(int32_t) * B)) != MIXATTN_OK) break;
+    if ((st = upload(c.d_base, c.base.data(), sizeof(int64_t) * B)) != MIXATTN_OK) break;
+    if ((st = upload(c.d_slots, c.slots.data(), sizeof(int32_t) * B)) != MIXATTN_OK) break;
+  }
+  if (st == MIXATTN_OK && L->tiled) {
+    const size_t rows = (size_t)B * L->Hq * kMaxChunks;
+    st = dev_alloc((void**)&L->scratch.acc, rows * L->D * sizeof(float));
+    if (st == MIXATTN_OK) st = dev_alloc((void**)&L->scratch.ml, rows * 2 * sizeof(float));
+    if (st == MIXATTN_OK) st = dev_alloc((void**)&L->scratch.counters, sizeof(uint32_t) * (size_t)B * L->Hkv);
+    if (st == MIXATTN_OK && !hip_ok(hipMemset(L->scratch.counters, 0, sizeof(uint32_t) * (size_t)B * L->Hkv)))
+      st = MIXATTN_ERR_HIP;
+  }
+  if (st == MIXATTN_OK) st = dev_alloc((void**)&L->d_stage_lens, sizeof(int32_t) * B);
+  if (st == MIXATTN_OK) st = dev_alloc((void**)&L->d_stage_src, sizeof(int64_t) * B);
+  if (st == MIXATTN_OK) st = dev_alloc((void**)&L->d_stage_base, sizeof(int64_t) * B);
+  if (st == MIXATTN_OK) st = dev_alloc((void**)&L->d_stage_slots, sizeof(int32_t) * B);
+  if (st == MIXATTN_OK) st = dev_alloc(&L->d_readback, 2 * kMaxHeadDim * sizeof(float));
+  if (st == MIXATTN_OK && !hip_ok(hipDeviceSynchronize())) st = MIXATTN_ERR_HIP;
+  if (st != MIXATTN_OK) {
+    free_layout(L);
+    return st;
+  }
+  *out = L;
+  return MIXATTN_OK;
+}
+
+int mixattn_destroy_layout(mixattn_layout* L) {
+  if (!L) return MIXATTN_ERR_NULL;
+  (void)hipDeviceSynchronize();
+  free_layout(L);
+  return MIXATTN_OK;
+}
+
+int mixattn_reset(mixattn_layout* L, void* stream) {
+  if (!L) return MIXATTN_ERR_NULL;
+  HIP_TRY(launch_fill_i32(L->d_lens_all, 0, (int64_t)L->caches.size() * L->batch, (hipStream_t)stream));
+  for (auto& c : L->caches) std::fill(c.len.begin(), c.len.end(), 0);
+  return MIXATTN_OK;
+}
+
+int mixattn_append_kv(mixattn_layout* L, int layer, const void* k, const void* v, void* stream) {
+  if (!L || !k || !v) return MIXATTN_ERR_NULL;
+  if (layer < 0 || layer >= L->n_layers) return MIXATTN_ERR_LAYER;
+  Cache& c = L->caches[L->layer_cache[layer]];
+  if (c.writer != layer) return MIXATTN_ERR_NOT_WRITER;
+  if (c.kind == MIXATTN_FULL)
+    for (int b = 0; b < L->batch; ++b)
+      if (c.len[b] + 1 > L->capacity[b]) return MIXATTN_ERR_CAPACITY;
+  for (int b = 0; b < L->batch; ++b)
+    if (c.len[b] + 1 > INT32_MAX) return MIXATTN_ERR_CAPACITY;
+  AppendLaunch a;
+  a.K = c.K; a.V = c.V; a.d_base = c.d_base; a.d_slots = c.d_slots; a.d_lens = c.d_lens;
+  a.window = c.window; a.k = k; a.v = v;
+  a.batch = L->batch; a.Hkv = L->Hkv; a.D = L->D; a.elem = L->elem;
+  HIP_TRY(L->tiled ? launch_append_tiled(a, (hipStream_t)stream) : launch_append_rowmajor(a, (hipStream_t)stream));
+  for (int b = 0; b < L->batch; ++b) c.len[b] += 1;
+  return MIXATTN_OK;
+}
+
+int mixattn_decode(mixattn_layout* L, int layer, const void* q, void* out, void* stream) {
+  if (!L || !q || !out) return MIXATTN_ERR_NULL;
+  if (layer < 0 || layer >= L->n_layers) return MIXATTN_ERR_LAYER;
+  const Cache& c = L->caches[L->layer_cache[layer]];
+  int64_t max_n = 0;
+  for (int b = 0; b < L->batch; ++b) {
+    if (c.len[b] < 1) return MIXATTN_ERR_ORDER;
+    const int64_t n = c.window > 0 ? std::min<int64_t>(c.len[b], c.window) : c.len[b];
+    max_n = std::max(max_n, n);
+  }
+  DecodeLaunch a;
+  a.K = c.K; a.V = c.V; a.d_base = c.d_base; a.d_slots = c.d_slots; a.d_lens = c.d_lens;
+  a.window = c.window; a.q = q; a.out = out;
+  a.batch = L->batch; a.Hq = L->Hq; a.Hkv = L->Hkv; a.G = L->G; a.D = L->D;
+  a.kv_dtype = L->kv_dtype; a.out_dtype = L->out_dtype; a.scale = L->scale;
+  a.scratch = L->scratch;
+  a.fused_combine = (int)L->fused_combine;
+  if (!L->tiled) {
+    a.max_blocks = a.chunk_blocks = a.n_chunks = 0;
+    HIP_TRY(launch_decode_rowmajor(a, (hipStream_t)stream));
+    return MIXATTN_OK;
+  }
+  const int max_blocks = (int)((max_n + kBlockKeys - 1) / kBlockKeys);
+  int chunk_blocks;
+  if (L->chunk_keys > 0) {
+    chunk_blocks = (int)(L->chunk_keys / kBlockKeys);
+  } else {
+    // enough workgroups to fill 256 CUs several times over, but at least 8 blocks (two per wavefront) each
+    const int64_t pairs = (int64_t)L->batch * L->Hkv;
+    const int64_t want_chunks = std::max<int64_t>(1, (2048 + pairs - 1) / pairs);
+    chunk_blocks = (int)std::max<int64_t>(8, (max_blocks + want_chunks - 1) / want_chunks);
+    chunk_blocks = (chunk_blocks + 3) / 4 * 4;
+  }
+  if ((max_blocks + chunk_blocks - 1) / chunk_blocks > kMaxChunks) {
+    chunk_blocks = (max_blocks + kMaxChunks - 1) / kMaxChunks;
+    chunk_blocks = (chunk_blocks + 3) / 4 * 4;
+  }
+  a.max_blocks = max_blocks;
+  a.chunk_blocks = chunk_blocks;
+  a.n_chunks = (max_blocks + chunk_blocks - 1) / chunk_blocks;
+  HIP_TRY(launch_decode_tiled(a, (hipStream_t)stream));
+  return MIXATTN_OK;
+}
+
+static int ensure_stage(mixattn_layout* L, int64_t blocks_per_head) {
+  if (L->stage_blocks >= blocks_per_head) return MIXATTN_OK;
+  // the old staging area may still be in use by work in flight
+  HIP_TRY(hipDeviceSynchronize());
+  if (L->stageK) (void)hipFree(L->stageK);
+  if (L->stageV) (void)hipFree(L->stageV);
+  L->stageK = L->stageV = nullptr;
+  L->stage_blocks = 0;
+  const size_t bytes = (size_t)L->batch * L->Hkv * blocks_per_head * kBlockElems * 2;
+  int st = dev_alloc(&L->stageK, bytes);
+  if (st != MIXATTN_OK) return st;
+  st = dev_alloc(&L->stageV, bytes);
+  if (st != MIXATTN_OK) return st;
+  std::vector<int64_t> base(L->batch);
+  std::vector<int32_t> slots(L->batch, (int32_t)(blocks_per_head * kBlockKeys));
+  for (int b = 0; b < L->batch; ++b) base[b] = (int64_t)b * L->Hkv * blocks_per_head;
+  if ((st = upload(L->d_stage_base, base.data(), sizeof(int64_t) * L->batch)) != MIXATTN_OK) return st;
+  if ((st = upload(L->d_stage_slots, slots.data(), sizeof(int32_t) * L->batch)) != MIXATTN_OK) return st;
+  L->stage_blocks = blocks_per_head;
+  return MIXATTN_OK;
+}
+
+int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, const void* v, void* out,
+                    int seq_len, void* stream) {
+  if (!L || !q || !out) return MIXATTN_ERR_NULL;
+  if (layer < 0 || layer >= L->n_layers) return MIXATTN_ERR_LAYER;
+  if (seq_len < 1) return MIXATTN_ERR_ORDER;
+  Cache& c = L->caches[L->layer_cache[layer]];
+  const bool writer = c.writer == layer;
+  const bool reads_cache = L->tiled && c.kind == MIXATTN_FULL;  // the kernel takes K/V from the cache itself
+  if ((writer || !reads_cache) && (!k || !v)) return MIXATTN_ERR_NULL;
+  for (int b = 0; b < L->batch; ++b) {
+    if (writer && c.len[b] != 0) return MIXATTN_ERR_ORDER;
+    if (!writer && c.len[b] != seq_len) return MIXATTN_ERR_ORDER;
+    if (c.kind == MIXATTN_FULL && seq_len > L->capacity[b]) return MIXATTN_ERR_CAPACITY;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  PrefillLaunch p;
+  p.q = q; p.out = out; p.k_src = k; p.v_src = v;
+  p.window = c.window; p.batch = L->batch; p.S = seq_len; p.Hq = L->Hq; p.Hkv = L->Hkv; p.G = L->G; p.D = L->D;
+  p.kv_dtype = L->kv_dtype; p.out_dtype = L->out_dtype; p.scale = L->scale;
+  p.Kt = p.Vt = nullptr; p.d_base = nullptr; p.d_slots = nullptr;
+
+  StoreLaunch st;
+  st.k_src = k; st.v_src = v; st.d_src_first = nullptr; st.d_src_len = nullptr; st.uniform_len = seq_len;
+  st.batch = L->batch; st.Hkv = L->Hkv; st.D = L->D; st.elem = L->elem;
+
+  if (L->tiled) {
+    const bool simple = L->prefill_simple != 0;  // scalar kernel on the caller's tensors (cross-check path)
+    if (simple && (!k || !v)) return MIXATTN_ERR_NULL;
+    if (c.kind == MIXATTN_FULL && writer) {
+      st.K = c.K; st.V = c.V; st.d_base = c.d_base; st.d_slots = c.d_slots; st.window = 0;
+      st.d_lens_out = c.d_lens; st.max_slots = seq_len;
+      HIP_TRY(launch_store_tiled(st, s));
+    }
+    if (simple) {
+      HIP_TRY(launch_prefill_rowmajor(p, s));
+    } else {
+      if (c.kind == MIXATTN_FULL) {
+        p.Kt = c.K; p.Vt = c.V; p.d_base = c.d_base; p.d_slots = c.d_slots;
+      } else {
+        int e = ensure_stage(L, (seq_len + kBlockKeys - 1) / kBlockKeys);
+        if (e != MIXATTN_OK) return e;
+        st.K = L->stageK; st.V = L->stageV; st.d_base = L->d_stage_base; st.d_slots = L->d_stage_slots;
+        st.window = 0; st.d_lens_out = nullptr; st.max_slots = seq_len;
+        HIP_TRY(launch_store_tiled(st, s));
+        p.Kt = L->stageK; p.Vt = L->stageV; p.d_base = L->d_stage_base; p.d_slots = L->d_stage_slots;
+      }
+      HIP_TRY(launch_prefill_tiled(p, s));
+    }
+    if (writer && c.kind == MIXATTN_SLIDING) {
+      st.K = c.K; st.V = c.V; st.d_base = c.d_base; st.d_slots = c.d_slots; st.window = c.window;
+      st.d_lens_out = c.d_lens; st.max_slots = std::min(seq_len, c.window);
+      HIP_TRY(launch_store_tiled(st, s));
+    }
+  } else {
+    HIP_TRY(launch_prefill_rowmajor(p, s));
+    if (writer) {
+      st.K = c.K; st.V = c.V; st.d_base = c.d_base; st.d_slots = c.d_slots; st.window = c.window;
+      st.d_lens_out = c.d_lens; st.max_slots = c.window > 0 ? std::min(seq_len, c.window) : seq_len;
+      HIP_TRY(launch_store_rowmajor(st, s));
+    }
+  }
+  if (writer)
+    for (int b = 0; b < L->batch; ++b) c.len[b] = seq_len;
+  return MIXATTN_OK;
+}
+
+int mixattn_load_kv(mixattn_layout* L, int layer, const void* k, const void* v, const int32_t* seq_lens,
+                    void* stream) {
+  if (!L || !k || !v || !seq_lens) return MIXATTN_ERR_NULL;
+  if (layer < 0 || layer >= L->n_layers) return MIXATTN_ERR_LAYER;
+  Cache& c = L->caches[L->layer_cache[layer]];
+  if (c.writer != layer) return MIXATTN_ERR_NOT_WRITER;
+  std::vector<int64_t> first(L->batch);
+  int64_t run = 0;
+  int max_len = 0;
+  for (int b = 0; b < L->batch; ++b) {
+    if (c.len[b] != 0) return MIXATTN_ERR_ORDER;
+    if (seq_lens[b] < 0) return MIXATTN_ERR_ORDER;
+    if (c.kind == MIXATTN_FULL && seq_lens[b] > L->capacity[b]) return MIXATTN_ERR_CAPACITY;
+    first[b] = run;
+    run += seq_lens[b];
+    max_len = std::max(max_len, seq_lens[b]);
+  }
+  hipStream_t s = (hipStream_t)stream;
+  // the device copies of the per-sequence tables may still be read by an earlier load on this stream
+  HIP_TRY(hipStreamSynchronize(s));
+  int e = upload(L->d_stage_lens, seq_lens, sizeof(int32_t) * L->batch);
+  if (e != MIXATTN_OK) return e;
+  e = upload(L->d_stage_src, first.data(), sizeof(int64_t) * L->batch);
+  if (e != MIXATTN_OK) return e;
+  StoreLaunch st;
+  st.K = c.K; st.V = c.V; st.d_base = c.d_base; st.d_slots = c.d_slots; st.window = c.window;
+  st.k_src = k; st.v_src = v; st.d_src_first = L->d_stage_src; st.d_src_len = L->d_stage_lens; st.uniform_len = 0;
+  st.d_lens_out = c.d_lens;
+  st.batch = L->batch; st.Hkv = L->Hkv; st.D = L->D; st.elem = L->elem;
+  st.max_slots = std::max(1, c.window > 0 ? std::min(max_len, c.window) : max_len);
+  HIP_TRY(L->tiled ? launch_store_tiled(st, s) : launch_store_rowmajor(st, s));
+  for (int b = 0; b < L->batch; ++b) c.len[b] = seq_lens[b];
+  return MIXATTN_OK;
+}
+
+int mixattn_n_caches(const mixattn_layout* L) { return L ? (int)L->caches.size() : MIXATTN_ERR_NULL; }
+
+int mixattn_cache_of(const mixattn_layout* L, int layer, int* cache_index, int* is_writer) {
+  if (!L) return MIXATTN_ERR_NULL;
+  if (layer < 0 || layer >= L->n_layers) return MIXATTN_ERR_LAYER;
+  const int ci = L->layer_cache[layer];
+  if (cache_index) *cache_index = ci;
+  if (is_writer) *is_writer = L->caches[ci].writer == layer ? 1 : 0;
+  return MIXATTN_OK;
+}
+
+int mixattn_seq_len(const mixattn_layout* L, int cache_index, int b, int64_t* n) {
+  if (!L || !n) return MIXATTN_ERR_NULL;
+  if (cache_index < 0 || cache_index >= (int)L->caches.size() || b < 0 || b >= L->batch) return MIXATTN_ERR_LAYER;
+  *n = L->caches[cache_index].len[b];
+  return MIXATTN_OK;
+}
+
+int mixattn_slot_of(const mixattn_layout* L, int cache_index, int64_t pos, int64_t* slot) {
+  if (!L || !slot) return MIXATTN_ERR_NULL;
+  if (cache_index < 0 || cache_index >= (int)L->caches.size()) return MIXATTN_ERR_LAYER;
+  const Cache& c = L->caches[cache_index];
+  return mixattn_slot_for(c.kind, c.window, pos, slot);
+}
+
+int mixattn_read_cache(mixattn_layout* L, int cache_index, int b, int kv_head, int64_t slot, void* k_row,
+                       void* v_row) {
+  if (!L) return MIXATTN_ERR_NULL;
+  if (cache_index < 0 || cache_index >= (int)L->caches.size() || b < 0 || b >= L->batch || kv_head < 0 ||
+      kv_head >= L->Hkv)
+    return MIXATTN_ERR_LAYER;
+  const Cache& c = L->caches[cache_index];
+  const int64_t limit = c.kind == MIXATTN_SLIDING ? c.window : L->capacity[b];
+  if (slot < 0 || slot >= limit) return MIXATTN_ERR_LAYER;
+  HIP_TRY(hipDeviceSynchronize());
+  HIP_TRY(launch_gather_row(c.K, c.V, c.base[b], c.slots[b], kv_head, slot, L->D, L->elem, L->tiled, L->d_readback,
+                            nullptr));
+  HIP_TRY(hipDeviceSynchronize());
+  const size_t row = (size_t)L->D * L->elem;
+  if (k_row) HIP_TRY(hipMemcpy(k_row, L->d_readback, row, hipMemcpyDeviceToHost));
+  if (v_row) HIP_TRY(hipMemcpy(v_row, (const char*)L->d_readback + row, row, hipMemcpyDeviceToHost));
+  return MIXATTN_OK;
+}
+
+int mixattn_read_device_lens(mixattn_layout* L, int cache_index, int32_t* lens) {
+  if (!L || !lens) return MIXATTN_ERR_NULL;
+  if (cache_index < 0 || cache_index >= (int)L->caches.size()) return MIXATTN_ERR_LAYER;
+  HIP_TRY(hipDeviceSynchronize());
+  HIP_TRY(hipMemcpy(lens, L->caches[cache_index].d_lens, sizeof(int32_t) * L->batch, hipMemcpyDeviceToHost));
+  return MIXATTN_OK;
+}
+
+int64_t mixattn_kv_bytes_allocated(const mixattn_layout* L) {
+  if (!L) return MIXATTN_ERR_NULL;
+  int64_t t = 0;
+  for (const auto& c : L->caches) t += 2 * c.total_elems * L->elem;
+  return t;
+}
+
+int64_t mixattn_kv_bytes_live(const mixattn_layout* L) {
+  if (!L) return MIXATTN_ERR_NULL;
+  int64_t tok = 0;
+  for (const auto& c : L->caches)
+    for (int b = 0; b < L->batch; ++b) tok += c.window > 0 ? std::min<int64_t>(c.len[b], c.window) : c.len[b];
+  return tok * 2 * L->Hkv * L->D * L->elem;
+}
+
+int64_t mixattn_step_read_bytes(const mixattn_layout* L, int layer) {
+  if (!L) return MIXATTN_ERR_NULL;
+  if (layer < 0 || layer >= L->n_layers) return MIXATTN_ERR_LAYER;
+  const Cache& c = L->caches[L->layer_cache[layer]];
+  int64_t tok = 0;
+  for (int b = 0; b < L->batch; ++b) tok += c.window > 0 ? std::min<int64_t>(c.len[b], c.window) : c.len[b];
+  return tok * 2 * L->Hkv * L->D * L->elem;
+}
+
+int mixattn_set_param(mixattn_layout* L, int param, int64_t value) {
+  if (!L) return MIXATTN_ERR_NULL;
+  switch (param) {
+    case MIXATTN_PARAM_CHUNK_KEYS:
+      if (value < 0 || value % kBlockKeys != 0 || value > (int64_t)1 << 30) return MIXATTN_ERR_PARAM;
+      L->chunk_keys = value;
+      return MIXATTN_OK;
+    case MIXATTN_PARAM_FUSED_COMBINE:
+      if (value != 0 && value != 1) return MIXATTN_ERR_PARAM;
+      L->fused_combine = value;
+      return MIXATTN_OK;
+    case MIXATTN_PARAM_PREFILL_SIMPLE:
+      if (value != 0 && value != 1) return MIXATTN_ERR_PARAM;
+      L->prefill_simple = value;
+      return MIXATTN_OK;
+    default: return MIXATTN_ERR_PARAM;
+  }
+}
+
+int mixattn_get_param(const mixattn_layout* L, int param, int64_t* value) {
+  if (!L || !value) return MIXATTN_ERR_NULL;
+  switch (param) {
+    case MIXATTN_PARAM_CHUNK_KEYS: *value = L->chunk_keys; return MIXATTN_OK;
+    case MIXATTN_PARAM_FUSED_COMBINE: *value = L->fused_combine; return MIXATTN_OK;
+    case MIXATTN_PARAM_PREFILL_SIMPLE: *value = L->prefill_simple; return MIXATTN_OK;
+    default: return MIXATTN_ERR_PARAM;
+  }
+}
+
+}  // extern "C"

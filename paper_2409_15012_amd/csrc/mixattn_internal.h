@@ -1,0 +1,153 @@
+// Internal declarations shared by the host side and the kernel launchers of libmixattn.
+// Not installed; the public interface is include/mixattn.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "mixattn.h"
+
+namespace mixattn {
+
+// ---- tile geometry of the MFMA ("tiled") cache format: bf16, head_dim 128 ----------------------
+// A cache is a sequence of 32-key blocks per (sequence, kv head).  One block holds 32 keys x 128 dims of K
+// (8 KiB) in the K buffer and the same of V in the V buffer, each arranged so that lane l of a wavefront
+// reads its MFMA operand as one 16-byte load at (fragment * 64 + l) * 16 bytes:
+//   K block:  element (key, dim) at  (key/16)*2048 + (dim/8)*128 + (key%16)*8 + dim%8
+//             -> fragment (t = key/16, kk = dim/32), lane = ((dim/8)%4)*16 + key%16   [A operand of 16x16x32]
+//   V block:  element (key, dim) at  (dim/16)*512 + (((key%16)/4)*16 + dim%16)*8 + 4*(key/16) + key%4
+//             -> fragment nn = dim/16, lane = ((key%16)/4)*16 + dim%16, the 8 keys of a lane being exactly the
+//                keys whose scores that lane holds after the two 16-key QK products of the block.
+constexpr int kBlockKeys = 32;
+constexpr int kTiledDim = 128;
+constexpr int kBlockElems = kBlockKeys * kTiledDim;  // 4096 elements = 8 KiB of bf16
+constexpr int kMaxGroup = 8;                         // query heads per KV head on the MFMA decode path
+constexpr int kMaxChunks = 64;                       // split-K chunks per (sequence, kv head)
+constexpr int kMaxHeadDim = 256;
+
+__host__ __device__ inline int k_tile_offset(int key, int dim) {
+  return (key >> 4) * 2048 + (dim >> 3) * 128 + (key & 15) * 8 + (dim & 7);
+}
+__host__ __device__ inline int v_tile_offset(int key, int dim) {
+  return (dim >> 4) * 512 + ((((key & 15) >> 2) << 4) + (dim & 15)) * 8 + 4 * (key >> 4) + (key & 3);
+}
+
+struct Cache {
+  int kind = 0;
+  int window = 0;      // SLIDING only
+  int writer = -1;     // layer index
+  int64_t total_elems = 0;  // elements in each of K and V
+  void* K = nullptr;   // device
+  void* V = nullptr;   // device
+  // per-sequence geometry (host copies; device copies in d_base / d_slots)
+  std::vector<int64_t> base;   // tiled: first block index of (b, h=0); row-major: first row index of (b, h=0)
+  std::vector<int32_t> slots;  // slots per (b, h): capacity rounded up to 32 (tiled) / capacity (row-major)
+  int64_t* d_base = nullptr;
+  int32_t* d_slots = nullptr;
+  int32_t* d_lens = nullptr;   // device, [batch] (points into Layout::d_lens_all)
+  std::vector<int64_t> len;    // host mirror
+};
+
+struct DecodeScratch {
+  float* acc = nullptr;  // [batch][n_q_heads][kMaxChunks][head_dim]
+  float* ml = nullptr;   // [batch][n_q_heads][kMaxChunks][2]  (max in log2 units, sum)
+  uint32_t* counters = nullptr;  // [batch][n_kv_heads] arrival counters for the fused combine
+};
+
+}  // namespace mixattn
+
+struct mixattn_layout {
+  int n_layers = 0;
+  int batch = 0, Hq = 0, Hkv = 0, G = 0, D = 0;
+  int kv_dtype = 0, out_dtype = 0;
+  int elem = 0;  // bytes per cache element
+  float scale = 0.f;
+  bool tiled = false;  // MFMA tile format (bf16, D == 128, G <= 8) vs row-major
+  std::vector<mixattn_layer_desc> layers;
+  std::vector<int> layer_cache;  // layer -> cache index
+  std::vector<mixattn::Cache> caches;
+  std::vector<int32_t> capacity;  // [batch] for FULL caches
+  int32_t* d_lens_all = nullptr;  // [n_caches][batch]
+  mixattn::DecodeScratch scratch;
+  // prompt staging for sliding-window prefill on the tiled path (grown on demand)
+  void* stageK = nullptr;
+  void* stageV = nullptr;
+  int64_t stage_blocks = 0;  // blocks per (b, h) currently allocated
+  int64_t* d_stage_base = nullptr;   // [batch] geometry tables of the staging area
+  int32_t* d_stage_slots = nullptr;  // [batch]
+  int32_t* d_stage_lens = nullptr;  // [batch] device copy of seq_lens for load_kv / prefill commits
+  int64_t* d_stage_src = nullptr;   // [batch] device: first packed token of each sequence
+  void* d_readback = nullptr;       // 2 * kMaxHeadDim elements for mixattn_read_cache
+  // tuning
+  int64_t chunk_keys = 0;
+  int64_t fused_combine = 0;
+  int64_t prefill_simple = 0;
+  int device = 0;
+};
+
+namespace mixattn {
+
+// ---- launchers implemented in the kernel files; all return hipError_t from hipGetLastError() ----
+struct DecodeLaunch {
+  const void* K; const void* V;
+  const int64_t* d_base; const int32_t* d_slots; const int32_t* d_lens;
+  int window;          // 0 = full
+  const void* q; void* out;
+  int batch, Hq, Hkv, G, D;
+  int kv_dtype, out_dtype;
+  float scale;
+  int max_blocks;      // over the batch, ceil(min(n_b, window)/32) (tiled path)
+  int chunk_blocks;    // blocks per split-K chunk
+  int n_chunks;        // grid.x
+  int fused_combine;
+  DecodeScratch scratch;
+};
+hipError_t launch_decode_tiled(const DecodeLaunch& a, hipStream_t s);
+hipError_t launch_decode_rowmajor(const DecodeLaunch& a, hipStream_t s);
+
+struct StoreLaunch {  // bulk commit of prompt / packed k,v into a cache or the staging area
+  void* K; void* V;
+  const int64_t* d_base; const int32_t* d_slots;
+  int window;             // 0 = position p -> slot p; >0 = ring (keep last min(len, window), slot p mod window)
+  const void* k_src; const void* v_src;  // [tokens, Hkv, D]
+  const int64_t* d_src_first;  // [batch] first packed token index of each sequence, or nullptr => b * uniform_len
+  const int32_t* d_src_len;    // [batch] tokens of each sequence, or nullptr => uniform_len
+  int uniform_len;
+  int32_t* d_lens_out;         // device lengths to set (nullptr: leave)
+  int batch, Hkv, D, elem;
+  int max_slots;               // max over b of slots that can receive data (grid size)
+};
+hipError_t launch_store_tiled(const StoreLaunch& a, hipStream_t s);
+hipError_t launch_store_rowmajor(const StoreLaunch& a, hipStream_t s);
+
+struct AppendLaunch {
+  void* K; void* V;
+  const int64_t* d_base; const int32_t* d_slots; int32_t* d_lens;
+  int window;
+  const void* k; const void* v;
+  int batch, Hkv, D, elem;
+};
+hipError_t launch_append_tiled(const AppendLaunch& a, hipStream_t s);
+hipError_t launch_append_rowmajor(const AppendLaunch& a, hipStream_t s);
+
+hipError_t launch_fill_i32(int32_t* p, int32_t value, int64_t n, hipStream_t s);
+hipError_t launch_gather_row(const void* K, const void* V, int64_t base, int32_t slots, int kv_head, int64_t slot,
+                             int D, int elem, bool tiled, void* dst, hipStream_t s);
+
+struct PrefillLaunch {
+  const void* q; void* out;
+  // tiled path: K/V in tile format (the full cache itself or the staging area)
+  const void* Kt; const void* Vt; const int64_t* d_base; const int32_t* d_slots;
+  // row-major path: the caller's prompt tensors
+  const void* k_src; const void* v_src;
+  int window;  // 0 = full causal
+  int batch, S, Hq, Hkv, G, D;
+  int kv_dtype, out_dtype;
+  float scale;
+};
+hipError_t launch_prefill_tiled(const PrefillLaunch& a, hipStream_t s);
+hipError_t launch_prefill_rowmajor(const PrefillLaunch& a, hipStream_t s);
+
+}  // namespace mixattn

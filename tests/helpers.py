@@ -62,3 +62,28 @@ def config0_oracle():
             outs.append(st.decode(li, to_f64(q)))
         dec_out.append(outs)
     return pre_out, dec_out, st
+
+
+# ----------------------------------------------------------------- comparison helpers
+BF16_MAX_ABS = 2e-3   # bf16 inputs, fp32 accumulation and fp32 output
+BF16_REL_L2 = 1e-3
+F32_TOL = 1e-5
+
+
+def errors(out: torch.Tensor, ref: np.ndarray):
+    o = to_f64(out)
+    diff = o - ref
+    max_abs = float(np.abs(diff).max()) if diff.size else 0.0
+    denom = float(np.linalg.norm(ref.ravel()))
+    rel_l2 = float(np.linalg.norm(diff.ravel())) / denom if denom > 0 else 0.0
+    return max_abs, rel_l2
+
+
+def assert_matches(out: torch.Tensor, ref: np.ndarray, dtype: str, what: str = ""):
+    assert not torch.isnan(out).any(), "NaN in output " + what
+    max_abs, rel_l2 = errors(out, ref)
+    if dtype == "f32":
+        assert max_abs <= F32_TOL and rel_l2 <= F32_TOL, "%s: max_abs %.3g rel_l2 %.3g" % (what, max_abs, rel_l2)
+    else:
+        assert max_abs <= BF16_MAX_ABS and rel_l2 <= BF16_REL_L2, "%s: max_abs %.3g rel_l2 %.3g" % (what, max_abs, rel_l2)
+    return max_abs, rel_l2

@@ -1,0 +1,98 @@
+"""CPU-side checks of the C-ABI library: it loads, exports what include/mixattn.h declares,
+and its pure host logic (descriptor validation, slot arithmetic) behaves.  No compute calls."""
+
+import os
+import re
+
+import pytest
+
+from oracle import mixattn_oracle as mo
+from paper_2409_15012_amd import binding as mx
+from paper_2409_15012_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "mixattn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mixattn_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = mx.load()
+    names = _declared_functions()
+    assert len(names) >= 20
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(mx.EXPORTS) == names
+    assert b"gfx950" in lib.mixattn_version()
+    assert lib.mixattn_strerror(0) == b"ok"
+    assert lib.mixattn_strerror(-4).startswith(b"layer reads a shared cache")
+
+
+def test_validate_config_accepts_the_workloads():
+    for i in range(5):
+        w = wl.config(i)
+        assert mx.validate_config(w.layers, w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim,
+                                  [w.context + 64] * w.batch, w.dtype, "f32") == 0
+    for name in ("ma", "ma_offset", "ma_pairs", "sliding"):
+        cap = None if name == "sliding" else [100] * 2
+        assert mx.validate_config(wl.layout_variant(name), 2, 12, 3, 128, cap) == 0
+    assert mx.validate_config(wl.layout_full24(), 2, 12, 3, 128, [100] * 2) == 0
+
+
+@pytest.mark.parametrize("layers,kw,status", [
+    ([(0, 0, 0), (1, 64, 0)], {}, -2),                 # sliding layer reading a full cache
+    ([(1, 64, 0), (1, 32, 0)], {}, -2),                # sharers with different windows
+    ([(1, 0, 0)], {}, -2),                             # window < 1
+    ([(2, 0, 0)], {}, -2),                             # unknown kind
+    ([(0, 0, -1)], {}, -2),                            # negative cache id
+    ([(0, 0, 0)], {"n_q_heads": 6, "n_kv_heads": 4}, -2),
+    ([(0, 0, 0)], {"head_dim": 300}, -2),
+    ([(0, 0, 0)], {"head_dim": 100, "kv_dtype": "bf16"}, -2),
+    ([(0, 0, 0)], {"capacity": None}, -1),             # full layer needs capacities
+    ([(0, 0, 0)], {"capacity": [0, 5]}, -2),
+    ([(0, 0, 0)], {"batch": 0, "capacity": []}, -2),
+    ([], {}, -2),
+])
+def test_validate_config_rejects(layers, kw, status):
+    args = dict(batch=2, n_q_heads=4, n_kv_heads=2, head_dim=64, capacity=[10, 10], kv_dtype="f32", out_dtype="f32")
+    args.update(kw)
+    assert mx.validate_config(layers, **args) == status
+
+
+def test_non_consecutive_sharing_is_a_valid_layout():
+    layers = [(0, 0, 7), (1, 8, 3), (0, 0, 7), (1, 8, 3), (1, 8, 9)]
+    assert mx.validate_config(layers, 1, 2, 1, 64, [4], "f32", "f32") == 0
+
+
+def test_slot_arithmetic_matches_the_oracle():
+    for W in (1, 3, 64, 1024):
+        for p in list(range(0, 70)) + [1023, 1024, 1025, 32767, 2 ** 31 + 5, 2 ** 40 + 17]:
+            assert mx.slot_for(mx.SLIDING, W, p) == mo.ring_slot(mo.SLIDING, W, p) == p % W
+    for p in (0, 5, 2 ** 40):
+        assert mx.slot_for(mx.FULL, 0, p) == mo.ring_slot(mo.FULL, 0, p) == p
+    with pytest.raises(mx.MixAttnError):
+        mx.slot_for(mx.SLIDING, 0, 3)
+    with pytest.raises(mx.MixAttnError):
+        mx.slot_for(mx.FULL, 0, -1)
+
+
+def test_workload_layouts_have_the_stated_shape():
+    lay = wl.layout_mix24()
+    assert len(lay) == 24 and lay[0][0] == wl.FULL and lay[12][0] == wl.FULL
+    assert len({c for _, _, c in lay}) == 8
+    groups = {}
+    for li, (_, _, c) in enumerate(lay):
+        groups.setdefault(c, []).append(li)
+    assert sorted(groups.values()) == [[0], [1, 2, 3, 4], [5, 6, 7, 8], [9, 10, 11], [12], [13, 14, 15, 16],
+                                       [17, 18, 19, 20], [21, 22, 23]]
+    w = wl.config(4)
+    assert len(w.seq_lens) == 64 and min(w.seq_lens) >= 1024 and max(w.seq_lens) <= 65536
+    assert w.seq_lens == wl.config(4).seq_lens
+    # decode bytes of the 32K configuration: 2 x 4 GiB + 22 x 128 MiB
+    w2 = wl.config(2)
+    specs = [mo.LayerSpec(*t) for t in w2.layers]
+    assert mo.step_read_tokens(specs, w2.seq_lens) * mo.kv_bytes_per_token(8, 128, 2) == 11542724608
+    assert mo.resident_kv_tokens(specs, w2.seq_lens) * 4096 == int(8.75 * 2 ** 30)

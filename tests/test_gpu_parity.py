@@ -1,0 +1,298 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU fp64 oracle, element by element, on the
+same seeded inputs.  Tolerances: fp32 inputs 1e-5; bf16 inputs with fp32 accumulation and fp32 output
+max-abs 2e-3 and relative L2 1e-3; slots, lengths and cache bytes bit-exact."""
+
+import numpy as np
+import pytest
+import torch
+
+from helpers import (assert_matches, config0_inputs, errors, oracle_for, to_f64)
+from oracle import mixattn_oracle as mo
+from oracle.mixattn_oracle import LayerSpec, OracleStack
+from paper_2409_15012_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def mx():
+    from paper_2409_15012_amd import binding
+    binding.load()
+    return binding
+
+
+def _check_cache(lay, ora, layer, bs=None, heads=None):
+    """Every valid slot of the cache `layer` reads holds exactly the bytes of the position the oracle says."""
+    ci, _ = lay.cache_of(layer)
+    sp = ora.layers[layer]
+    for b in (bs if bs is not None else range(lay.batch)):
+        assert lay.seq_len(ci, b) == ora.seq_len(layer, b)
+        K, V = ora.history(layer, b)
+        for slot, pos in ora.cache_view(layer, b):
+            assert lay.slot_of(ci, pos) == slot == mo.ring_slot(sp.kind, sp.window, pos)
+            for h in (heads if heads is not None else range(lay.Hkv)):
+                k_row, v_row = lay.read_cache(ci, b, h, slot)
+                assert np.array_equal(k_row.double().numpy(), K[pos, h]), (layer, b, h, slot, pos)
+                assert np.array_equal(v_row.double().numpy(), V[pos, h]), (layer, b, h, slot, pos)
+    assert lay.device_lens(ci) == [ora.seq_len(layer, b) for b in range(lay.batch)]
+
+
+# --------------------------------------------------------------------------- configuration 0, whole
+def test_config0_tiny_fp32_whole(mx):
+    w, pre, steps = config0_inputs()
+    lay = mx.Layout(w.layers, w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim,
+                    capacity=[w.prefill_len + w.decode_steps] * w.batch, kv_dtype="f32", out_dtype="f32")
+    ora = oracle_for(w)
+    kv = {}
+    for li, (q, k, v) in enumerate(pre):
+        wr = lay.writer_of(li)
+        if k is not None:
+            kv[li] = (k.to(DEV), v.to(DEV))
+        out = lay.prefill(li, q.to(DEV), *kv[wr])
+        ref = ora.prefill(li, to_f64(q), None if k is None else to_f64(k), None if v is None else to_f64(v))
+        assert_matches(out, ref, "f32", "prefill layer %d" % li)
+    for li in range(len(w.layers)):
+        _check_cache(lay, ora, li)
+    for t, per_layer in enumerate(steps):
+        for li, (q, k, v) in enumerate(per_layer):
+            if k is not None:
+                lay.append_kv(li, k.to(DEV), v.to(DEV))
+                ora.append(li, to_f64(k), to_f64(v))
+            out = lay.decode(li, q.to(DEV))
+            assert_matches(out, ora.decode(li, to_f64(q)), "f32", "step %d layer %d" % (t, li))
+        if t in (0, 7, 15):
+            for li in range(len(w.layers)):
+                _check_cache(lay, ora, li)
+    # step 0 wrote position 256 into ring slot 0 over position 192
+    assert lay.slot_of(1, 256) == 0 and lay.seq_len(1, 0) == 272
+    lay.close()
+
+
+# --------------------------------------------------------------------------- bf16 decode, small shapes
+def _mixed_layers(W):
+    # full (cache 0), sliding (1), sliding sharing 1, full sharing 0, sliding own (2)
+    return [(0, 0, 0), (1, W, 1), (1, W, 1), (0, 0, 0), (1, W, 2)]
+
+
+@pytest.mark.parametrize("Hq,Hkv,W,lens,chunk,fused", [
+    (8, 2, 64, [1, 31, 32, 33, 100, 257, 1000], 0, 1),
+    (8, 2, 48, [5, 47, 48, 49, 96, 700], 32, 1),       # window not a multiple of the block, one block per chunk
+    (8, 2, 256, [300, 2100, 64], 64, 0),               # separate combine launch
+    (4, 4, 100, [129, 4000], 128, 1),                  # G = 1
+    (8, 1, 1024, [1500, 1023, 2048], 0, 1),            # G = 8
+    (6, 2, 33, [77, 3], 0, 1),                         # G = 3
+])
+def test_bf16_decode_against_oracle(mx, Hq, Hkv, W, lens, chunk, fused):
+    B, d = len(lens), 128
+    layers = _mixed_layers(W)
+    steps = 3
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[n + steps for n in lens], kv_dtype="bf16", out_dtype="f32")
+    lay.set_param(mx.PARAM_CHUNK_KEYS, chunk)
+    lay.set_param(mx.PARAM_FUSED_COMBINE, fused)
+    ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
+    seed = 5000 + Hq * 31 + W
+    for li in range(len(layers)):
+        if lay.writer_of(li) == li:
+            k = wl.randn(seed + li, (sum(lens), Hkv, d), torch.bfloat16, DEV)
+            v = wl.randn(seed + 50 + li, (sum(lens), Hkv, d), torch.bfloat16, DEV)
+            lay.load_kv(li, k, v, lens)
+            ora.load(li, to_f64(k), to_f64(v), lens)
+    worst = (0.0, 0.0)
+    for t in range(steps):
+        for li in range(len(layers)):
+            if lay.writer_of(li) == li:
+                k = wl.randn(seed + 100 + 10 * t + li, (B, Hkv, d), torch.bfloat16, DEV)
+                v = wl.randn(seed + 200 + 10 * t + li, (B, Hkv, d), torch.bfloat16, DEV)
+                lay.append_kv(li, k, v)
+                ora.append(li, to_f64(k), to_f64(v))
+            q = wl.randn(seed + 300 + 10 * t + li, (B, Hq, d), torch.bfloat16, DEV)
+            out = lay.decode(li, q)
+            e = assert_matches(out, ora.decode(li, to_f64(q)), "bf16", "step %d layer %d" % (t, li))
+            worst = (max(worst[0], e[0]), max(worst[1], e[1]))
+            # same launch again: bit-identical
+            assert torch.equal(out, lay.decode(li, q))
+    for li in (0, 1, 4):
+        _check_cache(lay, ora, li, heads=[0, Hkv - 1])
+    print("worst max_abs %.3g rel_l2 %.3g" % worst)
+    lay.close()
+
+
+def test_bf16_decode_bf16_output(mx):
+    # bf16 output: the fp32 result rounded once; bound = tolerance + half an ulp of the reference
+    B, Hq, Hkv, d, n = 2, 8, 2, 128, 333
+    layers = [(0, 0, 0), (1, 64, 1)]
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[n] * B, kv_dtype="bf16", out_dtype="bf16")
+    ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
+    for li in range(2):
+        k = wl.randn(70 + li, (B * n, Hkv, d), torch.bfloat16, DEV)
+        v = wl.randn(80 + li, (B * n, Hkv, d), torch.bfloat16, DEV)
+        lay.load_kv(li, k, v, [n] * B)
+        ora.load(li, to_f64(k), to_f64(v), [n] * B)
+        q = wl.randn(90 + li, (B, Hq, d), torch.bfloat16, DEV)
+        out = lay.decode(li, q)
+        assert out.dtype == torch.bfloat16
+        ref = ora.decode(li, to_f64(q))
+        assert np.all(np.abs(to_f64(out) - ref) <= 2e-3 + 2.0 ** -8 * np.abs(ref))
+    lay.close()
+
+
+# --------------------------------------------------------------------------- bf16 prefill, small shapes
+@pytest.mark.parametrize("S,W,Hq,Hkv,B", [
+    (1, 64, 8, 2, 1), (31, 48, 8, 2, 2), (100, 48, 8, 2, 2), (129, 64, 4, 4, 1), (300, 200, 8, 2, 2),
+    (700, 100, 8, 1, 1), (257, 1024, 6, 2, 1),
+])
+@pytest.mark.parametrize("simple", [0, 1])
+def test_bf16_prefill_then_decode_against_oracle(mx, S, W, Hq, Hkv, B, simple):
+    d = 128
+    layers = _mixed_layers(W)
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[S + 2] * B, kv_dtype="bf16", out_dtype="f32")
+    lay.set_param(mx.PARAM_PREFILL_SIMPLE, simple)
+    ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
+    seed = 9000 + S * 7 + W
+    kv = {}
+    for li in range(len(layers)):
+        wr = lay.writer_of(li)
+        if wr == li:
+            kv[li] = (wl.randn(seed + li, (B, S, Hkv, d), torch.bfloat16, DEV),
+                      wl.randn(seed + 50 + li, (B, S, Hkv, d), torch.bfloat16, DEV))
+        q = wl.randn(seed + 100 + li, (B, S, Hq, d), torch.bfloat16, DEV)
+        k, v = kv[wr]
+        out = lay.prefill(li, q, k, v)
+        ref = ora.prefill(li, to_f64(q), to_f64(k) if wr == li else None, to_f64(v) if wr == li else None)
+        assert_matches(out, ref, "bf16", "prefill layer %d" % li)
+    for li in (0, 1, 4):
+        _check_cache(lay, ora, li, heads=[0])
+    for t in range(2):
+        for li in range(len(layers)):
+            if lay.writer_of(li) == li:
+                k = wl.randn(seed + 200 + 10 * t + li, (B, Hkv, d), torch.bfloat16, DEV)
+                v = wl.randn(seed + 300 + 10 * t + li, (B, Hkv, d), torch.bfloat16, DEV)
+                lay.append_kv(li, k, v)
+                ora.append(li, to_f64(k), to_f64(v))
+            q = wl.randn(seed + 400 + 10 * t + li, (B, Hq, d), torch.bfloat16, DEV)
+            assert_matches(lay.decode(li, q), ora.decode(li, to_f64(q)), "bf16", "decode %d layer %d" % (t, li))
+    lay.close()
+
+
+def test_row_major_path_other_shapes(mx):
+    # shapes outside the MFMA path run the scalar kernels: bf16 with head_dim 64, fp32 with head_dim 80
+    for kvd, d, tol in (("bf16", 64, "bf16"), ("f32", 80, "f32")):
+        B, Hq, Hkv, S, W = 2, 6, 3, 70, 20
+        layers = _mixed_layers(W)
+        tdt = torch.bfloat16 if kvd == "bf16" else torch.float32
+        lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[S + 3] * B, kv_dtype=kvd, out_dtype="f32")
+        ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
+        kv = {}
+        for li in range(len(layers)):
+            wr = lay.writer_of(li)
+            if wr == li:
+                kv[li] = (wl.randn(11 + li, (B, S, Hkv, d), tdt, DEV), wl.randn(21 + li, (B, S, Hkv, d), tdt, DEV))
+            q = wl.randn(31 + li, (B, S, Hq, d), tdt, DEV)
+            k, v = kv[wr]
+            out = lay.prefill(li, q, k, v)
+            ref = ora.prefill(li, to_f64(q), to_f64(k) if wr == li else None, to_f64(v) if wr == li else None)
+            assert_matches(out, ref, tol, "prefill layer %d" % li)
+        for t in range(3):
+            for li in range(len(layers)):
+                if lay.writer_of(li) == li:
+                    k = wl.randn(41 + 10 * t + li, (B, Hkv, d), tdt, DEV)
+                    v = wl.randn(141 + 10 * t + li, (B, Hkv, d), tdt, DEV)
+                    lay.append_kv(li, k, v)
+                    ora.append(li, to_f64(k), to_f64(v))
+                q = wl.randn(241 + 10 * t + li, (B, Hq, d), tdt, DEV)
+                assert_matches(lay.decode(li, q), ora.decode(li, to_f64(q)), tol, "decode layer %d" % li)
+        for li in (0, 1, 4):
+            _check_cache(lay, ora, li)
+        lay.close()
+
+
+# --------------------------------------------------------------------------- invariants on the GPU path
+def test_gpu_invariants(mx):
+    B, Hq, Hkv, d, n = 2, 8, 2, 128, 500
+    # (i) window >= context reproduces full attention; (ii) shared cache == duplicated cache
+    layers = [(0, 0, 0), (1, 512, 1), (1, 512, 1), (1, 512, 2)]
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[n] * B, kv_dtype="bf16", out_dtype="f32")
+    k = wl.randn(1, (B * n, Hkv, d), torch.bfloat16, DEV)
+    v = wl.randn(2, (B * n, Hkv, d), torch.bfloat16, DEV)
+    for li in (0, 1, 3):
+        lay.load_kv(li, k, v, [n] * B)
+    q = wl.randn(3, (B, Hq, d), torch.bfloat16, DEV)
+    o_full, o_win, o_shared, o_dup = (lay.decode(li, q) for li in range(4))
+    assert torch.equal(o_win, o_shared) and torch.equal(o_win, o_dup)
+    assert float((o_full - o_win).abs().max()) <= 1e-5
+    with pytest.raises(mx.MixAttnError) as ei:
+        lay.append_kv(2, k[:B], v[:B])
+    assert ei.value.status == -4
+    lay.close()
+
+    # (iii) constant keys give the mean of V over the attended set
+    W = 96
+    layers = [(0, 0, 0), (1, W, 1)]
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[n] * B, kv_dtype="bf16", out_dtype="f32")
+    kc = wl.randn(4, (1, Hkv, d), torch.bfloat16, DEV).expand(B * n, Hkv, d).contiguous()
+    for li in (0, 1):
+        lay.load_kv(li, kc, v, [n] * B)
+    vv = v.view(B, n, Hkv, d).float()
+    mean_full = vv.mean(1).repeat_interleave(Hq // Hkv, dim=1)
+    mean_win = vv[:, n - W:].mean(1).repeat_interleave(Hq // Hkv, dim=1)
+    assert float((lay.decode(0, q) - mean_full).abs().max()) <= 2e-3
+    assert float((lay.decode(1, q) - mean_win).abs().max()) <= 2e-3
+    lay.close()
+
+    # (iv) the same window contents at two ring rotations give the same output
+    W = 64
+    lay = mx.Layout([(1, W, 0)], 1, Hq, Hkv, d, kv_dtype="bf16", out_dtype="f32")
+    kw = wl.randn(5, (W, Hkv, d), torch.bfloat16, DEV)
+    vw = wl.randn(6, (W, Hkv, d), torch.bfloat16, DEV)
+    q1 = wl.randn(7, (1, Hq, d), torch.bfloat16, DEV)
+    outs = []
+    for shift in (0, 17, 40):
+        lay.reset()
+        junk = wl.randn(8 + shift, (shift, Hkv, d), torch.bfloat16, DEV)
+        lay.load_kv(0, torch.cat([junk, kw]), torch.cat([junk, vw]), [shift + W])
+        outs.append(lay.decode(0, q1))
+    assert float((outs[0] - outs[1]).abs().max()) <= 2e-5 and float((outs[0] - outs[2]).abs().max()) <= 2e-5
+    lay.close()
+
+
+def test_split_count_does_not_change_the_result(mx):
+    B, Hq, Hkv, d, n = 1, 8, 2, 128, 4099
+    lay = mx.Layout([(0, 0, 0)], B, Hq, Hkv, d, capacity=[n], kv_dtype="bf16", out_dtype="f32")
+    k = wl.randn(21, (n, Hkv, d), torch.bfloat16, DEV)
+    v = wl.randn(22, (n, Hkv, d), torch.bfloat16, DEV)
+    lay.load_kv(0, k, v, [n])
+    q = wl.randn(23, (B, Hq, d), torch.bfloat16, DEV)
+    outs = []
+    for chunk in (1 << 20, 2048, 256, 64):
+        for fused in (0, 1):
+            lay.set_param(mx.PARAM_CHUNK_KEYS, chunk)
+            lay.set_param(mx.PARAM_FUSED_COMBINE, fused)
+            outs.append(lay.decode(0, q))
+    for o in outs[1:]:
+        assert float((o - outs[0]).abs().max()) <= 2e-5
+    lay.close()
+
+
+def test_error_paths_leave_state_untouched(mx):
+    B, Hq, Hkv, d = 1, 4, 2, 128
+    lay = mx.Layout([(0, 0, 0), (0, 0, 0)], B, Hq, Hkv, d, capacity=[2], kv_dtype="bf16", out_dtype="f32")
+    q = wl.randn(1, (B, Hq, d), torch.bfloat16, DEV)
+    k = wl.randn(2, (B, Hkv, d), torch.bfloat16, DEV)
+    with pytest.raises(mx.MixAttnError) as e:
+        lay.decode(0, q)
+    assert e.value.status == -6
+    lay.append_kv(0, k, k)
+    lay.append_kv(0, k, k)
+    with pytest.raises(mx.MixAttnError) as e:
+        lay.append_kv(0, k, k)
+    assert e.value.status == -5 and lay.seq_len(0, 0) == 2 and lay.device_lens(0) == [2]
+    with pytest.raises(mx.MixAttnError) as e:
+        lay.prefill(0, q.view(1, 1, Hq, d), k.view(1, 1, Hkv, d), k.view(1, 1, Hkv, d))
+    assert e.value.status == -6
+    with pytest.raises(mx.MixAttnError) as e:
+        lay.decode(5, q)
+    assert e.value.status == -3
+    lay.reset()
+    assert lay.seq_len(0, 0) == 0 and lay.device_lens(0) == [0]
+    lay.close()
