@@ -1,0 +1,344 @@
+#!/usr/bin/env python3
+"""Benchmark of the MixAttention decode / prefill attention path on one MI355X.
+
+Default workload ("decode32k"): the 24-layer MixAttention stack (layers 0 and 12 full, 22 sliding-window layers
+W = 1024 in six sharing groups), bf16, batch 32, 32768 tokens of context per sequence.  One step = the whole hot
+path for one generated token per sequence: 8 KV appends (writer layers) + 24 decode attentions, with every input
+already resident in HBM.  Prints ONE JSON line (see README for the fields).
+
+Other workloads (--workload): decode4k (batch 8, context 4096), prefill32k (batch 1, 32768-token prompt through
+the 24 layers), ragged64 (batch 64, context lengths uniform in [1024, 65536], MixAttention stack next to the
+all-full 24-layer stack).
+
+Everything on the timed path runs in libmixattn's kernels; torch provides device memory, the stream and events.
+The CPU oracle is used only for the `cpu_baseline` leg (and never feeds the GPU path).
+"""
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="decode32k", choices=["decode32k", "decode4k", "prefill32k", "ragged64"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--chunk-keys", type=int, default=0)
+    ap.add_argument("--fused-combine", type=int, default=-1)
+    ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
+    ap.add_argument("--only", default="", help="profiling aid: 'full' or 'sliding' runs only that layer kind per step")
+    ap.add_argument("--copy-calibration", type=int, default=0,
+                    help="profiling aid: also run N plain device copies of 1 GiB (known traffic for counter scaling)")
+    return ap.parse_args()
+
+
+def _traffic_from_profiles(kernel_tag):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE), stored as text under profiles/."""
+    path = os.path.join(ROOT, "profiles", "traffic_%s.txt" % kernel_tag)
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def build_decode_stack(mx, wl, torch, layers, batch, Hq, Hkv, d, seq_lens, extra, out_dtype, dev, seed):
+    """Creates a layout, fills every writer cache with seq_lens[b] seeded tokens, returns (layout, per-layer inputs)."""
+    lay = mx.Layout(layers, batch, Hq, Hkv, d, capacity=[n + extra for n in seq_lens], kv_dtype="bf16",
+                    out_dtype=out_dtype)
+    total = int(sum(seq_lens))
+    qs, ks, vs = [], [], []
+    for li in range(len(layers)):
+        qs.append(wl.randn(wl.layer_seed(seed, li, "q"), (batch, Hq, d), torch.bfloat16, dev))
+        ci, is_writer = lay.cache_of(li)
+        if is_writer:
+            kind, W, _ = layers[li]
+            if kind == wl.SLIDING:
+                # a ring keeps the last W tokens only, so W tokens per sequence fill it completely (decode cost
+                # depends on min(n, W), not on n); later appends wrap around as usual
+                lens = [min(n, W) for n in seq_lens]
+                k = wl.randn(wl.layer_seed(seed, li, "k", 1), (sum(lens), Hkv, d), torch.bfloat16, dev)
+                v = wl.randn(wl.layer_seed(seed, li, "v", 1), (sum(lens), Hkv, d), torch.bfloat16, dev)
+                lay.load_kv(li, k, v, lens)
+            else:
+                k = wl.randn(wl.layer_seed(seed, li, "k", 1), (total, Hkv, d), torch.bfloat16, dev)
+                v = wl.randn(wl.layer_seed(seed, li, "v", 1), (total, Hkv, d), torch.bfloat16, dev)
+                lay.load_kv(li, k, v, seq_lens)
+            del k, v
+            torch.cuda.empty_cache()
+            ks.append(wl.randn(wl.layer_seed(seed, li, "k"), (batch, Hkv, d), torch.bfloat16, dev))
+            vs.append(wl.randn(wl.layer_seed(seed, li, "v"), (batch, Hkv, d), torch.bfloat16, dev))
+        else:
+            ks.append(None)
+            vs.append(None)
+    torch.cuda.synchronize()
+    return lay, qs, ks, vs
+
+
+def run_decode(args, mx, wl, torch, w, layers=None, label=None):
+    dev = "cuda:0"
+    layers = layers or w.layers
+    B, Hq, Hkv, d = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim
+    total_steps = args.warmup + args.steps
+    # the first timed step decodes at exactly the workload's context length
+    seq_lens = [max(1, n - 1 - args.warmup) for n in w.seq_lens]
+    lay, qs, ks, vs = build_decode_stack(mx, wl, torch, layers, B, Hq, Hkv, d, seq_lens, total_steps + 1,
+                                         args.out_dtype, dev, w.seed)
+    if args.chunk_keys:
+        lay.set_param(mx.PARAM_CHUNK_KEYS, args.chunk_keys)
+    if args.fused_combine >= 0:
+        lay.set_param(mx.PARAM_FUSED_COMBINE, args.fused_combine)
+    out = torch.empty((B, Hq, d), dtype=lay.out_torch, device=dev)
+    full_layers = [li for li, t in enumerate(layers) if t[0] == wl.FULL]
+    kinds = {"": None, "full": wl.FULL, "sliding": wl.SLIDING}[args.only]
+
+    def step(events=None):
+        for li in range(len(layers)):
+            if ks[li] is not None:
+                lay.append_kv(li, ks[li], vs[li])
+            if kinds is not None and layers[li][0] != kinds:
+                continue
+            if events is not None and li in full_layers:
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                lay.decode(li, qs[li], out)
+                e1.record()
+                events.append((li, e0, e1))
+            else:
+                lay.decode(li, qs[li], out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # logical KV bytes of one step, taken at the mid-point length (n grows by one per step)
+    ctx_lens = [n + args.warmup + 1 + args.steps // 2 for n in seq_lens]
+    per_tok = 2 * Hkv * d * 2
+    kv_step = 0
+    kv_full_launch = 0
+    for li, (kind, W, _) in enumerate(layers):
+        tok = sum(n if kind == wl.FULL else min(n, W) for n in ctx_lens)
+        if kinds is None or kind == kinds:
+            kv_step += tok * per_tok
+        if kind == wl.FULL:
+            kv_full_launch = tok * per_tok
+    qo_bytes = B * Hq * d * (2 + (2 if args.out_dtype == "bf16" else 4))
+    full_ms = [e0.elapsed_time(e1) for (_, e0, e1) in events]
+    res = {
+        "ms_per_step": ms_per_step,
+        "tokens_per_s": B / (ms_per_step * 1e-3),
+        "kv_bytes_per_step": kv_step,
+        "logical_gbs": kv_step / (ms_per_step * 1e-3) / 1e9,
+        "kv_bytes_resident": lay.kv_bytes_live(),
+        "kv_bytes_allocated": lay.kv_bytes_allocated(),
+        "full_layer_ms": (sum(full_ms) / len(full_ms)) if full_ms else None,
+        "full_layer_bytes": kv_full_launch + qo_bytes,
+    }
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(args.copy_calibration):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+    lay.close()
+    del lay
+    torch.cuda.empty_cache()
+    return res
+
+
+def cpu_baseline_decode(wl, torch, w, budget_s=15.0):
+    """Times the fp64 oracle on a bounded sample of the decode workload and scales to tokens/s.
+
+    Sample: one sequence, one KV head (its G query heads), one full layer at the workload's context and one
+    sliding layer at its window, repeated until about `budget_s` seconds of CPU work were measured.
+    Whole step = batch * n_kv_heads such samples per layer, 2 full + 22 sliding layers (linear scaling).
+    """
+    import numpy as np
+    from oracle.mixattn_oracle import LayerSpec, OracleStack
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = 1
+    G, d = w.n_q_heads // w.n_kv_heads, w.head_dim
+    n = w.context
+    W = max(t[1] for t in w.layers)
+    layers = [LayerSpec(0, 0, 0), LayerSpec(1, W, 1)]
+    ora = OracleStack(layers, 1, G, 1, d)
+    k = wl.randn(w.seed + 1, (n, 1, d), torch.bfloat16).double().numpy()
+    v = wl.randn(w.seed + 2, (n, 1, d), torch.bfloat16).double().numpy()
+    ora.load(0, k, v, [n])
+    ora.load(1, k, v, [n])
+    q = wl.randn(w.seed + 3, (1, G, d), torch.bfloat16).double().numpy()
+    t_full = t_slide = 0.0
+    reps = 0
+    t_start = time.perf_counter()
+    while time.perf_counter() - t_start < budget_s:
+        a = time.perf_counter()
+        ora.decode(0, q)
+        b = time.perf_counter()
+        ora.decode(1, q)
+        c = time.perf_counter()
+        t_full += b - a
+        t_slide += c - b
+        reps += 1
+    t_full /= reps
+    t_slide /= reps
+    n_full = sum(1 for t in w.layers if t[0] == wl.FULL)
+    n_slide = len(w.layers) - n_full
+    step_s = w.batch * w.n_kv_heads * (n_full * t_full + n_slide * t_slide)
+    return {
+        "value": w.batch / step_s, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+        "sample": "1 sequence x 1 KV head (%d query heads): one full-layer decode at n=%d and one sliding-layer "
+                  "decode at W=%d, %d repetitions (%.1f s); scaled linearly to batch %d x %d KV heads x "
+                  "(%d full + %d sliding layers)" % (G, n, W, reps, time.perf_counter() - t_start, w.batch,
+                                                      w.n_kv_heads, n_full, n_slide),
+    }
+
+
+def run_prefill(args, mx, wl, torch, w):
+    dev = "cuda:0"
+    B, S, Hq, Hkv, d = w.batch, w.prefill_len, w.n_q_heads, w.n_kv_heads, w.head_dim
+    lay = mx.Layout(w.layers, B, Hq, Hkv, d, capacity=[S] * B, kv_dtype="bf16", out_dtype=args.out_dtype)
+    # one q per layer kind is enough to time (values do not change the cost); K/V per writer layer
+    q = wl.randn(wl.layer_seed(w.seed, 0, "q"), (B, S, Hq, d), torch.bfloat16, dev)
+    kv = {}
+    for li in w.writer_layers():
+        kv[li] = (wl.randn(wl.layer_seed(w.seed, li, "k"), (B, S, Hkv, d), torch.bfloat16, dev),
+                  wl.randn(wl.layer_seed(w.seed, li, "v"), (B, S, Hkv, d), torch.bfloat16, dev))
+    out = torch.empty((B, S, Hq, d), dtype=lay.out_torch, device=dev)
+    writer_of = [lay.writer_of(li) for li in range(len(w.layers))]
+
+    def step(events=None):
+        lay.reset()
+        for li in range(len(w.layers)):
+            k, v = kv[writer_of[li]]
+            if events is not None and li == 0:
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                lay.prefill(li, q, k, v, out)
+                e1.record()
+                events.append((e0, e1))
+            else:
+                lay.prefill(li, q, k, v, out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    pairs_full = S * (S + 1) // 2
+    flops = 0
+    for kind, W, _ in w.layers:
+        pairs = pairs_full if kind == wl.FULL or W >= S else (W * (W + 1) // 2 + (S - W) * W)
+        flops += 4 * d * pairs * Hq * B
+    full_ms = sum(e0.elapsed_time(e1) for e0, e1 in events) / len(events)
+    lay.close()
+    return {"ms_per_step": ms, "flops": flops, "tflops": flops / (ms * 1e-3) / 1e12,
+            "full_layer_ms": full_ms, "full_layer_flops": 4 * d * pairs_full * Hq * B}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); --gpus %d is not "
+              "supported. Run with --gpus 1." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2409_15012_amd import binding as mx
+    from paper_2409_15012_amd import workloads as wl
+    mx.load()
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (the library has no CPU path)", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    base = {"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "bf16", "data": "synthetic"}
+    if args.workload in ("decode32k", "decode4k"):
+        w = wl.config(2 if args.workload == "decode32k" else 1)
+        r = run_decode(args, mx, wl, torch, w)
+        line = dict(base)
+        line.update({
+            "metric": "decode tokens/s through the 24-layer MixAttention attention stack (decode-attn HBM GB/s "
+                      "alongside)",
+            "value": r["tokens_per_s"], "unit": "tokens/s", "ms_per_step": r["ms_per_step"],
+            "config": {"workload": w.name, "batch": w.batch, "context": w.context, "window": 1024,
+                       "layers": "24: 0,12 full; 22 sliding in groups {1-4,5-8,9-11},{13-16,17-20,21-23}",
+                       "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
+                       "out_dtype": args.out_dtype, "only": args.only or "all"},
+            "kv_bytes_read_per_step": r["kv_bytes_per_step"],
+            "kv_bytes_resident": r["kv_bytes_resident"],
+            "decode_attn_logical_GBps": r["logical_gbs"],
+            "decode_attn_pct_of_8TBps": 100.0 * r["logical_gbs"] / HBM_PEAK_GBS,
+        })
+        if r["full_layer_ms"]:
+            ach = r["full_layer_bytes"] / (r["full_layer_ms"] * 1e-3) / 1e9
+            line["roofline"] = {"kernel": "decode_tiled_kernel<bf16 out, full> (one full-attention layer; plus its combine launch when split)",
+                                "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                "frac": ach / HBM_PEAK_GBS, "launch_ms": r["full_layer_ms"],
+                                "bytes_per_launch": r["full_layer_bytes"],
+                                "traffic": _traffic_from_profiles("decode_full_%s" % w.name)}
+        if not args.no_cpu_baseline:
+            line["cpu_baseline"] = cpu_baseline_decode(wl, torch, w)
+    elif args.workload == "prefill32k":
+        w = wl.config(3)
+        r = run_prefill(args, mx, wl, torch, w)
+        line = dict(base)
+        ach = r["full_layer_flops"] / (r["full_layer_ms"] * 1e-3) / 1e12
+        line.update({
+            "metric": "prefill attention TFLOP/s (unmasked pairs only), 24-layer MixAttention stack",
+            "value": r["tflops"], "unit": "TFLOP/s", "ms_per_step": r["ms_per_step"],
+            "config": {"workload": w.name, "batch": 1, "seq_len": w.prefill_len, "window": 1024,
+                       "out_dtype": args.out_dtype},
+            "useful_flops_per_step": r["flops"],
+            "roofline": {"kernel": "prefill_tiled_kernel (full causal layer, incl. cache commit)", "bound": "mfma",
+                         "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": ach / MFMA_BF16_PEAK_TFLOPS, "launch_ms": r["full_layer_ms"], "traffic": None},
+        })
+    else:  # ragged64
+        w = wl.config(4)
+        r_mix = run_decode(args, mx, wl, torch, w)
+        r_full = run_decode(args, mx, wl, torch, w, layers=wl.layout_full24())
+        line = dict(base)
+        line.update({
+            "metric": "decode tokens/s, ragged batch 64, MixAttention stack (standard 24-layer stack alongside)",
+            "value": r_mix["tokens_per_s"], "unit": "tokens/s", "ms_per_step": r_mix["ms_per_step"],
+            "config": {"workload": w.name, "batch": w.batch, "context": "uniform[1024,65536] seeded",
+                       "sum_context": int(sum(w.seq_lens)), "window": 1024, "out_dtype": args.out_dtype},
+            "mix": r_mix, "standard": r_full,
+            "step_time_ratio_standard_over_mix": r_full["ms_per_step"] / r_mix["ms_per_step"],
+            "kv_bytes_ratio_standard_over_mix": r_full["kv_bytes_resident"] / r_mix["kv_bytes_resident"],
+        })
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

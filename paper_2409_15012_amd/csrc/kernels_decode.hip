@@ -11,6 +11,8 @@
 // about 16 significant bits at no extra MFMA cost (the columns would otherwise be padding).  Scores, softmax
 // state and accumulators are fp32.  The online-softmax state of a head lives in the lanes of its column, so
 // rescaling the accumulator is lane-local; the only cross-lane traffic per block is two shuffles for the maximum.
+#include <type_traits>
+
 #include "mixattn_internal.h"
 
 namespace mixattn {
@@ -63,18 +65,23 @@ __device__ inline void merge_partials(const float* p_acc, const float* p_ml, int
   store_out<OutT>(out + d, acc / L);
 }
 
-template <typename OutT>
+// RING selects the sliding-window instantiation (reads min(n, window) ring slots); it is a template parameter so
+// that the two layer kinds are separate kernels in a profile.
+template <typename OutT, bool RING>
 __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(TiledDecodeParams a) {
   const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   int n = a.d_lens[b];
-  if (a.window > 0 && n > a.window) n = a.window;
+  if (RING && n > a.window) n = a.window;
   const int nb_total = (n + kBlockKeys - 1) / kBlockKeys;
-  const int blk0 = c * a.chunk_blocks;
-  if (blk0 >= nb_total) return;  // uniform for the workgroup
-  const int blk1 = min(blk0 + a.chunk_blocks, nb_total);
+  // this sequence's blocks are cut into n_chunks_b chunks of equal length (+-1 block), so that workgroups of one
+  // sequence finish together and a sequence a little longer than a multiple of the target does not grow a stub
   const int n_chunks_b = (nb_total + a.chunk_blocks - 1) / a.chunk_blocks;
+  if (c >= n_chunks_b) return;  // uniform for the workgroup
+  const int blk0 = (int)(((int64_t)c * nb_total) / n_chunks_b);
+  const int blk1 = (int)(((int64_t)(c + 1) * nb_total) / n_chunks_b);
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the block loop on scalar branches
   const int col = lane & 15, g = lane >> 4;
   const int G = a.G;
   const bool is_hi = col < G, is_lo = (col >= G) && (col < 2 * G);
@@ -112,7 +119,10 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
     for (int i = 0; i < 8; ++i) vd[i] = __builtin_nontemporal_load(vp + i * 64);
   };
 
-  auto compute_block = [&](int blk, u32x4_t* kd, u32x4_t* vd) {
+  // One 32-key block: scores, online softmax, accumulate.  TAIL = this is the last block of the sequence and it
+  // is ragged: keys >= n are dropped and their V entries cleared (they may hold stale data).
+  auto compute_block = [&](auto tail_tag, int blk, u32x4_t* kd, u32x4_t* vd) {
+    constexpr bool TAIL = decltype(tail_tag)::value;
     floatx4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
@@ -125,17 +135,16 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
       sv[i] = s0[i] * a.scale_log2;      // key 4g + i of the block
       sv[4 + i] = s1[i] * a.scale_log2;  // key 16 + 4g + i
     }
-    if (blk == nb_total - 1 && (n & 31)) {  // ragged tail: drop keys >= n and clear their V entries
+    if constexpr (TAIL) {
       const int valid = n - blk * kBlockKeys;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const int key = 16 * (j >> 2) + 4 * g + (j & 3);
-        if (key >= valid) {
-          sv[j] = -INFINITY;
-          const uint32_t keep = (j & 1) ? 0x0000ffffu : 0xffff0000u;
+        const bool drop = key >= valid;
+        sv[j] = drop ? -INFINITY : sv[j];
+        const uint32_t keep = drop ? ((j & 1) ? 0x0000ffffu : 0xffff0000u) : 0xffffffffu;
 #pragma unroll
-          for (int nn = 0; nn < 8; ++nn) vd[nn][j >> 1] &= keep;
-        }
+        for (int nn = 0; nn < 8; ++nn) vd[nn][j >> 1] &= keep;
       }
     }
     float mx = sv[0];
@@ -168,19 +177,34 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
       o[nn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vd[nn]), pf, o[nn], 0, 0, 0);
     }
   };
+  using no_tail = std::integral_constant<bool, false>;
+  using with_tail = std::integral_constant<bool, true>;
+  auto compute_last = [&](int blk, u32x4_t* kd, u32x4_t* vd) {
+    if (blk == nb_total - 1 && (n & (kBlockKeys - 1))) compute_block(with_tail{}, blk, kd, vd);
+    else compute_block(no_tail{}, blk, kd, vd);
+  };
 
-  // software pipeline over this wave's blocks: blk0 + wave, + 4, ...
-  int blk = blk0 + wave;
-  if (blk < blk1) load_block(blk, kr[0], vr[0]);
-  while (blk < blk1) {
-    const int nxt = blk + kDecodeWaves;
-    if (nxt < blk1) load_block(nxt, kr[1], vr[1]);
-    compute_block(blk, kr[0], vr[0]);
-    if (nxt >= blk1) break;
-    const int nxt2 = nxt + kDecodeWaves;
-    if (nxt2 < blk1) load_block(nxt2, kr[0], vr[0]);
-    compute_block(nxt, kr[1], vr[1]);
-    blk = nxt2;
+  // Software pipeline over this wavefront's blocks blk0 + wave + 4*i, i < cnt.  The steady-state loop issues the
+  // next block's loads unconditionally before it consumes the current one, so the wait before the MFMAs only
+  // covers the older of the two blocks in flight; the last one or two blocks are peeled.
+  const int cnt = (blk1 - blk0 - wave + kDecodeWaves - 1) / kDecodeWaves;  // may be <= 0
+  if (cnt > 0) {
+    const int first = blk0 + wave;
+    load_block(first, kr[0], vr[0]);
+    int i = 0;
+    for (; i + 2 < cnt; i += 2) {
+      load_block(first + (i + 1) * kDecodeWaves, kr[1], vr[1]);
+      compute_block(no_tail{}, first + i * kDecodeWaves, kr[0], vr[0]);
+      load_block(first + (i + 2) * kDecodeWaves, kr[0], vr[0]);
+      compute_block(no_tail{}, first + (i + 1) * kDecodeWaves, kr[1], vr[1]);
+    }
+    if (i + 1 < cnt) {
+      load_block(first + (i + 1) * kDecodeWaves, kr[1], vr[1]);
+      compute_block(no_tail{}, first + i * kDecodeWaves, kr[0], vr[0]);
+      compute_last(first + (i + 1) * kDecodeWaves, kr[1], vr[1]);
+    } else {
+      compute_last(first + i * kDecodeWaves, kr[0], vr[0]);
+    }
   }
 
   // ---- wave epilogue: total sum over the 4 lane groups, remainder columns folded into their head's column
@@ -277,10 +301,11 @@ hipError_t launch_decode_tiled(const DecodeLaunch& L, hipStream_t s) {
   p.fused_combine = L.fused_combine;
   p.p_acc = L.scratch.acc; p.p_ml = L.scratch.ml; p.counters = L.scratch.counters;
   const dim3 grid(L.n_chunks, L.Hkv, L.batch), block(kDecodeWaves * 64);
-  if (L.out_dtype == MIXATTN_F32)
-    hipLaunchKernelGGL(decode_tiled_kernel<float>, grid, block, 0, s, p);
-  else
-    hipLaunchKernelGGL(decode_tiled_kernel<uint16_t>, grid, block, 0, s, p);
+  const bool f32 = L.out_dtype == MIXATTN_F32, ring = L.window > 0;
+  if (f32 && ring) hipLaunchKernelGGL((decode_tiled_kernel<float, true>), grid, block, 0, s, p);
+  else if (f32) hipLaunchKernelGGL((decode_tiled_kernel<float, false>), grid, block, 0, s, p);
+  else if (ring) hipLaunchKernelGGL((decode_tiled_kernel<uint16_t, true>), grid, block, 0, s, p);
+  else hipLaunchKernelGGL((decode_tiled_kernel<uint16_t, false>), grid, block, 0, s, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (L.n_chunks > 1 && !L.fused_combine) {

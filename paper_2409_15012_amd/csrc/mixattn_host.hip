@@ -148,7 +148,12 @@ int mixattn_create_layout(const mixattn_config* cfg, mixattn_layout** out) {
   L->elem = elem_bytes(cfg->kv_dtype);
   L->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)cfg->head_dim);
   L->tiled = use_tiled(L->kv_dtype, L->D, L->G);
-  L->fused_combine = 1;
+  {
+    int cus = 0;
+    if (!hip_ok(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, L->device)) || cus < 1) cus = 256;
+    L->n_cus = cus;
+  }
+  L->fused_combine = 0;  // device-scope fences write back and invalidate the XCD L2s: measured far slower than a separate launch
   L->layers.assign(cfg->layers, cfg->layers + cfg->n_layers);
   if (cfg->capacity) L->capacity.assign(cfg->capacity, cfg->capacity + cfg->batch);
 
@@ -258,6 +263,49 @@ int mixattn_append_kv(mixattn_layout* L, int layer, const void* k, const void* v
   return MIXATTN_OK;
 }
 
+// Split-K plan for the tiled decode kernel: the target chunk length in blocks.  A sequence of nb blocks is cut
+// into ceil(nb / target) equal chunks, one workgroup each.  Two effects bound a launch (figures measured on
+// MI355X with this kernel): the HBM stream, about 7.0 TB/s once a few hundred workgroups are resident, and the
+// rate of one workgroup, whose four wavefronts keep 128 KiB in flight and so advance by one 16 KiB block in
+// about 0.6 us under load.  Cutting sequences shortens the second bound but costs a combine launch (about 5 us);
+// with two workgroups resident per CU, chunks run in rounds of 2 * CUs.
+static int plan_chunk_blocks(const mixattn_layout* L, const Cache& c, int max_blocks) {
+  const double slots = 2.0 * L->n_cus;
+  const double us_per_block_bw = 2.0 * kBlockElems * 2 / 7.0e6;  // 16 KiB at 7.0 TB/s
+  const double us_per_block_wg = 0.6, us_wg_fixed = 1.0, us_combine = 5.0;
+  std::vector<int> nb(L->batch);
+  double total_blocks = 0;
+  for (int b = 0; b < L->batch; ++b) {
+    const int64_t n = c.window > 0 ? std::min<int64_t>(c.len[b], c.window) : c.len[b];
+    nb[b] = (int)((n + kBlockKeys - 1) / kBlockKeys);
+    total_blocks += (double)nb[b] * L->Hkv;
+  }
+  const double t_bw = total_blocks * us_per_block_bw;
+  int best_t = max_blocks;
+  double best_cost = 1e300;
+  for (int chunks = 1; chunks <= kMaxChunks; ++chunks) {
+    const int t = (max_blocks + chunks - 1) / chunks;
+    if (chunks > 1 && t < kDecodeMinChunkBlocks) break;
+    double wgs = 0;
+    int longest = 0;
+    for (int b = 0; b < L->batch; ++b) {
+      const int cb = (nb[b] + t - 1) / t;
+      wgs += (double)cb * L->Hkv;
+      longest = std::max(longest, (nb[b] + cb - 1) / cb);
+    }
+    const double t_long = longest * us_per_block_wg + us_wg_fixed;
+    // list-scheduling estimate of the per-workgroup bound over `slots` resident workgroups
+    const double t_sched = wgs <= slots ? t_long
+                                        : (total_blocks * us_per_block_wg + wgs * us_wg_fixed) / slots + 0.5 * t_long;
+    const double cost = std::max(t_bw, std::max(t_long, t_sched)) + (chunks > 1 ? us_combine : 0.0);
+    if (cost < best_cost - 1e-9) {
+      best_cost = cost;
+      best_t = t;
+    }
+  }
+  return std::max(best_t, 1);
+}
+
 int mixattn_decode(mixattn_layout* L, int layer, const void* q, void* out, void* stream) {
   if (!L || !q || !out) return MIXATTN_ERR_NULL;
   if (layer < 0 || layer >= L->n_layers) return MIXATTN_ERR_LAYER;
@@ -285,16 +333,9 @@ int mixattn_decode(mixattn_layout* L, int layer, const void* q, void* out, void*
   if (L->chunk_keys > 0) {
     chunk_blocks = (int)(L->chunk_keys / kBlockKeys);
   } else {
-    // enough workgroups to fill 256 CUs several times over, but at least 8 blocks (two per wavefront) each
-    const int64_t pairs = (int64_t)L->batch * L->Hkv;
-    const int64_t want_chunks = std::max<int64_t>(1, (2048 + pairs - 1) / pairs);
-    chunk_blocks = (int)std::max<int64_t>(8, (max_blocks + want_chunks - 1) / want_chunks);
-    chunk_blocks = (chunk_blocks + 3) / 4 * 4;
+    chunk_blocks = plan_chunk_blocks(L, c, max_blocks);
   }
-  if ((max_blocks + chunk_blocks - 1) / chunk_blocks > kMaxChunks) {
-    chunk_blocks = (max_blocks + kMaxChunks - 1) / kMaxChunks;
-    chunk_blocks = (chunk_blocks + 3) / 4 * 4;
-  }
+  chunk_blocks = std::max(chunk_blocks, (max_blocks + kMaxChunks - 1) / kMaxChunks);
   a.max_blocks = max_blocks;
   a.chunk_blocks = chunk_blocks;
   a.n_chunks = (max_blocks + chunk_blocks - 1) / chunk_blocks;

@@ -26,6 +26,7 @@ constexpr int kBlockElems = kBlockKeys * kTiledDim;  // 4096 elements = 8 KiB of
 constexpr int kMaxGroup = 8;                         // query heads per KV head on the MFMA decode path
 constexpr int kMaxChunks = 64;                       // split-K chunks per (sequence, kv head)
 constexpr int kMaxHeadDim = 256;
+constexpr int kDecodeMinChunkBlocks = 4;              // a split-K chunk keeps every wavefront of its workgroup busy
 
 __host__ __device__ inline int k_tile_offset(int key, int dim) {
   return (key >> 4) * 2048 + (dim >> 3) * 128 + (key & 15) * 8 + (dim & 7);
@@ -85,6 +86,7 @@ struct mixattn_layout {
   int64_t fused_combine = 0;
   int64_t prefill_simple = 0;
   int device = 0;
+  int n_cus = 256;
 };
 
 namespace mixattn {
