@@ -43,21 +43,32 @@ struct TiledPrefillParams {
 // 16-key slab are exactly the 8 keys of one 16-byte V fragment.
 __device__ inline int pf_key_of_row(int m) { return (m & 7) | ((m & 8) << 1) | ((m & 16) >> 1); }
 
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float floatx2_t;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+
+// two floats -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32)
+__device__ inline uint32_t pf_pack_bf16(float lo, float hi) {
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(floatx2_t{lo, hi}, bf16x2_t));
+}
+
 template <typename OutT>
-__global__ __launch_bounds__(kPfWaves * 64) void prefill_tiled_kernel(TiledPrefillParams a) {
-  __shared__ __attribute__((aligned(16))) uint16_t sK[2 * kBlockElems];
-  __shared__ __attribute__((aligned(16))) uint16_t sV[2 * kBlockElems];
+__global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_tiled_kernel(TiledPrefillParams a) {
+  // two stages of one 64-key tile each (2 blocks of K, 2 blocks of V), filled by direct global->LDS loads
+  __shared__ __attribute__((aligned(16))) uint16_t sK[2][2 * kBlockElems];
+  __shared__ __attribute__((aligned(16))) uint16_t sV[2][2 * kBlockElems];
 
   const int n_qt = (a.S + kPfRows - 1) / kPfRows;
   const int qt = n_qt - 1 - blockIdx.x;  // longest rows first
   const int hq = blockIdx.y, b = blockIdx.z;
   const int h = hq / a.G;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, hh = lane >> 5;
   const int q0 = qt * kPfRows;
   const int r0 = q0 + wave * 32;  // first row of this wavefront
   const int row = r0 + col;
   const int S = a.S, W = a.window;
+  const float c2 = a.scale_log2;
 
   // Q^T fragments: lane (row, hh) holds dims kk*16 + hh*8 .. +7
   bf16x8_t qf[8];
@@ -86,40 +97,36 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_tiled_kernel(TiledPrefi
   for (int db = 0; db < 4; ++db)
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
-  float m = -INFINITY, lsum = 0.f;
+  float m = -INFINITY, lsum = 0.f;  // m in raw score units
 
-  // global -> register prefetch of one 64-key tile: 2 blocks x 512 pieces of 16 B for K and for V
-  u32x4_t pk[4], pv[4];
-  auto fetch = [&](int jt) {
+  // Tile jt -> stage buf.  A tile is 1024 16-byte pieces of K and of V; piece p = 256*i + tid lands at LDS byte
+  // 16*p, which is what a direct load does when the wave-uniform LDS base is that of the wave's first lane.
+  auto issue = [&](int jt, int buf) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int piece = tid + 256 * i;  // 0..1023 ; block = piece / 512
-      const int kb = jt * 2 + (piece >> 9);
-      u32x4_t kz = {0u, 0u, 0u, 0u}, vz = {0u, 0u, 0u, 0u};
+      const int kb = jt * 2 + (i >> 1);
+      const int in_block = tid + 256 * (i & 1);
+      uint16_t* lk = &sK[buf][(256 * i + wave * 64) * 8];
+      uint16_t* lv = &sV[buf][(256 * i + wave * 64) * 8];
       if (kb < nblk_valid) {
-        kz = Kg[(int64_t)kb * 512 + (piece & 511)];
-        vz = Vg[(int64_t)kb * 512 + (piece & 511)];
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Kg + (int64_t)kb * 512 + in_block),
+                                         (__attribute__((address_space(3))) void*)lk, 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Vg + (int64_t)kb * 512 + in_block),
+                                         (__attribute__((address_space(3))) void*)lv, 16, 0, 0);
+      } else {  // beyond the prompt: zeros (finite data for the masked products)
+        ((u32x4_t*)lk)[lane] = u32x4_t{0u, 0u, 0u, 0u};
+        ((u32x4_t*)lv)[lane] = u32x4_t{0u, 0u, 0u, 0u};
       }
-      pk[i] = kz;
-      pv[i] = vz;
-    }
-  };
-  auto stash = [&]() {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int piece = tid + 256 * i;
-      ((u32x4_t*)sK)[piece] = pk[i];
-      ((u32x4_t*)sV)[piece] = pv[i];
     }
   };
 
   const int key_row = pf_key_of_row(col);  // key (within a block) this lane feeds as MFMA row `col`
-  fetch(jt_lo);
+  issue(jt_lo, 0);
   for (int jt = jt_lo; jt <= jt_hi; ++jt) {
-    __syncthreads();
-    stash();
-    __syncthreads();
-    if (jt < jt_hi) fetch(jt + 1);
+    const int buf = (jt - jt_lo) & 1;
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's direct loads of tile jt have landed
+    __syncthreads();                     // ... and everybody's; everybody is also done reading the other stage
+    if (jt < jt_hi) issue(jt + 1, buf ^ 1);
 
     const int k0 = jt * kPfKeys;
     // whole tile masked for every row of this wavefront?
@@ -132,57 +139,61 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_tiled_kernel(TiledPrefi
     for (int sub = 0; sub < 2; ++sub) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) s[sub][i] = 0.f;
-      const uint16_t* kb = sK + sub * kBlockElems + (key_row >> 4) * 2048 + (key_row & 15) * 8;
+      const uint16_t* kb = &sK[buf][sub * kBlockElems + (key_row >> 4) * 2048 + (key_row & 15) * 8];
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
         const bf16x8_t kf = *(const bf16x8_t*)(kb + (2 * kk + hh) * 128);
         s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[sub], 0, 0, 0);
       }
     }
-    // scale, mask, row maximum
-    float mx = -INFINITY;
+    if (need_mask) {
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
+      for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        float v = s[sub][i] * a.scale_log2;
-        if (need_mask) {
+        for (int i = 0; i < 16; ++i) {
           // register i is MFMA row 8*(i/4) + 4*hh + i%4, which holds key pi(row)
           const int key = k0 + sub * 32 + pf_key_of_row(8 * (i >> 2) + 4 * hh + (i & 3));
           const bool ok = (key <= row) && (W == 0 || key > row - W);
-          v = ok ? v : -INFINITY;
+          s[sub][i] = ok ? s[sub][i] : -INFINITY;
         }
-        s[sub][i] = v;
-        mx = fmaxf(mx, v);
-      }
+    }
+    float mx = s[0][0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[0][i]);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[1][i]);
     mx = fmaxf(mx, __shfl_xor(mx, 32));
     const float m_new = fmaxf(m, mx);
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;  // row with nothing visible yet
-    const float alpha = __builtin_amdgcn_exp2f(m - m_use);
-    m = m_new;
+    // rescale only when some row of the wavefront saw a new maximum (rare after the first tiles)
+    if (__any(m_new > m)) {
+      const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c2);  // m = -inf -> 0 (accumulators are 0 anyway)
+      const float al = (m_new > m) ? alpha : 1.f;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][i] *= al;
+      lsum *= al;
+      m = m_new;
+    }
+    const float mc = (m == -INFINITY) ? 0.f : m * c2;  // row with nothing visible yet: all its scores are -inf
     float psum = 0.f;
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
-
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
-        uint32_t hi[8], lo[8];
+        u32x4_t hw, lw;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const float p = __builtin_amdgcn_exp2f(s[sub][8 * u + j] - m_use);
-          psum += p;
-          hi[j] = pf_bf16_bits_rn(p);
-          lo[j] = pf_bf16_bits_rn(p - __uint_as_float(hi[j] << 16));
+        for (int jp = 0; jp < 4; ++jp) {
+          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][8 * u + 2 * jp], c2, -mc));
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][8 * u + 2 * jp + 1], c2, -mc));
+          psum += p0 + p1;
+          const uint32_t hp = pf_pack_bf16(p0, p1);
+          hw[jp] = hp;
+          lw[jp] = pf_pack_bf16(p0 - __uint_as_float(hp << 16), p1 - __uint_as_float(hp & 0xffff0000u));
         }
-        const u32x4_t hw = {hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16)};
-        const u32x4_t lw = {lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16)};
         const bf16x8_t ph = __builtin_bit_cast(bf16x8_t, hw), pl = __builtin_bit_cast(bf16x8_t, lw);
         // V fragment of this slab: dims 32*db + col, keys of piece g = 2u + hh
-        const uint16_t* vb = sV + sub * kBlockElems + (col >> 4) * 512 + ((2 * u + hh) * 16 + (col & 15)) * 8;
+        const uint16_t* vb = &sV[buf][sub * kBlockElems + (col >> 4) * 512 + ((2 * u + hh) * 16 + (col & 15)) * 8];
 #pragma unroll
         for (int db = 0; db < 4; ++db) {
           const bf16x8_t vf = *(const bf16x8_t*)(vb + db * 1024);
@@ -191,7 +202,7 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_tiled_kernel(TiledPrefi
         }
       }
     }
-    lsum = lsum * alpha + psum;
+    lsum += psum;
   }
 
   lsum += __shfl_xor(lsum, 32);
@@ -209,8 +220,8 @@ __global__ __launch_bounds__(kPfWaves * 64) void prefill_tiled_kernel(TiledPrefi
           *(floatx4_t*)((float*)op + d) = floatx4_t{v0, v1, v2, v3};
         } else {
           uint2 w;
-          w.x = pf_bf16_bits_rn(v0) | (pf_bf16_bits_rn(v1) << 16);
-          w.y = pf_bf16_bits_rn(v2) | (pf_bf16_bits_rn(v3) << 16);
+          w.x = pf_pack_bf16(v0, v1);
+          w.y = pf_pack_bf16(v2, v3);
           *(uint2*)((uint16_t*)op + d) = w;
         }
       }
