@@ -88,6 +88,15 @@ hipError_t launch_append_rowmajor(const AppendLaunch& a, hipStream_t s) {
 //   window  > 0 : slot s <- largest position p < len with p = s (mod window)   (valid while s < min(len, window))
 // Slots of the block that receive nothing are zero-filled so that later MFMA reads see finite data.
 // ------------------------------------------------------------------------------------------------
+// bf16 -> fp16 bit pattern, round to nearest even, magnitudes above the fp16 range saturate to +-65504
+__device__ inline uint16_t bf16_to_f16_sat(uint16_t b) {
+  float f = __uint_as_float((uint32_t)b << 16);
+  f = fminf(fmaxf(f, -65504.f), 65504.f);  // NaN stays NaN through the conversion below
+  if (!(f == f)) f = __uint_as_float((uint32_t)b << 16);
+  const _Float16 hval = (_Float16)f;
+  return __builtin_bit_cast(uint16_t, hval);
+}
+
 __device__ inline int64_t source_position(int slot, int len, int window) {
   if (window == 0) return slot < len ? slot : -1;
   if (slot >= window || slot >= len) return -1;
@@ -115,8 +124,8 @@ __global__ __launch_bounds__(256) void store_tiled_kernel(StoreLaunch a) {
     uint4 kq = make_uint4(0, 0, 0, 0), vq = make_uint4(0, 0, 0, 0);
     if (p >= 0) {
       const int64_t off = ((first + p) * a.Hkv + h) * kTiledDim + c * 8;
-      kq = *(const uint4*)(ksrc + off);
-      vq = *(const uint4*)(vsrc + off);
+      if (a.K) kq = *(const uint4*)(ksrc + off);
+      if (a.V) vq = *(const uint4*)(vsrc + off);
     }
     *(uint4*)&sK[key][c * 8] = kq;
     *(uint4*)&sV[key][c * 8] = vq;
@@ -128,17 +137,20 @@ __global__ __launch_bounds__(256) void store_tiled_kernel(StoreLaunch a) {
   uint16_t* Vd = (uint16_t*)a.V + blk_elem;
   for (int o = threadIdx.x; o < kBlockElems / 8; o += blockDim.x) {
     // K piece o = t*256 + c*16 + r  holds key t*16+r, dims c*8..c*8+7
-    {
+    if (a.K) {
       const int t = o >> 8, c = (o >> 4) & 15, r = o & 15;
       *(uint4*)(Kd + o * 8) = *(const uint4*)&sK[t * 16 + r][c * 8];
     }
     // V piece o = nn*64 + g*16 + c  holds dim nn*16+c of keys 16*(j/4) + 4g + j%4, j = 0..7
-    {
+    if (a.V) {
       const int nn = o >> 6, g = (o >> 4) & 3, c = o & 15;
       const int d = nn * 16 + c;
       uint16_t e[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) e[j] = sV[16 * (j >> 2) + 4 * g + (j & 3)][d];
+      for (int j = 0; j < 8; ++j) {
+        e[j] = sV[16 * (j >> 2) + 4 * g + (j & 3)][d];
+        if (a.v_as_f16) e[j] = bf16_to_f16_sat(e[j]);
+      }
       uint4 val;
       val.x = e[0] | ((uint32_t)e[1] << 16);
       val.y = e[2] | ((uint32_t)e[3] << 16);

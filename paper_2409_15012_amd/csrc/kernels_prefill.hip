@@ -2,13 +2,16 @@
 // including the query's own token (arXiv 2409.15012, Section 3, "Sliding Window Attention Layers"; Section 1 for
 // the causal standard layer).
 //
-// Tiled path (bf16, head_dim 128): flash-attention forward on 32x32x16 bf16 MFMA.  K and V are read in the same
-// 32-key block format the decode caches use (the full cache itself, or a staging copy of the prompt for sliding
-// layers), so a block is copied verbatim into LDS and every operand fragment is one 16-byte LDS read per lane.
+// Tiled path (bf16, head_dim 128): flash-attention forward on 32x32x16 MFMA.  K and V are read in the same
+// 32-key block format the decode caches use (K: the full cache itself, or a staging copy of the prompt for
+// sliding layers; V: a staging copy converted to fp16), so a block is copied verbatim into LDS and every operand
+// fragment is one 16-byte LDS read per lane.  Scores use the bf16 MFMA (exact products of the bf16 inputs); the
+// probabilities are rounded to fp16 (11 significant bits) and multiply fp16 V on the fp16 MFMA: a bf16 rounding
+// of P would by itself cost about 1.6e-3 relative L2 error.
 // A workgroup of 4 wavefronts owns 128 query rows of one query head (32 rows per wavefront) and walks the 64-key
 // tiles its rows can see, skipping tiles that are masked for all of them:
 //   scores^T[key, row]  = K (A, 32 keys x 16 dims) x Q^T (B, 16 dims x 32 rows),  8 k-steps per 32-key block
-//   out^T[dim, row]    += V^T (A, 32 dims x 16 keys) x P^T (B, 16 keys x 32 rows), P split into bf16 head + remainder
+//   out^T[dim, row]    += V^T (A, 32 dims x 16 keys) x P^T (B, 16 keys x 32 rows), both fp16
 // Lane l holds query row l%32 in both products, so the online-softmax state and the accumulator rescale are
 // lane-local; the row maximum needs one exchange with lane l^32.
 #include "mixattn_internal.h"
@@ -33,8 +36,8 @@ __device__ inline uint32_t pf_bf16_bits_rn(float f) {
 
 struct TiledPrefillParams {
   const uint16_t* q; void* out;
-  const uint16_t* Kt; const uint16_t* Vt;
-  const int64_t* d_base; const int32_t* d_slots;
+  const uint16_t* Kt; const int64_t* k_base; const int32_t* k_slots;  // bf16 tiles
+  const uint16_t* Vt; const int64_t* v_base; const int32_t* v_slots;  // fp16 tiles
   int window, S, Hq, G;
   float scale_log2;
 };
@@ -45,6 +48,16 @@ __device__ inline int pf_key_of_row(int m) { return (m & 7) | ((m & 8) << 1) | (
 
 typedef __attribute__((__vector_size__(2 * sizeof(float)))) float floatx2_t;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+typedef __attribute__((__vector_size__(2 * sizeof(_Float16)))) _Float16 halfx2_t;
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 halfx8_t;
+
+// two floats -> packed fp16 pair, round to nearest even (one v_cvt_pk_f16_f32)
+__device__ inline uint32_t pf_pack_f16(float lo, float hi) {
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(floatx2_t{lo, hi}, halfx2_t));
+}
+// Probabilities enter the P.V product as fp16 scaled by 2^12 (so that weights down to 2^-26 of the row maximum
+// stay normal numbers); the row sum carries the same factor and it cancels in the final division.
+constexpr float kPShift = 12.0f;
 
 // two floats -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32)
 __device__ inline uint32_t pf_pack_bf16(float lo, float hi) {
@@ -57,9 +70,22 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_tiled_kernel(TiledPr
   __shared__ __attribute__((aligned(16))) uint16_t sK[2][2 * kBlockElems];
   __shared__ __attribute__((aligned(16))) uint16_t sV[2][2 * kBlockElems];
 
+  // Workgroup ids go round-robin over the 8 XCDs, each with its own L2.  Map them so that one XCD works on the
+  // query tiles of one head at a time (ids = 8*slot + xcd): its L2 then holds one head's K/V stream, not eight.
   const int n_qt = (a.S + kPfRows - 1) / kPfRows;
-  const int qt = n_qt - 1 - blockIdx.x;  // longest rows first
-  const int hq = blockIdx.y, b = blockIdx.z;
+  int qt, hq;
+  {
+    const int id = blockIdx.x + gridDim.x * blockIdx.y;
+    if ((a.Hq & 7) == 0) {
+      const int xcd = id & 7, slot = id >> 3;
+      hq = xcd + 8 * (slot / n_qt);
+      qt = n_qt - 1 - (slot % n_qt);  // longest rows first
+    } else {
+      hq = id / n_qt;
+      qt = n_qt - 1 - (id % n_qt);
+    }
+  }
+  const int b = blockIdx.z;
   const int h = hq / a.G;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -82,11 +108,9 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_tiled_kernel(TiledPr
     }
   }
 
-  const int64_t nblk_alloc = a.d_slots[b] >> 5;
   const int nblk_valid = (S + kBlockKeys - 1) / kBlockKeys;
-  const int64_t first_blk = a.d_base[b] + (int64_t)h * nblk_alloc;
-  const u32x4_t* Kg = (const u32x4_t*)(a.Kt + first_blk * kBlockElems);
-  const u32x4_t* Vg = (const u32x4_t*)(a.Vt + first_blk * kBlockElems);
+  const u32x4_t* Kg = (const u32x4_t*)(a.Kt + (a.k_base[b] + (int64_t)h * (a.k_slots[b] >> 5)) * kBlockElems);
+  const u32x4_t* Vg = (const u32x4_t*)(a.Vt + (a.v_base[b] + (int64_t)h * (a.v_slots[b] >> 5)) * kBlockElems);
 
   const int last_row = min(q0 + kPfRows, S) - 1;
   const int jt_hi = last_row / kPfKeys;
@@ -175,30 +199,28 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_tiled_kernel(TiledPr
       lsum *= al;
       m = m_new;
     }
-    const float mc = (m == -INFINITY) ? 0.f : m * c2;  // row with nothing visible yet: all its scores are -inf
+    // row with nothing visible yet: all its scores are -inf, any finite offset gives p = 0
+    const float mc = (m == -INFINITY) ? 0.f : m * c2 - kPShift;
     float psum = 0.f;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
-        u32x4_t hw, lw;
+        u32x4_t pw;
 #pragma unroll
         for (int jp = 0; jp < 4; ++jp) {
           const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][8 * u + 2 * jp], c2, -mc));
           const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[sub][8 * u + 2 * jp + 1], c2, -mc));
           psum += p0 + p1;
-          const uint32_t hp = pf_pack_bf16(p0, p1);
-          hw[jp] = hp;
-          lw[jp] = pf_pack_bf16(p0 - __uint_as_float(hp << 16), p1 - __uint_as_float(hp & 0xffff0000u));
+          pw[jp] = pf_pack_f16(p0, p1);
         }
-        const bf16x8_t ph = __builtin_bit_cast(bf16x8_t, hw), pl = __builtin_bit_cast(bf16x8_t, lw);
+        const halfx8_t pf = __builtin_bit_cast(halfx8_t, pw);
         // V fragment of this slab: dims 32*db + col, keys of piece g = 2u + hh
         const uint16_t* vb = &sV[buf][sub * kBlockElems + (col >> 4) * 512 + ((2 * u + hh) * 16 + (col & 15)) * 8];
 #pragma unroll
         for (int db = 0; db < 4; ++db) {
-          const bf16x8_t vf = *(const bf16x8_t*)(vb + db * 1024);
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, ph, o[db], 0, 0, 0);
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pl, o[db], 0, 0, 0);
+          const halfx8_t vf = *(const halfx8_t*)(vb + db * 1024);
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf, o[db], 0, 0, 0);
         }
       }
     }
@@ -231,8 +253,8 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_tiled_kernel(TiledPr
 hipError_t launch_prefill_tiled(const PrefillLaunch& L, hipStream_t s) {
   TiledPrefillParams p;
   p.q = (const uint16_t*)L.q; p.out = L.out;
-  p.Kt = (const uint16_t*)L.Kt; p.Vt = (const uint16_t*)L.Vt;
-  p.d_base = L.d_base; p.d_slots = L.d_slots;
+  p.Kt = (const uint16_t*)L.Kt; p.k_base = L.k_base; p.k_slots = L.k_slots;
+  p.Vt = (const uint16_t*)L.Vt; p.v_base = L.v_base; p.v_slots = L.v_slots;
   p.window = L.window; p.S = L.S; p.Hq = L.Hq; p.G = L.G;
   p.scale_log2 = L.scale * kLog2e;
   const dim3 grid((L.S + kPfRows - 1) / kPfRows, L.Hq, L.batch), block(kPfWaves * 64);

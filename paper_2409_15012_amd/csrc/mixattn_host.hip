@@ -372,8 +372,7 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
   if (seq_len < 1) return MIXATTN_ERR_ORDER;
   Cache& c = L->caches[L->layer_cache[layer]];
   const bool writer = c.writer == layer;
-  const bool reads_cache = L->tiled && c.kind == MIXATTN_FULL;  // the kernel takes K/V from the cache itself
-  if ((writer || !reads_cache) && (!k || !v)) return MIXATTN_ERR_NULL;
+  if (!k || !v) return MIXATTN_ERR_NULL;
   for (int b = 0; b < L->batch; ++b) {
     if (writer && c.len[b] != 0) return MIXATTN_ERR_ORDER;
     if (!writer && c.len[b] != seq_len) return MIXATTN_ERR_ORDER;
@@ -384,7 +383,7 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
   p.q = q; p.out = out; p.k_src = k; p.v_src = v;
   p.window = c.window; p.batch = L->batch; p.S = seq_len; p.Hq = L->Hq; p.Hkv = L->Hkv; p.G = L->G; p.D = L->D;
   p.kv_dtype = L->kv_dtype; p.out_dtype = L->out_dtype; p.scale = L->scale;
-  p.Kt = p.Vt = nullptr; p.d_base = nullptr; p.d_slots = nullptr;
+  p.Kt = p.Vt = nullptr; p.k_base = p.v_base = nullptr; p.k_slots = p.v_slots = nullptr;
 
   StoreLaunch st;
   st.k_src = k; st.v_src = v; st.d_src_first = nullptr; st.d_src_len = nullptr; st.uniform_len = seq_len;
@@ -392,7 +391,6 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
 
   if (L->tiled) {
     const bool simple = L->prefill_simple != 0;  // scalar kernel on the caller's tensors (cross-check path)
-    if (simple && (!k || !v)) return MIXATTN_ERR_NULL;
     if (c.kind == MIXATTN_FULL && writer) {
       st.K = c.K; st.V = c.V; st.d_base = c.d_base; st.d_slots = c.d_slots; st.window = 0;
       st.d_lens_out = c.d_lens; st.max_slots = seq_len;
@@ -401,16 +399,22 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
     if (simple) {
       HIP_TRY(launch_prefill_rowmajor(p, s));
     } else {
+      // the MFMA kernel reads V as fp16 from the staging area (every layer) and K either from the full cache
+      // (committed above, or by the writer's prefill) or, for sliding layers, from the staging area
+      int e = ensure_stage(L, (seq_len + kBlockKeys - 1) / kBlockKeys);
+      if (e != MIXATTN_OK) return e;
+      st.K = c.kind == MIXATTN_FULL ? nullptr : L->stageK;
+      st.V = L->stageV; st.v_as_f16 = 1;
+      st.d_base = L->d_stage_base; st.d_slots = L->d_stage_slots;
+      st.window = 0; st.d_lens_out = nullptr; st.max_slots = seq_len;
+      HIP_TRY(launch_store_tiled(st, s));
+      st.v_as_f16 = 0;
       if (c.kind == MIXATTN_FULL) {
-        p.Kt = c.K; p.Vt = c.V; p.d_base = c.d_base; p.d_slots = c.d_slots;
+        p.Kt = c.K; p.k_base = c.d_base; p.k_slots = c.d_slots;
       } else {
-        int e = ensure_stage(L, (seq_len + kBlockKeys - 1) / kBlockKeys);
-        if (e != MIXATTN_OK) return e;
-        st.K = L->stageK; st.V = L->stageV; st.d_base = L->d_stage_base; st.d_slots = L->d_stage_slots;
-        st.window = 0; st.d_lens_out = nullptr; st.max_slots = seq_len;
-        HIP_TRY(launch_store_tiled(st, s));
-        p.Kt = L->stageK; p.Vt = L->stageV; p.d_base = L->d_stage_base; p.d_slots = L->d_stage_slots;
+        p.Kt = L->stageK; p.k_base = L->d_stage_base; p.k_slots = L->d_stage_slots;
       }
+      p.Vt = L->stageV; p.v_base = L->d_stage_base; p.v_slots = L->d_stage_slots;
       HIP_TRY(launch_prefill_tiled(p, s));
     }
     if (writer && c.kind == MIXATTN_SLIDING) {

@@ -72,7 +72,7 @@ struct mixattn_layout {
   std::vector<int32_t> capacity;  // [batch] for FULL caches
   int32_t* d_lens_all = nullptr;  // [n_caches][batch]
   mixattn::DecodeScratch scratch;
-  // prompt staging for sliding-window prefill on the tiled path (grown on demand)
+  // prompt staging for prefill on the tiled path (grown on demand): V of every layer as fp16, K of sliding layers
   void* stageK = nullptr;
   void* stageV = nullptr;
   int64_t stage_blocks = 0;  // blocks per (b, h) currently allocated
@@ -110,7 +110,8 @@ hipError_t launch_decode_tiled(const DecodeLaunch& a, hipStream_t s);
 hipError_t launch_decode_rowmajor(const DecodeLaunch& a, hipStream_t s);
 
 struct StoreLaunch {  // bulk commit of prompt / packed k,v into a cache or the staging area
-  void* K; void* V;
+  void* K; void* V;            // tiled path: either may be nullptr (that tensor is skipped)
+  int v_as_f16 = 0;            // tiled path: store V converted to fp16 (prefill staging), saturating at +-65504
   const int64_t* d_base; const int32_t* d_slots;
   int window;             // 0 = position p -> slot p; >0 = ring (keep last min(len, window), slot p mod window)
   const void* k_src; const void* v_src;  // [tokens, Hkv, D]
@@ -140,8 +141,9 @@ hipError_t launch_gather_row(const void* K, const void* V, int64_t base, int32_t
 
 struct PrefillLaunch {
   const void* q; void* out;
-  // tiled path: K/V in tile format (the full cache itself or the staging area)
-  const void* Kt; const void* Vt; const int64_t* d_base; const int32_t* d_slots;
+  // tiled path: K in tile format (the full cache itself or the staging area), V in tile format as fp16 (staging)
+  const void* Kt; const int64_t* k_base; const int32_t* k_slots;
+  const void* Vt; const int64_t* v_base; const int32_t* v_slots;
   // row-major path: the caller's prompt tensors
   const void* k_src; const void* v_src;
   int window;  // 0 = full causal
