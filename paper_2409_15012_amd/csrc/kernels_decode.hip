@@ -37,7 +37,6 @@ __device__ inline void store_out<float>(float* p, float v) { *p = v; }
 template <>
 __device__ inline void store_out<uint16_t>(uint16_t* p, float v) { *p = (uint16_t)bf16_bits_rn(v); }
 
-constexpr int kDecodeWaves = 4;
 
 struct TiledDecodeParams {
   const uint16_t* K; const uint16_t* V;
@@ -66,9 +65,10 @@ __device__ inline void merge_partials(const float* p_acc, const float* p_ml, int
 }
 
 // RING selects the sliding-window instantiation (reads min(n, window) ring slots); it is a template parameter so
-// that the two layer kinds are separate kernels in a profile.
-template <typename OutT, bool RING>
-__global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(TiledDecodeParams a) {
+// that the two layer kinds are separate kernels in a profile.  NW = wavefronts per workgroup (4 or 8): wave w
+// takes blocks w, w + NW, ... of the chunk.
+template <typename OutT, bool RING, int NW>
+__global__ __launch_bounds__(NW * 64, 2) void decode_tiled_kernel(TiledDecodeParams a) {
   const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   int n = a.d_lens[b];
   if (RING && n > a.window) n = a.window;
@@ -187,23 +187,23 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
   // Software pipeline over this wavefront's blocks blk0 + wave + 4*i, i < cnt.  The steady-state loop issues the
   // next block's loads unconditionally before it consumes the current one, so the wait before the MFMAs only
   // covers the older of the two blocks in flight; the last one or two blocks are peeled.
-  const int cnt = (blk1 - blk0 - wave + kDecodeWaves - 1) / kDecodeWaves;  // may be <= 0
+  const int cnt = (blk1 - blk0 - wave + NW - 1) / NW;  // may be <= 0
   if (cnt > 0) {
     const int first = blk0 + wave;
     load_block(first, kr[0], vr[0]);
     int i = 0;
     for (; i + 2 < cnt; i += 2) {
-      load_block(first + (i + 1) * kDecodeWaves, kr[1], vr[1]);
-      compute_block(no_tail{}, first + i * kDecodeWaves, kr[0], vr[0]);
-      load_block(first + (i + 2) * kDecodeWaves, kr[0], vr[0]);
-      compute_block(no_tail{}, first + (i + 1) * kDecodeWaves, kr[1], vr[1]);
+      load_block(first + (i + 1) * NW, kr[1], vr[1]);
+      compute_block(no_tail{}, first + i * NW, kr[0], vr[0]);
+      load_block(first + (i + 2) * NW, kr[0], vr[0]);
+      compute_block(no_tail{}, first + (i + 1) * NW, kr[1], vr[1]);
     }
     if (i + 1 < cnt) {
-      load_block(first + (i + 1) * kDecodeWaves, kr[1], vr[1]);
-      compute_block(no_tail{}, first + i * kDecodeWaves, kr[0], vr[0]);
-      compute_last(first + (i + 1) * kDecodeWaves, kr[1], vr[1]);
+      load_block(first + (i + 1) * NW, kr[1], vr[1]);
+      compute_block(no_tail{}, first + i * NW, kr[0], vr[0]);
+      compute_last(first + (i + 1) * NW, kr[1], vr[1]);
     } else {
-      compute_last(first + i * kDecodeWaves, kr[0], vr[0]);
+      compute_last(first + i * NW, kr[0], vr[0]);
     }
   }
 
@@ -215,9 +215,9 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
 #pragma unroll
     for (int i = 0; i < 4; ++i) o[nn][i] += __shfl_down(o[nn][i], G);  // lane col+G of the same 16-lane row
 
-  __shared__ float s_o[kDecodeWaves][kMaxGroup][kTiledDim];
-  __shared__ float s_m[kDecodeWaves][kMaxGroup];
-  __shared__ float s_l[kDecodeWaves][kMaxGroup];
+  __shared__ float s_o[NW][kMaxGroup][kTiledDim];
+  __shared__ float s_m[NW][kMaxGroup];
+  __shared__ float s_l[NW][kMaxGroup];
   __shared__ int s_last;
   if (is_hi) {
 #pragma unroll
@@ -232,14 +232,14 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
   __syncthreads();
 
   const bool direct = (a.n_chunks == 1);
-  for (int idx = tid; idx < G * kTiledDim; idx += kDecodeWaves * 64) {
+  for (int idx = tid; idx < G * kTiledDim; idx += NW * 64) {
     const int hd = idx >> 7, d = idx & 127;
     float M = s_m[0][hd];
 #pragma unroll
-    for (int w = 1; w < kDecodeWaves; ++w) M = fmaxf(M, s_m[w][hd]);
+    for (int w = 1; w < NW; ++w) M = fmaxf(M, s_m[w][hd]);
     float L = 0.f, acc = 0.f;
 #pragma unroll
-    for (int w = 0; w < kDecodeWaves; ++w) {
+    for (int w = 0; w < NW; ++w) {
       const float wgt = fast_exp2(s_m[w][hd] - M);  // a wave without blocks has m = -inf, weight 0
       L += s_l[w][hd] * wgt;
       acc += s_o[w][hd][d] * wgt;
@@ -269,7 +269,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
   __syncthreads();
   if (!s_last) return;
   __threadfence();
-  for (int idx = tid; idx < G * kTiledDim; idx += kDecodeWaves * 64) {
+  for (int idx = tid; idx < G * kTiledDim; idx += NW * 64) {
     const int hd = idx >> 7, d = idx & 127;
     const int64_t row = (int64_t)b * a.Hq + (int64_t)h * G + hd;
     merge_partials<OutT>(a.p_acc + row * kMaxChunks * kTiledDim, a.p_ml + row * kMaxChunks * 2, n_chunks_b, d,
@@ -300,12 +300,22 @@ hipError_t launch_decode_tiled(const DecodeLaunch& L, hipStream_t s) {
   p.chunk_blocks = L.chunk_blocks; p.n_chunks = L.n_chunks;
   p.fused_combine = L.fused_combine;
   p.p_acc = L.scratch.acc; p.p_ml = L.scratch.ml; p.counters = L.scratch.counters;
-  const dim3 grid(L.n_chunks, L.Hkv, L.batch), block(kDecodeWaves * 64);
+  const dim3 grid(L.n_chunks, L.Hkv, L.batch);
   const bool f32 = L.out_dtype == MIXATTN_F32, ring = L.window > 0;
-  if (f32 && ring) hipLaunchKernelGGL((decode_tiled_kernel<float, true>), grid, block, 0, s, p);
-  else if (f32) hipLaunchKernelGGL((decode_tiled_kernel<float, false>), grid, block, 0, s, p);
-  else if (ring) hipLaunchKernelGGL((decode_tiled_kernel<uint16_t, true>), grid, block, 0, s, p);
-  else hipLaunchKernelGGL((decode_tiled_kernel<uint16_t, false>), grid, block, 0, s, p);
+#define MIXATTN_LAUNCH_DECODE(OUT, RING, NW) \
+  hipLaunchKernelGGL((decode_tiled_kernel<OUT, RING, NW>), grid, dim3(NW * 64), 0, s, p)
+  if (L.waves == 8) {
+    if (f32 && ring) MIXATTN_LAUNCH_DECODE(float, true, 8);
+    else if (f32) MIXATTN_LAUNCH_DECODE(float, false, 8);
+    else if (ring) MIXATTN_LAUNCH_DECODE(uint16_t, true, 8);
+    else MIXATTN_LAUNCH_DECODE(uint16_t, false, 8);
+  } else {
+    if (f32 && ring) MIXATTN_LAUNCH_DECODE(float, true, 4);
+    else if (f32) MIXATTN_LAUNCH_DECODE(float, false, 4);
+    else if (ring) MIXATTN_LAUNCH_DECODE(uint16_t, true, 4);
+    else MIXATTN_LAUNCH_DECODE(uint16_t, false, 4);
+  }
+#undef MIXATTN_LAUNCH_DECODE
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (L.n_chunks > 1 && !L.fused_combine) {

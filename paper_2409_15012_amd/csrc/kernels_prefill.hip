@@ -158,6 +158,8 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_tiled_kernel(TiledPr
     if (W > 0 && k0 + kPfKeys - 1 < r0 - W + 1) continue;
     const bool need_mask = (k0 + kPfKeys - 1 > r0) || (W > 0 && k0 < r0 + 31 - W + 1);
 
+    // the wavefront feeding the matrix pipe wins issue arbitration over its SIMD mate's softmax arithmetic
+    __builtin_amdgcn_s_setprio(3);
     floatx16_t s[2];
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
@@ -170,6 +172,7 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void prefill_tiled_kernel(TiledPr
         s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[sub], 0, 0, 0);
       }
     }
+    __builtin_amdgcn_s_setprio(0);
     if (need_mask) {
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub)

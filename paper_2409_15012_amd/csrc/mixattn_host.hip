@@ -339,6 +339,11 @@ int mixattn_decode(mixattn_layout* L, int layer, const void* q, void* out, void*
   a.max_blocks = max_blocks;
   a.chunk_blocks = chunk_blocks;
   a.n_chunks = (max_blocks + chunk_blocks - 1) / chunk_blocks;
+  if (L->decode_waves > 0) {
+    a.waves = (int)L->decode_waves;
+  } else {
+    a.waves = 4;  // eight wavefronts per workgroup measured no faster at any shape tried
+  }
   HIP_TRY(launch_decode_tiled(a, (hipStream_t)stream));
   return MIXATTN_OK;
 }
@@ -561,6 +566,10 @@ int mixattn_set_param(mixattn_layout* L, int param, int64_t value) {
       if (value != 0 && value != 1) return MIXATTN_ERR_PARAM;
       L->prefill_simple = value;
       return MIXATTN_OK;
+    case MIXATTN_PARAM_DECODE_WAVES:
+      if (value != 0 && value != 4 && value != 8) return MIXATTN_ERR_PARAM;
+      L->decode_waves = value;
+      return MIXATTN_OK;
     default: return MIXATTN_ERR_PARAM;
   }
 }
@@ -571,6 +580,7 @@ int mixattn_get_param(const mixattn_layout* L, int param, int64_t* value) {
     case MIXATTN_PARAM_CHUNK_KEYS: *value = L->chunk_keys; return MIXATTN_OK;
     case MIXATTN_PARAM_FUSED_COMBINE: *value = L->fused_combine; return MIXATTN_OK;
     case MIXATTN_PARAM_PREFILL_SIMPLE: *value = L->prefill_simple; return MIXATTN_OK;
+    case MIXATTN_PARAM_DECODE_WAVES: *value = L->decode_waves; return MIXATTN_OK;
     default: return MIXATTN_ERR_PARAM;
   }
 }

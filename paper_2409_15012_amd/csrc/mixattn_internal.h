@@ -85,6 +85,7 @@ struct mixattn_layout {
   int64_t chunk_keys = 0;
   int64_t fused_combine = 0;
   int64_t prefill_simple = 0;
+  int64_t decode_waves = 0;  // 0 = automatic
   int device = 0;
   int n_cus = 256;
 };
@@ -103,6 +104,7 @@ struct DecodeLaunch {
   int max_blocks;      // over the batch, ceil(min(n_b, window)/32) (tiled path)
   int chunk_blocks;    // blocks per split-K chunk
   int n_chunks;        // grid.x
+  int waves;           // wavefronts per workgroup: 4 or 8
   int fused_combine;
   DecodeScratch scratch;
 };
