@@ -37,6 +37,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-keys", type=int, default=0)
     ap.add_argument("--fused-combine", type=int, default=-1)
+    ap.add_argument("--prefill-waves", type=int, default=0)
     ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
     ap.add_argument("--only", default="", help="profiling aid: 'full' or 'sliding' runs only that layer kind per step")
     ap.add_argument("--copy-calibration", type=int, default=0,
@@ -222,6 +223,8 @@ def run_prefill(args, mx, wl, torch, w):
     dev = "cuda:0"
     B, S, Hq, Hkv, d = w.batch, w.prefill_len, w.n_q_heads, w.n_kv_heads, w.head_dim
     lay = mx.Layout(w.layers, B, Hq, Hkv, d, capacity=[S] * B, kv_dtype="bf16", out_dtype=args.out_dtype)
+    if args.prefill_waves:
+        lay.set_param(mx.PARAM_PREFILL_WAVES, args.prefill_waves)
     # one q per layer kind is enough to time (values do not change the cost); K/V per writer layer
     q = wl.randn(wl.layer_seed(w.seed, 0, "q"), (B, S, Hq, d), torch.bfloat16, dev)
     kv = {}
@@ -235,6 +238,8 @@ def run_prefill(args, mx, wl, torch, w):
         lay.reset()
         for li in range(len(w.layers)):
             k, v = kv[writer_of[li]]
+            if writer_of[li] != li:
+                k = v = None  # readers follow their writer directly: reuse the staged prompt
             if events is not None and li == 0:
                 e0 = torch.cuda.Event(enable_timing=True)
                 e1 = torch.cuda.Event(enable_timing=True)

@@ -123,7 +123,11 @@ int mixattn_decode(mixattn_layout* L, int layer, const void* q, void* out, void*
    Writer layer: k, v are its prompt keys/values; they are attended over and committed to its cache (FULL: all
    seq_len positions; SLIDING: the last min(seq_len, window) positions, each at slot p mod window) and every
    n_b becomes seq_len.  Reader layer: pass the writer's prompt k, v again (attended over, not stored); the
-   writer's prefill must have run (n_b == seq_len).  Errors: ORDER, CAPACITY, NULL. */
+   writer's prefill must have run (n_b == seq_len).  On the MFMA path (bf16, head_dim 128) a reader may instead
+   pass k = v = NULL to reuse the tile-format copy of the prompt that the most recent mixattn_prefill call on this
+   layout staged, provided that call was for the same cache and seq_len (ORDER otherwise): this is the cheap way
+   to run the readers of a sharing group right after their writer.  On that path V is staged as fp16 (values
+   beyond +-65504 saturate).  Errors: ORDER, CAPACITY, NULL. */
 int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, const void* v, void* out,
                     int seq_len, void* stream);
 
@@ -162,7 +166,8 @@ typedef enum {
   MIXATTN_PARAM_FUSED_COMBINE = 1, /* 1: the last workgroup of a (sequence, kv head) merges the split-K partials
                                       itself; 0: separate combine launch */
   MIXATTN_PARAM_PREFILL_SIMPLE = 2, /* 1: force the scalar prefill kernel (testing) */
-  MIXATTN_PARAM_DECODE_WAVES = 3    /* wavefronts per decode workgroup: 4, 8, or 0 = automatic */
+  MIXATTN_PARAM_DECODE_WAVES = 3,   /* wavefronts per decode workgroup: 4, 8, or 0 = automatic */
+  MIXATTN_PARAM_PREFILL_WAVES = 4   /* wavefronts per MFMA prefill workgroup: 4, 8, or 0 = default (4) */
 } mixattn_param;
 int mixattn_set_param(mixattn_layout* L, int param, int64_t value);
 int mixattn_get_param(const mixattn_layout* L, int param, int64_t* value);

@@ -241,6 +241,7 @@ int mixattn_reset(mixattn_layout* L, void* stream) {
   if (!L) return MIXATTN_ERR_NULL;
   HIP_TRY(launch_fill_i32(L->d_lens_all, 0, (int64_t)L->caches.size() * L->batch, (hipStream_t)stream));
   for (auto& c : L->caches) std::fill(c.len.begin(), c.len.end(), 0);
+  L->stage_cache = -1;
   return MIXATTN_OK;
 }
 
@@ -356,6 +357,7 @@ static int ensure_stage(mixattn_layout* L, int64_t blocks_per_head) {
   if (L->stageV) (void)hipFree(L->stageV);
   L->stageK = L->stageV = nullptr;
   L->stage_blocks = 0;
+  L->stage_cache = -1;
   const size_t bytes = (size_t)L->batch * L->Hkv * blocks_per_head * kBlockElems * 2;
   int st = dev_alloc(&L->stageK, bytes);
   if (st != MIXATTN_OK) return st;
@@ -377,7 +379,16 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
   if (seq_len < 1) return MIXATTN_ERR_ORDER;
   Cache& c = L->caches[L->layer_cache[layer]];
   const bool writer = c.writer == layer;
-  if (!k || !v) return MIXATTN_ERR_NULL;
+  const int ci = L->layer_cache[layer];
+  // a reader may pass k = v = NULL to reuse the prompt copy staged by the latest prefill call, if that call was for
+  // the same cache and length (tiled path only)
+  const bool reuse_stage = !k && !v;
+  if (reuse_stage) {
+    if (writer || !L->tiled || L->prefill_simple) return MIXATTN_ERR_NULL;
+    if (L->stage_cache != ci || L->stage_len != seq_len) return MIXATTN_ERR_ORDER;
+  } else if (!k || !v) {
+    return MIXATTN_ERR_NULL;
+  }
   for (int b = 0; b < L->batch; ++b) {
     if (writer && c.len[b] != 0) return MIXATTN_ERR_ORDER;
     if (!writer && c.len[b] != seq_len) return MIXATTN_ERR_ORDER;
@@ -389,6 +400,7 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
   p.window = c.window; p.batch = L->batch; p.S = seq_len; p.Hq = L->Hq; p.Hkv = L->Hkv; p.G = L->G; p.D = L->D;
   p.kv_dtype = L->kv_dtype; p.out_dtype = L->out_dtype; p.scale = L->scale;
   p.Kt = p.Vt = nullptr; p.k_base = p.v_base = nullptr; p.k_slots = p.v_slots = nullptr;
+  p.waves = (int)L->prefill_waves;
 
   StoreLaunch st;
   st.k_src = k; st.v_src = v; st.d_src_first = nullptr; st.d_src_len = nullptr; st.uniform_len = seq_len;
@@ -406,14 +418,19 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
     } else {
       // the MFMA kernel reads V as fp16 from the staging area (every layer) and K either from the full cache
       // (committed above, or by the writer's prefill) or, for sliding layers, from the staging area
-      int e = ensure_stage(L, (seq_len + kBlockKeys - 1) / kBlockKeys);
-      if (e != MIXATTN_OK) return e;
-      st.K = c.kind == MIXATTN_FULL ? nullptr : L->stageK;
-      st.V = L->stageV; st.v_as_f16 = 1;
-      st.d_base = L->d_stage_base; st.d_slots = L->d_stage_slots;
-      st.window = 0; st.d_lens_out = nullptr; st.max_slots = seq_len;
-      HIP_TRY(launch_store_tiled(st, s));
-      st.v_as_f16 = 0;
+      if (!reuse_stage) {
+        int e = ensure_stage(L, (seq_len + kBlockKeys - 1) / kBlockKeys);
+        if (e != MIXATTN_OK) return e;
+        L->stage_cache = -1;
+        st.K = c.kind == MIXATTN_FULL ? nullptr : L->stageK;
+        st.V = L->stageV; st.v_as_f16 = 1;
+        st.d_base = L->d_stage_base; st.d_slots = L->d_stage_slots;
+        st.window = 0; st.d_lens_out = nullptr; st.max_slots = seq_len;
+        HIP_TRY(launch_store_tiled(st, s));
+        st.v_as_f16 = 0;
+        L->stage_cache = ci;
+        L->stage_len = seq_len;
+      }
       if (c.kind == MIXATTN_FULL) {
         p.Kt = c.K; p.k_base = c.d_base; p.k_slots = c.d_slots;
       } else {
@@ -570,6 +587,10 @@ int mixattn_set_param(mixattn_layout* L, int param, int64_t value) {
       if (value != 0 && value != 4 && value != 8) return MIXATTN_ERR_PARAM;
       L->decode_waves = value;
       return MIXATTN_OK;
+    case MIXATTN_PARAM_PREFILL_WAVES:
+      if (value != 0 && value != 4 && value != 8) return MIXATTN_ERR_PARAM;
+      L->prefill_waves = value;
+      return MIXATTN_OK;
     default: return MIXATTN_ERR_PARAM;
   }
 }
@@ -581,6 +602,7 @@ int mixattn_get_param(const mixattn_layout* L, int param, int64_t* value) {
     case MIXATTN_PARAM_FUSED_COMBINE: *value = L->fused_combine; return MIXATTN_OK;
     case MIXATTN_PARAM_PREFILL_SIMPLE: *value = L->prefill_simple; return MIXATTN_OK;
     case MIXATTN_PARAM_DECODE_WAVES: *value = L->decode_waves; return MIXATTN_OK;
+    case MIXATTN_PARAM_PREFILL_WAVES: *value = L->prefill_waves; return MIXATTN_OK;
     default: return MIXATTN_ERR_PARAM;
   }
 }

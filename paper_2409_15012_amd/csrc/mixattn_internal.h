@@ -76,6 +76,8 @@ struct mixattn_layout {
   void* stageK = nullptr;
   void* stageV = nullptr;
   int64_t stage_blocks = 0;  // blocks per (b, h) currently allocated
+  int stage_cache = -1;      // cache whose prompt the staging area holds (-1: none)
+  int stage_len = 0;         // its prompt length
   int64_t* d_stage_base = nullptr;   // [batch] geometry tables of the staging area
   int32_t* d_stage_slots = nullptr;  // [batch]
   int32_t* d_stage_lens = nullptr;  // [batch] device copy of seq_lens for load_kv / prefill commits
@@ -86,6 +88,7 @@ struct mixattn_layout {
   int64_t fused_combine = 0;
   int64_t prefill_simple = 0;
   int64_t decode_waves = 0;  // 0 = automatic
+  int64_t prefill_waves = 0; // 0 = automatic
   int device = 0;
   int n_cus = 256;
 };
@@ -152,6 +155,7 @@ struct PrefillLaunch {
   int batch, S, Hq, Hkv, G, D;
   int kv_dtype, out_dtype;
   float scale;
+  int waves;  // wavefronts per workgroup on the tiled path: 4, 8, or 0 = default (4)
 };
 hipError_t launch_prefill_tiled(const PrefillLaunch& a, hipStream_t s);
 hipError_t launch_prefill_rowmajor(const PrefillLaunch& a, hipStream_t s);

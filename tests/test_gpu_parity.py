@@ -158,7 +158,14 @@ def test_bf16_prefill_then_decode_against_oracle(mx, S, W, Hq, Hkv, B, simple):
                       wl.randn(seed + 50 + li, (B, S, Hkv, d), torch.bfloat16, DEV))
         q = wl.randn(seed + 100 + li, (B, S, Hq, d), torch.bfloat16, DEV)
         k, v = kv[wr]
-        out = lay.prefill(li, q, k, v)
+        if wr != li and not simple and li == wr + 1:
+            out = lay.prefill(li, q, None, None)  # reader right after its writer: reuse the staged prompt
+        else:
+            if wr != li and not simple:
+                with pytest.raises(mx.MixAttnError) as ei:  # another group's prompt is staged by now
+                    lay.prefill(li, q, None, None)
+                assert ei.value.status == -6
+            out = lay.prefill(li, q, k, v)
         ref = ora.prefill(li, to_f64(q), to_f64(k) if wr == li else None, to_f64(v) if wr == li else None)
         assert_matches(out, ref, "bf16", "prefill layer %d" % li)
     for li in (0, 1, 4):
