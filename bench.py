@@ -3,8 +3,8 @@
 
 Default workload ("decode32k"): the 24-layer MixAttention stack (layers 0 and 12 full, 22 sliding-window layers
 W = 1024 in six sharing groups), bf16, batch 32, 32768 tokens of context per sequence.  One step = the whole hot
-path for one generated token per sequence: 8 KV appends (writer layers) + 24 decode attentions, with every input
-already resident in HBM.  Prints ONE JSON line (see README for the fields).
+path for one generated token per sequence: 8 KV appends (writer layers, fused into their decode launch unless
+--two-call-append) + 24 decode attentions, with every input already resident in HBM.  Prints ONE JSON line (see README for the fields).
 
 Other workloads (--workload): decode4k (batch 8, context 4096), prefill32k (batch 1, 32768-token prompt through
 the 24 layers), ragged64 (batch 64, context lengths uniform in [1024, 65536], MixAttention stack next to the
@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--chunk-keys", type=int, default=0)
     ap.add_argument("--fused-combine", type=int, default=-1)
     ap.add_argument("--prefill-waves", type=int, default=0)
+    ap.add_argument("--two-call-append", action="store_true",
+                    help="writer layers call append_kv and decode separately instead of append_decode")
     ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
     ap.add_argument("--only", default="", help="profiling aid: 'full' or 'sliding' runs only that layer kind per step")
     ap.add_argument("--copy-calibration", type=int, default=0,
@@ -109,19 +111,24 @@ def run_decode(args, mx, wl, torch, w, layers=None, label=None):
 
     def step(events=None):
         for li in range(len(layers)):
-            if ks[li] is not None:
+            skip = kinds is not None and layers[li][0] != kinds
+            fused = ks[li] is not None and not args.two_call_append and not skip
+            if ks[li] is not None and not fused:
                 lay.append_kv(li, ks[li], vs[li])
-            if kinds is not None and layers[li][0] != kinds:
+            if skip:
                 continue
-            if events is not None and li in full_layers:
+            timed = events is not None and li in full_layers
+            if timed:
                 e0 = torch.cuda.Event(enable_timing=True)
                 e1 = torch.cuda.Event(enable_timing=True)
                 e0.record()
-                lay.decode(li, qs[li], out)
-                e1.record()
-                events.append((li, e0, e1))
+            if fused:
+                lay.append_decode(li, ks[li], vs[li], qs[li], out)
             else:
                 lay.decode(li, qs[li], out)
+            if timed:
+                e1.record()
+                events.append((li, e0, e1))
 
     for _ in range(args.warmup):
         step()

@@ -119,6 +119,12 @@ int mixattn_append_kv(mixattn_layout* L, int layer, const void* k, const void* v
    sequence is empty. */
 int mixattn_decode(mixattn_layout* L, int layer, const void* q, void* out, void* stream);
 
+/* mixattn_append_kv followed by mixattn_decode on the same (writer) layer, as one call: same arguments, same
+   result, same errors (NOT_WRITER, CAPACITY, NULL).  On the MFMA path (bf16, head_dim 128) it is a single launch:
+   the decode kernel takes this step's token from k, v directly and stores it to the cache on the way. */
+int mixattn_append_decode(mixattn_layout* L, int layer, const void* k, const void* v, const void* q, void* out,
+                          void* stream);
+
 /* Prompt attention on empty caches (causal; SLIDING layers also mask keys more than window-1 tokens back).
    Writer layer: k, v are its prompt keys/values; they are attended over and committed to its cache (FULL: all
    seq_len positions; SLIDING: the last min(seq_len, window) positions, each at slot p mod window) and every
@@ -166,8 +172,7 @@ typedef enum {
   MIXATTN_PARAM_FUSED_COMBINE = 1, /* 1: the last workgroup of a (sequence, kv head) merges the split-K partials
                                       itself; 0: separate combine launch */
   MIXATTN_PARAM_PREFILL_SIMPLE = 2, /* 1: force the scalar prefill kernel (testing) */
-  MIXATTN_PARAM_DECODE_WAVES = 3,   /* wavefronts per decode workgroup: 4, 8, or 0 = automatic */
-  MIXATTN_PARAM_PREFILL_WAVES = 4   /* wavefronts per MFMA prefill workgroup: 4, 8, or 0 = default (4) */
+  MIXATTN_PARAM_PREFILL_WAVES = 3   /* wavefronts per MFMA prefill workgroup: 4, 8, or 0 = default (4) */
 } mixattn_param;
 int mixattn_set_param(mixattn_layout* L, int param, int64_t value);
 int mixattn_get_param(const mixattn_layout* L, int param, int64_t* value);

@@ -18,11 +18,11 @@ _lib = None
 
 FULL, SLIDING = 0, 1
 F32, BF16 = 0, 1
-PARAM_CHUNK_KEYS, PARAM_FUSED_COMBINE, PARAM_PREFILL_SIMPLE, PARAM_DECODE_WAVES, PARAM_PREFILL_WAVES = 0, 1, 2, 3, 4
+PARAM_CHUNK_KEYS, PARAM_FUSED_COMBINE, PARAM_PREFILL_SIMPLE, PARAM_PREFILL_WAVES = 0, 1, 2, 3
 
 EXPORTS = [
     "mixattn_validate_config", "mixattn_create_layout", "mixattn_destroy_layout", "mixattn_reset",
-    "mixattn_append_kv", "mixattn_decode", "mixattn_prefill", "mixattn_load_kv", "mixattn_n_caches",
+    "mixattn_append_kv", "mixattn_decode", "mixattn_append_decode", "mixattn_prefill", "mixattn_load_kv", "mixattn_n_caches",
     "mixattn_cache_of", "mixattn_seq_len", "mixattn_slot_of", "mixattn_slot_for", "mixattn_read_cache",
     "mixattn_read_device_lens", "mixattn_kv_bytes_allocated", "mixattn_kv_bytes_live", "mixattn_step_read_bytes",
     "mixattn_set_param", "mixattn_get_param", "mixattn_strerror", "mixattn_last_hip_error", "mixattn_version",
@@ -64,6 +64,7 @@ def load():
     lib.mixattn_reset.argtypes = [vp, vp]
     lib.mixattn_append_kv.argtypes = [vp, i32, vp, vp, vp]
     lib.mixattn_decode.argtypes = [vp, i32, vp, vp, vp]
+    lib.mixattn_append_decode.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     lib.mixattn_prefill.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
     lib.mixattn_load_kv.argtypes = [vp, i32, vp, vp, C.POINTER(C.c_int32), vp]
     lib.mixattn_n_caches.argtypes = [vp]
@@ -187,6 +188,19 @@ class Layout:
         else:
             self._dtype_check(out, self.out_torch, (self.batch, self.Hq, self.d))
         self._check(self.lib.mixattn_decode(self.h, layer, _ptr(q), _ptr(out), _stream()), "mixattn_decode")
+        return out
+
+    def append_decode(self, layer: int, k: torch.Tensor, v: torch.Tensor, q: torch.Tensor,
+                      out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        self._dtype_check(k, self.kv_torch, (self.batch, self.Hkv, self.d))
+        self._dtype_check(v, self.kv_torch, (self.batch, self.Hkv, self.d))
+        self._dtype_check(q, self.kv_torch, (self.batch, self.Hq, self.d))
+        if out is None:
+            out = torch.empty((self.batch, self.Hq, self.d), dtype=self.out_torch, device=q.device)
+        else:
+            self._dtype_check(out, self.out_torch, (self.batch, self.Hq, self.d))
+        self._check(self.lib.mixattn_append_decode(self.h, layer, _ptr(k), _ptr(v), _ptr(q), _ptr(out), _stream()),
+                    "mixattn_append_decode")
         return out
 
     def prefill(self, layer: int, q: torch.Tensor, k: Optional[torch.Tensor], v: Optional[torch.Tensor],

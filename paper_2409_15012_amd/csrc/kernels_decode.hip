@@ -38,6 +38,8 @@ template <>
 __device__ inline void store_out<uint16_t>(uint16_t* p, float v) { *p = (uint16_t)bf16_bits_rn(v); }
 
 
+constexpr int kDecodeWaves = 4;
+
 struct TiledDecodeParams {
   const uint16_t* K; const uint16_t* V;
   const int64_t* d_base; const int32_t* d_slots; const int32_t* d_lens;
@@ -48,6 +50,8 @@ struct TiledDecodeParams {
   int chunk_blocks, n_chunks;
   int fused_combine;
   float* p_acc; float* p_ml; uint32_t* counters;
+  // fused append (writer layers): this step's token, writable cache pointers, length array to receive n + 1
+  const uint16_t* k_new; const uint16_t* v_new; uint16_t* Kw; uint16_t* Vw; int32_t* d_lens_out;
 };
 
 // merges the split-K partials of one (sequence, query head): thread d handles one output dim
@@ -65,13 +69,20 @@ __device__ inline void merge_partials(const float* p_acc, const float* p_ml, int
 }
 
 // RING selects the sliding-window instantiation (reads min(n, window) ring slots); it is a template parameter so
-// that the two layer kinds are separate kernels in a profile.  NW = wavefronts per workgroup (4 or 8): wave w
-// takes blocks w, w + NW, ... of the chunk.
-template <typename OutT, bool RING, int NW>
-__global__ __launch_bounds__(NW * 64, 2) void decode_tiled_kernel(TiledDecodeParams a) {
+// that the two layer kinds are separate kernels in a profile.  Wave w takes blocks w, w + 4, ... of the chunk.
+// FUSED: the launch also appends this step's token (k_new, v_new) of a writer layer: the sequence is one token
+// longer than the length array says, the wavefront that owns the token's block patches it into the loaded
+// fragments, stores it to the cache for later launches, and writes the new length to a second length array
+// (the old one is still being read by other workgroups of this launch).
+template <typename OutT, bool RING, bool FUSED>
+__global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(TiledDecodeParams a) {
+  constexpr int NW = kDecodeWaves;
   const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  int n = a.d_lens[b];
+  const int n_old = a.d_lens[b];
+  int n = FUSED ? n_old + 1 : n_old;
   if (RING && n > a.window) n = a.window;
+  const int new_slot = RING ? n_old % a.window : n_old;  // where a fused launch puts its token
+  const int new_blk = new_slot >> 5, new_key = new_slot & 31;
   const int nb_total = (n + kBlockKeys - 1) / kBlockKeys;
   // this sequence's blocks are cut into n_chunks_b chunks of equal length (+-1 block), so that workgroups of one
   // sequence finish together and a sequence a little longer than a multiple of the target does not grow a stub
@@ -187,23 +198,72 @@ __global__ __launch_bounds__(NW * 64, 2) void decode_tiled_kernel(TiledDecodePar
   // Software pipeline over this wavefront's blocks blk0 + wave + 4*i, i < cnt.  The steady-state loop issues the
   // next block's loads unconditionally before it consumes the current one, so the wait before the MFMAs only
   // covers the older of the two blocks in flight; the last one or two blocks are peeled.
-  const int cnt = (blk1 - blk0 - wave + NW - 1) / NW;  // may be <= 0
+  // A fused launch takes the block that receives the new token out of this sequence (the wavefront that owns it
+  // handles it after the pipeline, see below), so the steady-state loop stays free of conditional loads.
+  const int first = blk0 + wave;
+  const bool own_new = FUSED && new_blk >= blk0 && new_blk < blk1 && ((new_blk - blk0) & (NW - 1)) == wave;
+  const int i_new = own_new ? (new_blk - first) / NW : 0x7fffffff;
+  const int cnt = (blk1 - blk0 - wave + NW - 1) / NW - (own_new ? 1 : 0);  // may be <= 0
+  auto blk_of = [&](int i) { return first + (i + (i >= i_new ? 1 : 0)) * NW; };
   if (cnt > 0) {
-    const int first = blk0 + wave;
-    load_block(first, kr[0], vr[0]);
+    load_block(blk_of(0), kr[0], vr[0]);
     int i = 0;
     for (; i + 2 < cnt; i += 2) {
-      load_block(first + (i + 1) * NW, kr[1], vr[1]);
-      compute_block(no_tail{}, first + i * NW, kr[0], vr[0]);
-      load_block(first + (i + 2) * NW, kr[0], vr[0]);
-      compute_block(no_tail{}, first + (i + 1) * NW, kr[1], vr[1]);
+      load_block(blk_of(i + 1), kr[1], vr[1]);
+      compute_block(no_tail{}, blk_of(i), kr[0], vr[0]);
+      load_block(blk_of(i + 2), kr[0], vr[0]);
+      compute_block(no_tail{}, blk_of(i + 1), kr[1], vr[1]);
     }
     if (i + 1 < cnt) {
-      load_block(first + (i + 1) * NW, kr[1], vr[1]);
-      compute_block(no_tail{}, first + i * NW, kr[0], vr[0]);
-      compute_last(first + (i + 1) * NW, kr[1], vr[1]);
+      load_block(blk_of(i + 1), kr[1], vr[1]);
+      compute_block(no_tail{}, blk_of(i), kr[0], vr[0]);
+      compute_last(blk_of(i + 1), kr[1], vr[1]);
     } else {
-      compute_last(first + i * NW, kr[0], vr[0]);
+      compute_last(blk_of(i), kr[0], vr[0]);
+    }
+  }
+  if constexpr (FUSED) {
+    if (own_new) {
+      load_block(new_blk, kr[0], vr[0]);
+      const uint16_t* kn = a.k_new + ((int64_t)b * a.Hkv + h) * kTiledDim;
+      const uint16_t* vn = a.v_new + ((int64_t)b * a.Hkv + h) * kTiledDim;
+      // K fragments: lanes of MFMA row new_key % 16 take the token's dims kk*32 + g*8 .. +7 in key tile new_key / 16
+      {
+        const bool mine = col == (new_key & 15);
+        const bool t1 = (new_key >> 4) != 0;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          const u32x4_t val = *(const u32x4_t*)(kn + kk * 32 + g * 8);
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            kr[0][kk][w] = (mine && !t1) ? val[w] : kr[0][kk][w];
+            kr[0][4 + kk][w] = (mine && t1) ? val[w] : kr[0][4 + kk][w];
+          }
+        }
+      }
+      // V fragments: lanes of key group (new_key % 16) / 4 hold the token as element j of every dim fragment
+      {
+        const bool mine = g == ((new_key & 15) >> 2);
+        const int j = 4 * (new_key >> 4) + (new_key & 3);
+        const uint32_t half_mask = (j & 1) ? 0xffff0000u : 0x0000ffffu;
+#pragma unroll
+        for (int nn = 0; nn < 8; ++nn) {
+          const uint32_t val = (uint32_t)vn[nn * 16 + col] << ((j & 1) * 16);
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            const uint32_t msk = (mine && w == (j >> 1)) ? half_mask : 0u;
+            vr[0][nn][w] = (vr[0][nn][w] & ~msk) | (val & msk);
+          }
+        }
+      }
+      compute_last(new_blk, kr[0], vr[0]);
+      // the token goes to the cache for the launches that follow (no other wavefront of this launch reads the block)
+      uint16_t* Kd = a.Kw + (first_blk + new_blk) * kBlockElems;
+      uint16_t* Vd = a.Vw + (first_blk + new_blk) * kBlockElems;
+      if (lane < 16) *(u32x4_t*)(Kd + k_tile_offset(new_key, lane * 8)) = *(const u32x4_t*)(kn + lane * 8);
+      Vd[v_tile_offset(new_key, lane)] = vn[lane];
+      Vd[v_tile_offset(new_key, lane + 64)] = vn[lane + 64];
+      if (h == 0 && lane == 0) a.d_lens_out[b] = n_old + 1;
     }
   }
 
@@ -280,7 +340,7 @@ __global__ __launch_bounds__(NW * 64, 2) void decode_tiled_kernel(TiledDecodePar
 template <typename OutT>
 __global__ __launch_bounds__(kTiledDim) void combine_kernel(TiledDecodeParams a) {
   const int hq = blockIdx.x, b = blockIdx.y;
-  int n = a.d_lens[b];
+  int n = a.d_lens[b] + (a.k_new ? 1 : 0);  // the fused launch before this one read the old length array
   if (a.window > 0 && n > a.window) n = a.window;
   const int nb_total = (n + kBlockKeys - 1) / kBlockKeys;
   const int n_chunks_b = (nb_total + a.chunk_blocks - 1) / a.chunk_blocks;
@@ -300,20 +360,22 @@ hipError_t launch_decode_tiled(const DecodeLaunch& L, hipStream_t s) {
   p.chunk_blocks = L.chunk_blocks; p.n_chunks = L.n_chunks;
   p.fused_combine = L.fused_combine;
   p.p_acc = L.scratch.acc; p.p_ml = L.scratch.ml; p.counters = L.scratch.counters;
+  p.k_new = (const uint16_t*)L.k_new; p.v_new = (const uint16_t*)L.v_new;
+  p.Kw = (uint16_t*)L.K; p.Vw = (uint16_t*)L.V; p.d_lens_out = L.d_lens_out;
   const dim3 grid(L.n_chunks, L.Hkv, L.batch);
-  const bool f32 = L.out_dtype == MIXATTN_F32, ring = L.window > 0;
-#define MIXATTN_LAUNCH_DECODE(OUT, RING, NW) \
-  hipLaunchKernelGGL((decode_tiled_kernel<OUT, RING, NW>), grid, dim3(NW * 64), 0, s, p)
-  if (L.waves == 8) {
-    if (f32 && ring) MIXATTN_LAUNCH_DECODE(float, true, 8);
-    else if (f32) MIXATTN_LAUNCH_DECODE(float, false, 8);
-    else if (ring) MIXATTN_LAUNCH_DECODE(uint16_t, true, 8);
-    else MIXATTN_LAUNCH_DECODE(uint16_t, false, 8);
+  const bool f32 = L.out_dtype == MIXATTN_F32, ring = L.window > 0, fused = L.k_new != nullptr;
+#define MIXATTN_LAUNCH_DECODE(OUT, RING, FUSED) \
+  hipLaunchKernelGGL((decode_tiled_kernel<OUT, RING, FUSED>), grid, dim3(kDecodeWaves * 64), 0, s, p)
+  if (fused) {
+    if (f32 && ring) MIXATTN_LAUNCH_DECODE(float, true, true);
+    else if (f32) MIXATTN_LAUNCH_DECODE(float, false, true);
+    else if (ring) MIXATTN_LAUNCH_DECODE(uint16_t, true, true);
+    else MIXATTN_LAUNCH_DECODE(uint16_t, false, true);
   } else {
-    if (f32 && ring) MIXATTN_LAUNCH_DECODE(float, true, 4);
-    else if (f32) MIXATTN_LAUNCH_DECODE(float, false, 4);
-    else if (ring) MIXATTN_LAUNCH_DECODE(uint16_t, true, 4);
-    else MIXATTN_LAUNCH_DECODE(uint16_t, false, 4);
+    if (f32 && ring) MIXATTN_LAUNCH_DECODE(float, true, false);
+    else if (f32) MIXATTN_LAUNCH_DECODE(float, false, false);
+    else if (ring) MIXATTN_LAUNCH_DECODE(uint16_t, true, false);
+    else MIXATTN_LAUNCH_DECODE(uint16_t, false, false);
   }
 #undef MIXATTN_LAUNCH_DECODE
   hipError_t e = hipGetLastError();

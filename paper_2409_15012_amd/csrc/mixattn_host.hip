@@ -177,14 +177,16 @@ int mixattn_create_layout(const mixattn_config* cfg, mixattn_layout** out) {
   }
   const int B = L->batch;
   const int nc = (int)L->caches.size();
-  st = dev_alloc((void**)&L->d_lens_all, sizeof(int32_t) * (size_t)nc * B);
-  if (st == MIXATTN_OK && !hip_ok(hipMemset(L->d_lens_all, 0, sizeof(int32_t) * (size_t)nc * B))) st = MIXATTN_ERR_HIP;
+  st = dev_alloc((void**)&L->d_lens_all, sizeof(int32_t) * (size_t)nc * 2 * B);
+  if (st == MIXATTN_OK && !hip_ok(hipMemset(L->d_lens_all, 0, sizeof(int32_t) * (size_t)nc * 2 * B))) st = MIXATTN_ERR_HIP;
   for (int ci = 0; ci < nc && st == MIXATTN_OK; ++ci) {
     Cache& c = L->caches[ci];
     c.base.resize(B);
     c.slots.resize(B);
     c.len.assign(B, 0);
-    c.d_lens = L->d_lens_all + (size_t)ci * B;
+    c.d_lens2[0] = L->d_lens_all + (size_t)ci * 2 * B;
+    c.d_lens2[1] = c.d_lens2[0] + B;
+    c.cur = 0;
     int64_t run = 0;  // blocks (tiled) or rows (row-major) before sequence b
     for (int b = 0; b < B; ++b) {
       const int64_t want = c.kind == MIXATTN_SLIDING ? c.window : L->capacity[b];
@@ -239,7 +241,7 @@ int mixattn_destroy_layout(mixattn_layout* L) {
 
 int mixattn_reset(mixattn_layout* L, void* stream) {
   if (!L) return MIXATTN_ERR_NULL;
-  HIP_TRY(launch_fill_i32(L->d_lens_all, 0, (int64_t)L->caches.size() * L->batch, (hipStream_t)stream));
+  HIP_TRY(launch_fill_i32(L->d_lens_all, 0, (int64_t)L->caches.size() * 2 * L->batch, (hipStream_t)stream));
   for (auto& c : L->caches) std::fill(c.len.begin(), c.len.end(), 0);
   L->stage_cache = -1;
   return MIXATTN_OK;
@@ -256,7 +258,7 @@ int mixattn_append_kv(mixattn_layout* L, int layer, const void* k, const void* v
   for (int b = 0; b < L->batch; ++b)
     if (c.len[b] + 1 > INT32_MAX) return MIXATTN_ERR_CAPACITY;
   AppendLaunch a;
-  a.K = c.K; a.V = c.V; a.d_base = c.d_base; a.d_slots = c.d_slots; a.d_lens = c.d_lens;
+  a.K = c.K; a.V = c.V; a.d_base = c.d_base; a.d_slots = c.d_slots; a.d_lens = c.lens();
   a.window = c.window; a.k = k; a.v = v;
   a.batch = L->batch; a.Hkv = L->Hkv; a.D = L->D; a.elem = L->elem;
   HIP_TRY(L->tiled ? launch_append_tiled(a, (hipStream_t)stream) : launch_append_rowmajor(a, (hipStream_t)stream));
@@ -270,14 +272,14 @@ int mixattn_append_kv(mixattn_layout* L, int layer, const void* k, const void* v
 // rate of one workgroup, whose four wavefronts keep 128 KiB in flight and so advance by one 16 KiB block in
 // about 0.6 us under load.  Cutting sequences shortens the second bound but costs a combine launch (about 5 us);
 // with two workgroups resident per CU, chunks run in rounds of 2 * CUs.
-static int plan_chunk_blocks(const mixattn_layout* L, const Cache& c, int max_blocks) {
+static int plan_chunk_blocks(const mixattn_layout* L, const Cache& c, int max_blocks, int extra) {
   const double slots = 2.0 * L->n_cus;
   const double us_per_block_bw = 2.0 * kBlockElems * 2 / 7.0e6;  // 16 KiB at 7.0 TB/s
   const double us_per_block_wg = 0.6, us_wg_fixed = 1.0, us_combine = 5.0;
   std::vector<int> nb(L->batch);
   double total_blocks = 0;
   for (int b = 0; b < L->batch; ++b) {
-    const int64_t n = c.window > 0 ? std::min<int64_t>(c.len[b], c.window) : c.len[b];
+    const int64_t n = c.window > 0 ? std::min<int64_t>(c.len[b] + extra, c.window) : c.len[b] + extra;
     nb[b] = (int)((n + kBlockKeys - 1) / kBlockKeys);
     total_blocks += (double)nb[b] * L->Hkv;
   }
@@ -307,26 +309,28 @@ static int plan_chunk_blocks(const mixattn_layout* L, const Cache& c, int max_bl
   return std::max(best_t, 1);
 }
 
-int mixattn_decode(mixattn_layout* L, int layer, const void* q, void* out, void* stream) {
-  if (!L || !q || !out) return MIXATTN_ERR_NULL;
-  if (layer < 0 || layer >= L->n_layers) return MIXATTN_ERR_LAYER;
-  const Cache& c = L->caches[L->layer_cache[layer]];
+// Decode launch shared by mixattn_decode and mixattn_append_decode.  `extra` = 1 when a fused launch appends this
+// step's token itself (lengths on host and device still hold the old value while planning).
+static int launch_decode(mixattn_layout* L, Cache& c, const void* q, void* out, const void* k_new,
+                         const void* v_new, hipStream_t stream) {
+  const int extra = k_new ? 1 : 0;
   int64_t max_n = 0;
   for (int b = 0; b < L->batch; ++b) {
-    if (c.len[b] < 1) return MIXATTN_ERR_ORDER;
-    const int64_t n = c.window > 0 ? std::min<int64_t>(c.len[b], c.window) : c.len[b];
+    const int64_t len = c.len[b] + extra;
+    const int64_t n = c.window > 0 ? std::min<int64_t>(len, c.window) : len;
     max_n = std::max(max_n, n);
   }
   DecodeLaunch a;
-  a.K = c.K; a.V = c.V; a.d_base = c.d_base; a.d_slots = c.d_slots; a.d_lens = c.d_lens;
+  a.K = c.K; a.V = c.V; a.d_base = c.d_base; a.d_slots = c.d_slots; a.d_lens = c.lens();
   a.window = c.window; a.q = q; a.out = out;
   a.batch = L->batch; a.Hq = L->Hq; a.Hkv = L->Hkv; a.G = L->G; a.D = L->D;
   a.kv_dtype = L->kv_dtype; a.out_dtype = L->out_dtype; a.scale = L->scale;
   a.scratch = L->scratch;
   a.fused_combine = (int)L->fused_combine;
+  a.k_new = k_new; a.v_new = v_new; a.d_lens_out = k_new ? c.lens_other() : nullptr;
   if (!L->tiled) {
     a.max_blocks = a.chunk_blocks = a.n_chunks = 0;
-    HIP_TRY(launch_decode_rowmajor(a, (hipStream_t)stream));
+    HIP_TRY(launch_decode_rowmajor(a, stream));
     return MIXATTN_OK;
   }
   const int max_blocks = (int)((max_n + kBlockKeys - 1) / kBlockKeys);
@@ -334,18 +338,49 @@ int mixattn_decode(mixattn_layout* L, int layer, const void* q, void* out, void*
   if (L->chunk_keys > 0) {
     chunk_blocks = (int)(L->chunk_keys / kBlockKeys);
   } else {
-    chunk_blocks = plan_chunk_blocks(L, c, max_blocks);
+    chunk_blocks = plan_chunk_blocks(L, c, max_blocks, extra);
   }
   chunk_blocks = std::max(chunk_blocks, (max_blocks + kMaxChunks - 1) / kMaxChunks);
   a.max_blocks = max_blocks;
   a.chunk_blocks = chunk_blocks;
   a.n_chunks = (max_blocks + chunk_blocks - 1) / chunk_blocks;
-  if (L->decode_waves > 0) {
-    a.waves = (int)L->decode_waves;
-  } else {
-    a.waves = 4;  // eight wavefronts per workgroup measured no faster at any shape tried
+  HIP_TRY(launch_decode_tiled(a, stream));
+  return MIXATTN_OK;
+}
+
+int mixattn_decode(mixattn_layout* L, int layer, const void* q, void* out, void* stream) {
+  if (!L || !q || !out) return MIXATTN_ERR_NULL;
+  if (layer < 0 || layer >= L->n_layers) return MIXATTN_ERR_LAYER;
+  Cache& c = L->caches[L->layer_cache[layer]];
+  for (int b = 0; b < L->batch; ++b)
+    if (c.len[b] < 1) return MIXATTN_ERR_ORDER;
+  return launch_decode(L, c, q, out, nullptr, nullptr, (hipStream_t)stream);
+}
+
+static int check_append(const mixattn_layout* L, const Cache& c, int layer) {
+  if (c.writer != layer) return MIXATTN_ERR_NOT_WRITER;
+  for (int b = 0; b < L->batch; ++b) {
+    if (c.kind == MIXATTN_FULL && c.len[b] + 1 > L->capacity[b]) return MIXATTN_ERR_CAPACITY;
+    if (c.len[b] + 1 > INT32_MAX) return MIXATTN_ERR_CAPACITY;
   }
-  HIP_TRY(launch_decode_tiled(a, (hipStream_t)stream));
+  return MIXATTN_OK;
+}
+
+int mixattn_append_decode(mixattn_layout* L, int layer, const void* k, const void* v, const void* q, void* out,
+                          void* stream) {
+  if (!L || !k || !v || !q || !out) return MIXATTN_ERR_NULL;
+  if (layer < 0 || layer >= L->n_layers) return MIXATTN_ERR_LAYER;
+  Cache& c = L->caches[L->layer_cache[layer]];
+  int st = check_append(L, c, layer);
+  if (st != MIXATTN_OK) return st;
+  if (!L->tiled) {  // row-major path: the two launches, one after the other
+    st = mixattn_append_kv(L, layer, k, v, stream);
+    return st != MIXATTN_OK ? st : mixattn_decode(L, layer, q, out, stream);
+  }
+  st = launch_decode(L, c, q, out, k, v, (hipStream_t)stream);
+  if (st != MIXATTN_OK) return st;
+  c.cur ^= 1;  // the launch wrote n + 1 into the other length array
+  for (int b = 0; b < L->batch; ++b) c.len[b] += 1;
   return MIXATTN_OK;
 }
 
@@ -410,7 +445,7 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
     const bool simple = L->prefill_simple != 0;  // scalar kernel on the caller's tensors (cross-check path)
     if (c.kind == MIXATTN_FULL && writer) {
       st.K = c.K; st.V = c.V; st.d_base = c.d_base; st.d_slots = c.d_slots; st.window = 0;
-      st.d_lens_out = c.d_lens; st.max_slots = seq_len;
+      st.d_lens_out = c.lens(); st.max_slots = seq_len;
       HIP_TRY(launch_store_tiled(st, s));
     }
     if (simple) {
@@ -441,14 +476,14 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
     }
     if (writer && c.kind == MIXATTN_SLIDING) {
       st.K = c.K; st.V = c.V; st.d_base = c.d_base; st.d_slots = c.d_slots; st.window = c.window;
-      st.d_lens_out = c.d_lens; st.max_slots = std::min(seq_len, c.window);
+      st.d_lens_out = c.lens(); st.max_slots = std::min(seq_len, c.window);
       HIP_TRY(launch_store_tiled(st, s));
     }
   } else {
     HIP_TRY(launch_prefill_rowmajor(p, s));
     if (writer) {
       st.K = c.K; st.V = c.V; st.d_base = c.d_base; st.d_slots = c.d_slots; st.window = c.window;
-      st.d_lens_out = c.d_lens; st.max_slots = c.window > 0 ? std::min(seq_len, c.window) : seq_len;
+      st.d_lens_out = c.lens(); st.max_slots = c.window > 0 ? std::min(seq_len, c.window) : seq_len;
       HIP_TRY(launch_store_rowmajor(st, s));
     }
   }
@@ -484,7 +519,7 @@ int mixattn_load_kv(mixattn_layout* L, int layer, const void* k, const void* v, 
   StoreLaunch st;
   st.K = c.K; st.V = c.V; st.d_base = c.d_base; st.d_slots = c.d_slots; st.window = c.window;
   st.k_src = k; st.v_src = v; st.d_src_first = L->d_stage_src; st.d_src_len = L->d_stage_lens; st.uniform_len = 0;
-  st.d_lens_out = c.d_lens;
+  st.d_lens_out = c.lens();
   st.batch = L->batch; st.Hkv = L->Hkv; st.D = L->D; st.elem = L->elem;
   st.max_slots = std::max(1, c.window > 0 ? std::min(max_len, c.window) : max_len);
   HIP_TRY(L->tiled ? launch_store_tiled(st, s) : launch_store_rowmajor(st, s));
@@ -540,7 +575,7 @@ int mixattn_read_device_lens(mixattn_layout* L, int cache_index, int32_t* lens) 
   if (!L || !lens) return MIXATTN_ERR_NULL;
   if (cache_index < 0 || cache_index >= (int)L->caches.size()) return MIXATTN_ERR_LAYER;
   HIP_TRY(hipDeviceSynchronize());
-  HIP_TRY(hipMemcpy(lens, L->caches[cache_index].d_lens, sizeof(int32_t) * L->batch, hipMemcpyDeviceToHost));
+  HIP_TRY(hipMemcpy(lens, L->caches[cache_index].lens(), sizeof(int32_t) * L->batch, hipMemcpyDeviceToHost));
   return MIXATTN_OK;
 }
 
@@ -583,10 +618,6 @@ int mixattn_set_param(mixattn_layout* L, int param, int64_t value) {
       if (value != 0 && value != 1) return MIXATTN_ERR_PARAM;
       L->prefill_simple = value;
       return MIXATTN_OK;
-    case MIXATTN_PARAM_DECODE_WAVES:
-      if (value != 0 && value != 4 && value != 8) return MIXATTN_ERR_PARAM;
-      L->decode_waves = value;
-      return MIXATTN_OK;
     case MIXATTN_PARAM_PREFILL_WAVES:
       if (value != 0 && value != 4 && value != 8) return MIXATTN_ERR_PARAM;
       L->prefill_waves = value;
@@ -601,7 +632,6 @@ int mixattn_get_param(const mixattn_layout* L, int param, int64_t* value) {
     case MIXATTN_PARAM_CHUNK_KEYS: *value = L->chunk_keys; return MIXATTN_OK;
     case MIXATTN_PARAM_FUSED_COMBINE: *value = L->fused_combine; return MIXATTN_OK;
     case MIXATTN_PARAM_PREFILL_SIMPLE: *value = L->prefill_simple; return MIXATTN_OK;
-    case MIXATTN_PARAM_DECODE_WAVES: *value = L->decode_waves; return MIXATTN_OK;
     case MIXATTN_PARAM_PREFILL_WAVES: *value = L->prefill_waves; return MIXATTN_OK;
     default: return MIXATTN_ERR_PARAM;
   }

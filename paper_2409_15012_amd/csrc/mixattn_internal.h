@@ -47,7 +47,12 @@ struct Cache {
   std::vector<int32_t> slots;  // slots per (b, h): capacity rounded up to 32 (tiled) / capacity (row-major)
   int64_t* d_base = nullptr;
   int32_t* d_slots = nullptr;
-  int32_t* d_lens = nullptr;   // device, [batch] (points into Layout::d_lens_all)
+  // device lengths, [batch], two copies in Layout::d_lens_all: kernels read lens(); a fused append+decode launch
+  // writes the other copy and the host then flips `cur`
+  int32_t* d_lens2[2] = {nullptr, nullptr};
+  int cur = 0;
+  int32_t* lens() const { return d_lens2[cur]; }
+  int32_t* lens_other() const { return d_lens2[cur ^ 1]; }
   std::vector<int64_t> len;    // host mirror
 };
 
@@ -70,7 +75,7 @@ struct mixattn_layout {
   std::vector<int> layer_cache;  // layer -> cache index
   std::vector<mixattn::Cache> caches;
   std::vector<int32_t> capacity;  // [batch] for FULL caches
-  int32_t* d_lens_all = nullptr;  // [n_caches][batch]
+  int32_t* d_lens_all = nullptr;  // [n_caches][2][batch]
   mixattn::DecodeScratch scratch;
   // prompt staging for prefill on the tiled path (grown on demand): V of every layer as fp16, K of sliding layers
   void* stageK = nullptr;
@@ -87,7 +92,6 @@ struct mixattn_layout {
   int64_t chunk_keys = 0;
   int64_t fused_combine = 0;
   int64_t prefill_simple = 0;
-  int64_t decode_waves = 0;  // 0 = automatic
   int64_t prefill_waves = 0; // 0 = automatic
   int device = 0;
   int n_cus = 256;
@@ -107,9 +111,10 @@ struct DecodeLaunch {
   int max_blocks;      // over the batch, ceil(min(n_b, window)/32) (tiled path)
   int chunk_blocks;    // blocks per split-K chunk
   int n_chunks;        // grid.x
-  int waves;           // wavefronts per workgroup: 4 or 8
   int fused_combine;
   DecodeScratch scratch;
+  // fused append (tiled path): this step's k, v [batch, Hkv, D] and the length array that receives n + 1; nullptr = none
+  const void* k_new = nullptr; const void* v_new = nullptr; int32_t* d_lens_out = nullptr;
 };
 hipError_t launch_decode_tiled(const DecodeLaunch& a, hipStream_t s);
 hipError_t launch_decode_rowmajor(const DecodeLaunch& a, hipStream_t s);

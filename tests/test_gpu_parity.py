@@ -303,3 +303,66 @@ def test_error_paths_leave_state_untouched(mx):
     lay.reset()
     assert lay.seq_len(0, 0) == 0 and lay.device_lens(0) == [0]
     lay.close()
+
+
+@pytest.mark.parametrize("Hq,Hkv,W,lens,chunk", [
+    (8, 2, 64, [1, 31, 32, 33, 63, 64, 65, 100, 257, 1000], 0),   # tokens landing first/last in a block, ring wrap
+    (8, 2, 48, [5, 47, 48, 49, 95, 96, 700], 32),                 # window not a multiple of the block
+    (32, 8, 1024, [1023, 1024, 1025, 4095, 4096, 2000], 0),
+    (8, 1, 100, [3000, 99], 256),
+])
+def test_fused_append_decode_against_oracle(mx, Hq, Hkv, W, lens, chunk):
+    """mixattn_append_decode == append + decode: outputs against the oracle, cache rows and lengths bit-exact,
+    and interchangeable with the two-call form from step to step."""
+    B, d = len(lens), 128
+    layers = _mixed_layers(W)
+    steps = 5
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[n + steps for n in lens], kv_dtype="bf16", out_dtype="f32")
+    lay.set_param(mx.PARAM_CHUNK_KEYS, chunk)
+    ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
+    seed = 7000 + Hq * 31 + W
+    for li in range(len(layers)):
+        if lay.writer_of(li) == li:
+            k = wl.randn(seed + li, (sum(lens), Hkv, d), torch.bfloat16, DEV)
+            v = wl.randn(seed + 50 + li, (sum(lens), Hkv, d), torch.bfloat16, DEV)
+            lay.load_kv(li, k, v, lens)
+            ora.load(li, to_f64(k), to_f64(v), lens)
+    for t in range(steps):
+        for li in range(len(layers)):
+            q = wl.randn(seed + 300 + 10 * t + li, (B, Hq, d), torch.bfloat16, DEV)
+            if lay.writer_of(li) == li:
+                k = wl.randn(seed + 100 + 10 * t + li, (B, Hkv, d), torch.bfloat16, DEV)
+                v = wl.randn(seed + 200 + 10 * t + li, (B, Hkv, d), torch.bfloat16, DEV)
+                ora.append(li, to_f64(k), to_f64(v))
+                if t == 3:  # the two-call form in between
+                    lay.append_kv(li, k, v)
+                    out = lay.decode(li, q)
+                else:
+                    out = lay.append_decode(li, k, v, q)
+            else:
+                out = lay.decode(li, q)
+            assert_matches(out, ora.decode(li, to_f64(q)), "bf16", "step %d layer %d" % (t, li))
+        if t in (0, 4):
+            for li in (0, 1, 4):
+                _check_cache(lay, ora, li, heads=[0, Hkv - 1])
+    with pytest.raises(mx.MixAttnError) as ei:
+        lay.append_decode(2, k, v, q)  # reader layer
+    assert ei.value.status == -4
+    lay.close()
+
+
+def test_fused_append_decode_row_major_and_capacity(mx):
+    B, Hq, Hkv, d = 2, 4, 2, 64
+    lay = mx.Layout([(0, 0, 0), (1, 8, 1)], B, Hq, Hkv, d, capacity=[3, 3], kv_dtype="f32", out_dtype="f32")
+    ora = OracleStack([LayerSpec(0, 0, 0), LayerSpec(1, 8, 1)], B, Hq, Hkv, d)
+    for t in range(3):
+        for li in range(2):
+            k = wl.randn(10 * t + li, (B, Hkv, d), torch.float32, DEV)
+            v = wl.randn(100 + 10 * t + li, (B, Hkv, d), torch.float32, DEV)
+            q = wl.randn(200 + 10 * t + li, (B, Hq, d), torch.float32, DEV)
+            ora.append(li, to_f64(k), to_f64(v))
+            assert_matches(lay.append_decode(li, k, v, q), ora.decode(li, to_f64(q)), "f32", "step %d" % t)
+    with pytest.raises(mx.MixAttnError) as ei:
+        lay.append_decode(0, k, v, q)
+    assert ei.value.status == -5 and lay.seq_len(0, 0) == 3 and lay.device_lens(0) == [3, 3]
+    lay.close()
