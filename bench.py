@@ -38,6 +38,7 @@ def parse():
     ap.add_argument("--chunk-keys", type=int, default=0)
     ap.add_argument("--fused-combine", type=int, default=-1)
     ap.add_argument("--prefill-waves", type=int, default=0)
+    ap.add_argument("--skip-standard", action="store_true", help="ragged64: time the MixAttention stack only")
     ap.add_argument("--two-call-append", action="store_true",
                     help="writer layers call append_kv and decode separately instead of append_decode")
     ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
@@ -338,7 +339,7 @@ def main():
     else:  # ragged64
         w = wl.config(4)
         r_mix = run_decode(args, mx, wl, torch, w)
-        r_full = run_decode(args, mx, wl, torch, w, layers=wl.layout_full24())
+        r_full = r_mix if args.skip_standard else run_decode(args, mx, wl, torch, w, layers=wl.layout_full24())
         line = dict(base)
         line.update({
             "metric": "decode tokens/s, ragged batch 64, MixAttention stack (standard 24-layer stack alongside)",
