@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="decode32k", choices=["decode32k", "decode4k", "prefill32k", "ragged64"])
+    ap.add_argument("--workload", default="decode32k", choices=["decode32k", "decode4k", "prefill32k", "ragged64", "variants"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-keys", type=int, default=0)
     ap.add_argument("--fused-combine", type=int, default=-1)
@@ -336,6 +336,27 @@ def main():
                          "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                          "frac": ach / MFMA_BF16_PEAK_TFLOPS, "launch_ms": r["full_layer_ms"], "traffic": None},
         })
+    elif args.workload == "variants":
+        # decode step of several layer layouts at the decode32k shape (batch 32, context 32768): how the mix of
+        # standard / sliding layers and the amount of sharing move KV bytes and step time (Sections 3, 5.1, 5.2)
+        w = wl.config(2)
+        rows = {}
+        for name, layers in [("mix24 (2 full unshared + 22 sliding in 6 groups)", wl.layout_mix24()),
+                             ("ma-like (1 full cache read by 4 layers, sliding pairs)", wl.layout_variant("ma")),
+                             ("ma-offset-like", wl.layout_variant("ma_offset")),
+                             ("ma-pairs-like (2 full caches, each read twice)", wl.layout_variant("ma_pairs")),
+                             ("all sliding, no sharing", wl.layout_variant("sliding")),
+                             ("standard (24 full, no sharing)", wl.layout_full24())]:
+            r = run_decode(args, mx, wl, torch, w, layers=layers)
+            rows[name] = {"ms_per_step": r["ms_per_step"], "tokens_per_s": r["tokens_per_s"],
+                          "kv_bytes_resident": r["kv_bytes_resident"], "kv_bytes_read_per_step": r["kv_bytes_per_step"],
+                          "logical_GBps": r["logical_gbs"], "n_caches": len({c for _, _, c in layers})}
+        base_row = rows["mix24 (2 full unshared + 22 sliding in 6 groups)"]
+        line = dict(base)
+        line.update({"metric": "decode tokens/s by layer layout, batch 32, context 32768", "value": base_row["tokens_per_s"],
+                     "unit": "tokens/s", "ms_per_step": base_row["ms_per_step"],
+                     "config": {"workload": "layout variants at " + w.name, "batch": w.batch, "context": w.context},
+                     "layouts": rows})
     else:  # ragged64
         w = wl.config(4)
         r_mix = run_decode(args, mx, wl, torch, w)
