@@ -66,8 +66,11 @@ template <typename OutT, int NW>
 __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillParams a) {
   constexpr int kPfRows = 32 * NW;  // query rows per workgroup
   // two stages of one 64-key tile each (2 blocks of K, 2 blocks of V), filled by direct global->LDS loads
-  __shared__ __attribute__((aligned(16))) uint16_t sK[2][2 * kBlockElems];
-  __shared__ __attribute__((aligned(16))) uint16_t sV[2][2 * kBlockElems];
+  // 64 KiB: stage s holds K at smem + s*16384 and V at smem + s*16384 + 8192 (elements).  Before the first tile
+  // lands in stage 1 that stage stages the query rows; after the last tile the whole array stages the output rows.
+  __shared__ __attribute__((aligned(16))) uint16_t smem[4 * 2 * kBlockElems];
+  auto sK = [&](int buf) { return smem + buf * (4 * kBlockElems); };
+  auto sV = [&](int buf) { return smem + buf * (4 * kBlockElems) + 2 * kBlockElems; };
 
   // Workgroup ids go round-robin over the 8 XCDs, each with its own L2.  Map them so that one XCD works on the
   // query tiles of one head at a time (ids = 8*slot + xcd): its L2 then holds one head's K/V stream, not eight.
@@ -95,9 +98,22 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
   const int S = a.S, W = a.window;
   const float c2 = a.scale_log2;
 
-  // Q^T fragments: lane (row, hh) holds dims kk*16 + hh*8 .. +7
+  // Q^T fragments: lane (row, hh) holds dims kk*16 + hh*8 .. +7.  With 4 wavefronts each one first copies its 32
+  // query rows (8 KiB) into a private slice of stage 1 with coalesced direct loads (4 whole rows per instruction)
+  // and picks its fragments up from there; read straight from global memory, the fragment pattern touches 32
+  // different rows per instruction.
   bf16x8_t qf[8];
-  {
+  constexpr bool kStageQ = (NW == 4);
+  if constexpr (kStageQ) {
+    uint16_t* slice = smem + 4 * kBlockElems + wave * (32 * kTiledDim);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int r = min(r0 + 4 * i + (lane >> 4), S - 1);  // rows past the prompt re-read the last row (never stored)
+      const uint16_t* src = a.q + (((int64_t)b * S + r) * a.Hq + hq) * kTiledDim + (lane & 15) * 8;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                       (__attribute__((address_space(3))) void*)(slice + i * 512), 16, 0, 0);
+    }
+  } else {
     const uint16_t* qp = a.q + (((int64_t)b * S + row) * a.Hq + hq) * kTiledDim + hh * 8;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
@@ -131,8 +147,8 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
     for (int i = 0; i < 1024 / T; ++i) {
       const int kb = jt * 2 + (T * i) / 512;
       const int in_block = tid + (T * i) % 512;
-      uint16_t* lk = &sK[buf][(T * i + wave * 64) * 8];
-      uint16_t* lv = &sV[buf][(T * i + wave * 64) * 8];
+      uint16_t* lk = sK(buf) + (T * i + wave * 64) * 8;
+      uint16_t* lv = sV(buf) + (T * i + wave * 64) * 8;
       if (kb < nblk_valid) {
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Kg + (int64_t)kb * 512 + in_block),
                                          (__attribute__((address_space(3))) void*)lk, 16, 0, 0);
@@ -147,6 +163,13 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
 
   const int key_row = pf_key_of_row(col);  // key (within a block) this lane feeds as MFMA row `col`
   issue(jt_lo, 0);
+  if constexpr (kStageQ) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the query rows (and the first tile) of this wavefront landed
+    const uint16_t* slice = smem + 4 * kBlockElems + wave * (32 * kTiledDim) + col * kTiledDim + hh * 8;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) qf[kk] = *(const bf16x8_t*)(slice + kk * 16);
+    // stage 1 is overwritten only after the first barrier of the loop, which this wavefront reaches after these reads
+  }
   for (int jt = jt_lo; jt <= jt_hi; ++jt) {
     const int buf = (jt - jt_lo) & 1;
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's direct loads of tile jt have landed
@@ -166,7 +189,7 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
     for (int sub = 0; sub < 2; ++sub) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) s[sub][i] = 0.f;
-      const uint16_t* kb = &sK[buf][sub * kBlockElems + (key_row >> 4) * 2048 + (key_row & 15) * 8];
+      const uint16_t* kb = sK(buf) + sub * kBlockElems + (key_row >> 4) * 2048 + (key_row & 15) * 8;
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
         const bf16x8_t kf = *(const bf16x8_t*)(kb + (2 * kk + hh) * 128);
@@ -220,7 +243,7 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
         }
         const halfx8_t pf = __builtin_bit_cast(halfx8_t, pw);
         // V fragment of this slab: dims 32*db + col, keys of piece g = 2u + hh
-        const uint16_t* vb = &sV[buf][sub * kBlockElems + (col >> 4) * 512 + ((2 * u + hh) * 16 + (col & 15)) * 8];
+        const uint16_t* vb = sV(buf) + sub * kBlockElems + (col >> 4) * 512 + ((2 * u + hh) * 16 + (col & 15)) * 8;
 #pragma unroll
         for (int db = 0; db < 4; ++db) {
           const halfx8_t vf = *(const halfx8_t*)(vb + db * 1024);
@@ -232,8 +255,30 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
   }
 
   lsum += __shfl_xor(lsum, 32);
-  if (row < S) {
-    const float inv = 1.f / lsum;
+  const float inv = 1.f / lsum;
+  if constexpr (sizeof(OutT) == 2 && NW == 4) {
+    // bf16 output: transpose through LDS so that every store instruction writes 4 whole 256-byte rows
+    constexpr int kRowPitch = kTiledDim + 8;  // elements; the pad spreads the rows over the LDS banks
+    __syncthreads();                          // every wavefront is done with the K/V stages
+    uint16_t* slice = smem + wave * (32 * kRowPitch);
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        uint2 w;
+        w.x = pf_pack_bf16(o[db][4 * q4] * inv, o[db][4 * q4 + 1] * inv);
+        w.y = pf_pack_bf16(o[db][4 * q4 + 2] * inv, o[db][4 * q4 + 3] * inv);
+        *(uint2*)(slice + col * kRowPitch + 32 * db + 8 * q4 + 4 * hh) = w;
+      }
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this wavefront's slice is complete (it is private to it)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int rl = 4 * i + (lane >> 4);
+      const u32x4_t v = *(const u32x4_t*)(slice + rl * kRowPitch + (lane & 15) * 8);
+      if (r0 + rl < S)
+        *(u32x4_t*)((uint16_t*)a.out + (((int64_t)b * S + r0 + rl) * a.Hq + hq) * kTiledDim + (lane & 15) * 8) = v;
+    }
+  } else if (row < S) {
     OutT* op = (OutT*)a.out + (((int64_t)b * S + row) * a.Hq + hq) * kTiledDim;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
