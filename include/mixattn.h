@@ -56,8 +56,9 @@ typedef enum { MIXATTN_F32 = 0, MIXATTN_BF16 = 1 } mixattn_dtype;
 typedef enum {
   MIXATTN_OK = 0,
   MIXATTN_ERR_NULL = -1,       /* a required pointer is NULL */
-  MIXATTN_ERR_LAYOUT = -2,     /* invalid descriptor: bad kind, window < 1, sharers of one cache differ in
-                                  kind/window, heads not divisible, unsupported head_dim or dtype, batch < 1 */
+  MIXATTN_ERR_LAYOUT = -2,     /* invalid descriptor: bad kind, window < 1, a reader that is neither like its
+                                  writer nor a sliding reader of a full cache, heads not divisible, unsupported
+                                  head_dim or dtype, batch < 1 */
   MIXATTN_ERR_LAYER = -3,      /* layer / cache / sequence / head / slot index out of range */
   MIXATTN_ERR_NOT_WRITER = -4, /* append, load or k/v commit on a layer that only reads a shared cache */
   MIXATTN_ERR_CAPACITY = -5,   /* a full cache would exceed capacity[b] */
@@ -71,8 +72,9 @@ typedef enum {
 /* One layer (Section 3): its attention kind, its window (tokens, >= 1, SLIDING only; the query attends the
    last `window` keys including its own token), and the id of the KV cache it reads.  The lowest-index layer
    using a cache id is that cache's writer; later layers with the same id read it and store nothing.  Cache ids
-   are arbitrary non-negative integers; sharers need not be consecutive layers (Section 5.1).  All layers of
-   one cache must have the same kind and window. */
+   are arbitrary non-negative integers; sharers need not be consecutive layers (Section 5.1).  A reader must have
+   its writer's kind and window, with one exception: a SLIDING layer may read a FULL layer's cache, in which case
+   it attends the last `window` positions of that cache (nothing extra is stored). */
 typedef struct {
   int32_t kind;     /* mixattn_kind */
   int32_t window;   /* SLIDING: window size in tokens; FULL: ignored */
@@ -163,7 +165,8 @@ int mixattn_read_device_lens(mixattn_layout* L, int cache_index, int32_t* lens);
 /* bytes of K+V storage resident for all caches (allocated) and bytes holding live tokens right now */
 int64_t mixattn_kv_bytes_allocated(const mixattn_layout* L);
 int64_t mixattn_kv_bytes_live(const mixattn_layout* L);
-/* K+V bytes a decode of `layer` streams right now: sum_b min(n_b, window or inf) * 2*n_kv_heads*head_dim*elem */
+/* K+V bytes a decode of `layer` streams right now: sum_b min(n_b, window or inf) * 2*n_kv_heads*head_dim*elem
+   (whole 32-key blocks are fetched, so a window that straddles a block boundary moves up to one block more) */
 int64_t mixattn_step_read_bytes(const mixattn_layout* L, int layer);
 
 /* ---- tuning knobs (defaults are chosen per call from the shapes) ---- */

@@ -15,6 +15,8 @@ What it follows (arXiv 2409.15012):
   token, i.e. positions max(0, i-W+1) .. i.
 * Section 3, "KV cache reuse": a layer may read the cache computed by an
   earlier layer; the first (lowest-index) layer of a sharing group writes it.
+  Readers have their writer's kind and window; as an extension a sliding layer
+  may read a standard layer's cache and then sees its last `window` positions.
 * Section 3, last paragraph: grouped-query attention, query head j reads KV
   head j // (Hq // Hkv).
 
@@ -134,11 +136,12 @@ class OracleStack:
                 self.writer[sp.cache_id] = li
             else:
                 w = self.layers[self.writer[sp.cache_id]]
-                if (w.kind, w.window if w.kind == SLIDING else 0) != (
-                    sp.kind,
-                    sp.window if sp.kind == SLIDING else 0,
-                ):
-                    raise ValueError("layers sharing a cache must have the same kind and window")
+                same = (w.kind, w.window if w.kind == SLIDING else 0) == (
+                    sp.kind, sp.window if sp.kind == SLIDING else 0)
+                windowed_reader = w.kind == FULL and sp.kind == SLIDING  # last `window` positions of a full cache
+                if not (same or windowed_reader):
+                    raise ValueError("sharers of a cache need the writer's kind and window "
+                                     "(or be sliding readers of a full cache)")
         # history store key: cache id (shared) or layer index (duplicate mode)
         self._K = {}
         self._V = {}
@@ -254,7 +257,7 @@ class OracleStack:
 
     def cache_view(self, layer: int, b: int) -> List[Tuple[int, int]]:
         """[(slot, position)] for every valid slot of the cache `layer` reads, sequence b."""
-        sp = self.layers[layer]
+        sp = self.layers[self.writer[self.layers[layer].cache_id]]  # the writer's kind decides the storage
         n = self.seq_len(layer, b)
         return list(enumerate(ring_view(sp.kind, sp.window, n)))
 

@@ -43,7 +43,8 @@ constexpr int kDecodeWaves = 4;
 struct TiledDecodeParams {
   const uint16_t* K; const uint16_t* V;
   const int64_t* d_base; const int32_t* d_slots; const int32_t* d_lens;
-  int window;
+  int window;       // ring size of a sliding cache (RING)
+  int attn_window;  // WINDOWED: a sliding layer reading a full cache attends its last attn_window positions
   const uint16_t* q; void* out;
   int Hq, Hkv, G;
   float scale_log2;  // softmax scale times log2(e)
@@ -74,8 +75,11 @@ __device__ inline void merge_partials(const float* p_acc, const float* p_ml, int
 // longer than the length array says, the wavefront that owns the token's block patches it into the loaded
 // fragments, stores it to the cache for later launches, and writes the new length to a second length array
 // (the old one is still being read by other workgroups of this launch).
-template <typename OutT, bool RING, bool FUSED>
+// WINDOWED (full caches only): the layer is a sliding-window layer that shares a standard layer's cache; it reads
+// the blocks holding positions n - attn_window .. n - 1 and masks the keys before that range.
+template <typename OutT, bool RING, bool FUSED, bool WINDOWED = false>
 __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(TiledDecodeParams a) {
+  static_assert(!(WINDOWED && (RING || FUSED)), "a windowed reader of a full cache never writes it");
   constexpr int NW = kDecodeWaves;
   const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int n_old = a.d_lens[b];
@@ -84,12 +88,15 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
   const int new_slot = RING ? n_old % a.window : n_old;  // where a fused launch puts its token
   const int new_blk = new_slot >> 5, new_key = new_slot & 31;
   const int nb_total = (n + kBlockKeys - 1) / kBlockKeys;
+  const int lo = (WINDOWED && n > a.attn_window) ? n - a.attn_window : 0;  // first position attended
+  const int fb = lo / kBlockKeys;                                           // first block read
+  const int nb_read = nb_total - fb;
   // this sequence's blocks are cut into n_chunks_b chunks of equal length (+-1 block), so that workgroups of one
   // sequence finish together and a sequence a little longer than a multiple of the target does not grow a stub
-  const int n_chunks_b = (nb_total + a.chunk_blocks - 1) / a.chunk_blocks;
+  const int n_chunks_b = (nb_read + a.chunk_blocks - 1) / a.chunk_blocks;
   if (c >= n_chunks_b) return;  // uniform for the workgroup
-  const int blk0 = (int)(((int64_t)c * nb_total) / n_chunks_b);
-  const int blk1 = (int)(((int64_t)(c + 1) * nb_total) / n_chunks_b);
+  const int blk0 = fb + (int)(((int64_t)c * nb_read) / n_chunks_b);
+  const int blk1 = fb + (int)(((int64_t)(c + 1) * nb_read) / n_chunks_b);
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the block loop on scalar branches
@@ -145,6 +152,14 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
     for (int i = 0; i < 4; ++i) {
       sv[i] = s0[i] * a.scale_log2;      // key 4g + i of the block
       sv[4 + i] = s1[i] * a.scale_log2;  // key 16 + 4g + i
+    }
+    if constexpr (WINDOWED) {  // keys before the window (only the first block read has any)
+      const int first = lo - blk * kBlockKeys;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int key = 16 * (j >> 2) + 4 * g + (j & 3);
+        sv[j] = key < first ? -INFINITY : sv[j];
+      }
     }
     if constexpr (TAIL) {
       const int valid = n - blk * kBlockKeys;
@@ -343,7 +358,9 @@ __global__ __launch_bounds__(kTiledDim) void combine_kernel(TiledDecodeParams a)
   int n = a.d_lens[b] + (a.k_new ? 1 : 0);  // the fused launch before this one read the old length array
   if (a.window > 0 && n > a.window) n = a.window;
   const int nb_total = (n + kBlockKeys - 1) / kBlockKeys;
-  const int n_chunks_b = (nb_total + a.chunk_blocks - 1) / a.chunk_blocks;
+  const int lo = (a.attn_window > 0 && n > a.attn_window) ? n - a.attn_window : 0;
+  const int nb_read = nb_total - lo / kBlockKeys;
+  const int n_chunks_b = (nb_read + a.chunk_blocks - 1) / a.chunk_blocks;
   const int64_t row = (int64_t)b * a.Hq + hq;
   merge_partials<OutT>(a.p_acc + row * kMaxChunks * kTiledDim, a.p_ml + row * kMaxChunks * 2, n_chunks_b,
                        threadIdx.x, (OutT*)a.out + row * kTiledDim);
@@ -353,7 +370,7 @@ hipError_t launch_decode_tiled(const DecodeLaunch& L, hipStream_t s) {
   TiledDecodeParams p;
   p.K = (const uint16_t*)L.K; p.V = (const uint16_t*)L.V;
   p.d_base = L.d_base; p.d_slots = L.d_slots; p.d_lens = L.d_lens;
-  p.window = L.window;
+  p.window = L.window; p.attn_window = L.attn_window;
   p.q = (const uint16_t*)L.q; p.out = L.out;
   p.Hq = L.Hq; p.Hkv = L.Hkv; p.G = L.G;
   p.scale_log2 = L.scale * kLog2e;
@@ -366,7 +383,10 @@ hipError_t launch_decode_tiled(const DecodeLaunch& L, hipStream_t s) {
   const bool f32 = L.out_dtype == MIXATTN_F32, ring = L.window > 0, fused = L.k_new != nullptr;
 #define MIXATTN_LAUNCH_DECODE(OUT, RING, FUSED) \
   hipLaunchKernelGGL((decode_tiled_kernel<OUT, RING, FUSED>), grid, dim3(kDecodeWaves * 64), 0, s, p)
-  if (fused) {
+  if (L.attn_window > 0) {
+    if (f32) hipLaunchKernelGGL((decode_tiled_kernel<float, false, false, true>), grid, dim3(kDecodeWaves * 64), 0, s, p);
+    else hipLaunchKernelGGL((decode_tiled_kernel<uint16_t, false, false, true>), grid, dim3(kDecodeWaves * 64), 0, s, p);
+  } else if (fused) {
     if (f32 && ring) MIXATTN_LAUNCH_DECODE(float, true, true);
     else if (f32) MIXATTN_LAUNCH_DECODE(float, false, true);
     else if (ring) MIXATTN_LAUNCH_DECODE(uint16_t, true, true);
@@ -411,7 +431,7 @@ __device__ inline float wave_sum(float x) {
 struct RowDecodeParams {
   const void* K; const void* V;
   const int64_t* d_base; const int32_t* d_slots; const int32_t* d_lens;
-  int window;
+  int window, attn_window;
   const void* q; void* out;
   int Hq, G, D;
   float scale;
@@ -424,6 +444,7 @@ __global__ __launch_bounds__(256) void decode_rowmajor_kernel(RowDecodeParams a)
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   int n = a.d_lens[b];
   if (a.window > 0 && n > a.window) n = a.window;
+  const int lo = (a.attn_window > 0 && n > a.attn_window) ? n - a.attn_window : 0;  // sliding reader of a full cache
   const int slots = a.d_slots[b];
   const int D = a.D;
   const T* Kp = (const T*)a.K + (a.d_base[b] + (int64_t)h * slots) * D;
@@ -437,7 +458,7 @@ __global__ __launch_bounds__(256) void decode_rowmajor_kernel(RowDecodeParams a)
     acc[i] = 0.f;
   }
   float m = -INFINITY, l = 0.f;
-  for (int s = wave; s < n; s += 4) {
+  for (int s = lo + wave; s < n; s += 4) {
     float part = 0.f;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -484,7 +505,8 @@ __global__ __launch_bounds__(256) void decode_rowmajor_kernel(RowDecodeParams a)
 hipError_t launch_decode_rowmajor(const DecodeLaunch& L, hipStream_t s) {
   RowDecodeParams p;
   p.K = L.K; p.V = L.V; p.d_base = L.d_base; p.d_slots = L.d_slots; p.d_lens = L.d_lens;
-  p.window = L.window; p.q = L.q; p.out = L.out; p.Hq = L.Hq; p.G = L.G; p.D = L.D; p.scale = L.scale;
+  p.window = L.window; p.attn_window = L.attn_window;
+  p.q = L.q; p.out = L.out; p.Hq = L.Hq; p.G = L.G; p.D = L.D; p.scale = L.scale;
   const dim3 grid(L.Hq, L.batch), block(256);
   const bool f32 = L.kv_dtype == MIXATTN_F32, of32 = L.out_dtype == MIXATTN_F32;
   if (f32 && of32) hipLaunchKernelGGL((decode_rowmajor_kernel<float, float>), grid, block, 0, s, p);

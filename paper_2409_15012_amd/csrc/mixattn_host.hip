@@ -115,8 +115,13 @@ int mixattn_validate_config(const mixattn_config* cfg) {
     if (d.kind == MIXATTN_SLIDING && d.window < 1) return MIXATTN_ERR_LAYOUT;
     const int w = d.kind == MIXATTN_SLIDING ? d.window : 0;
     auto it = seen.find(d.cache_id);
-    if (it == seen.end()) seen[d.cache_id] = {d.kind, w};
-    else if (it->second != std::make_pair((int)d.kind, w)) return MIXATTN_ERR_LAYOUT;
+    if (it == seen.end()) {
+      seen[d.cache_id] = {d.kind, w};  // the first user is the writer: its kind is the cache's kind
+    } else {
+      const bool same = it->second == std::make_pair((int)d.kind, w);
+      const bool windowed_reader = it->second.first == MIXATTN_FULL && d.kind == MIXATTN_SLIDING;
+      if (!same && !windowed_reader) return MIXATTN_ERR_LAYOUT;
+    }
     any_full |= d.kind == MIXATTN_FULL;
   }
   if (any_full) {
@@ -272,15 +277,29 @@ int mixattn_append_kv(mixattn_layout* L, int layer, const void* k, const void* v
 // rate of one workgroup, whose four wavefronts keep 128 KiB in flight and so advance by one 16 KiB block in
 // about 0.6 us under load.  Cutting sequences shortens the second bound but costs a combine launch (about 5 us);
 // with two workgroups resident per CU, chunks run in rounds of 2 * CUs.
-static int plan_chunk_blocks(const mixattn_layout* L, const Cache& c, int max_blocks, int extra) {
+// tokens a decode streams for a sequence of `len` tokens: all of a full cache, the ring's content, or the window
+static inline int64_t tokens_read(const Cache& c, int64_t len, int attn_window) {
+  if (c.window > 0) return std::min<int64_t>(len, c.window);
+  if (attn_window > 0) return std::min<int64_t>(len, attn_window);
+  return len;
+}
+
+// A sliding layer that reads a standard layer's (full) cache attends the last `window` positions of it; every other
+// layer attends whatever its cache holds.
+static inline int layer_attn_window(const mixattn_layout* L, int layer) {
+  const Cache& c = L->caches[L->layer_cache[layer]];
+  return (c.kind == MIXATTN_FULL && L->layers[layer].kind == MIXATTN_SLIDING) ? L->layers[layer].window : 0;
+}
+
+static int plan_chunk_blocks(const mixattn_layout* L, const Cache& c, int max_blocks, int extra, int attn_window) {
   const double slots = 2.0 * L->n_cus;
   const double us_per_block_bw = 2.0 * kBlockElems * 2 / 7.0e6;  // 16 KiB at 7.0 TB/s
   const double us_per_block_wg = 0.6, us_wg_fixed = 1.0, us_combine = 5.0;
   std::vector<int> nb(L->batch);
   double total_blocks = 0;
   for (int b = 0; b < L->batch; ++b) {
-    const int64_t n = c.window > 0 ? std::min<int64_t>(c.len[b] + extra, c.window) : c.len[b] + extra;
-    nb[b] = (int)((n + kBlockKeys - 1) / kBlockKeys);
+    const int64_t n = tokens_read(c, c.len[b] + extra, attn_window);
+    nb[b] = (int)((n + kBlockKeys - 1) / kBlockKeys) + (attn_window > 0 ? 1 : 0);  // a window may straddle one more block
     total_blocks += (double)nb[b] * L->Hkv;
   }
   const double t_bw = total_blocks * us_per_block_bw;
@@ -311,18 +330,22 @@ static int plan_chunk_blocks(const mixattn_layout* L, const Cache& c, int max_bl
 
 // Decode launch shared by mixattn_decode and mixattn_append_decode.  `extra` = 1 when a fused launch appends this
 // step's token itself (lengths on host and device still hold the old value while planning).
-static int launch_decode(mixattn_layout* L, Cache& c, const void* q, void* out, const void* k_new,
+static int launch_decode(mixattn_layout* L, Cache& c, int attn_window, const void* q, void* out, const void* k_new,
                          const void* v_new, hipStream_t stream) {
   const int extra = k_new ? 1 : 0;
-  int64_t max_n = 0;
+  int max_blocks = 0;  // most blocks one sequence reads
   for (int b = 0; b < L->batch; ++b) {
     const int64_t len = c.len[b] + extra;
-    const int64_t n = c.window > 0 ? std::min<int64_t>(len, c.window) : len;
-    max_n = std::max(max_n, n);
+    int64_t blocks;
+    if (attn_window > 0 && len > attn_window)
+      blocks = (len + kBlockKeys - 1) / kBlockKeys - (len - attn_window) / kBlockKeys;
+    else
+      blocks = (tokens_read(c, len, attn_window) + kBlockKeys - 1) / kBlockKeys;
+    max_blocks = std::max<int>(max_blocks, (int)blocks);
   }
   DecodeLaunch a;
   a.K = c.K; a.V = c.V; a.d_base = c.d_base; a.d_slots = c.d_slots; a.d_lens = c.lens();
-  a.window = c.window; a.q = q; a.out = out;
+  a.window = c.window; a.attn_window = attn_window; a.q = q; a.out = out;
   a.batch = L->batch; a.Hq = L->Hq; a.Hkv = L->Hkv; a.G = L->G; a.D = L->D;
   a.kv_dtype = L->kv_dtype; a.out_dtype = L->out_dtype; a.scale = L->scale;
   a.scratch = L->scratch;
@@ -333,12 +356,11 @@ static int launch_decode(mixattn_layout* L, Cache& c, const void* q, void* out, 
     HIP_TRY(launch_decode_rowmajor(a, stream));
     return MIXATTN_OK;
   }
-  const int max_blocks = (int)((max_n + kBlockKeys - 1) / kBlockKeys);
   int chunk_blocks;
   if (L->chunk_keys > 0) {
     chunk_blocks = (int)(L->chunk_keys / kBlockKeys);
   } else {
-    chunk_blocks = plan_chunk_blocks(L, c, max_blocks, extra);
+    chunk_blocks = plan_chunk_blocks(L, c, max_blocks, extra, attn_window);
   }
   chunk_blocks = std::max(chunk_blocks, (max_blocks + kMaxChunks - 1) / kMaxChunks);
   a.max_blocks = max_blocks;
@@ -354,7 +376,7 @@ int mixattn_decode(mixattn_layout* L, int layer, const void* q, void* out, void*
   Cache& c = L->caches[L->layer_cache[layer]];
   for (int b = 0; b < L->batch; ++b)
     if (c.len[b] < 1) return MIXATTN_ERR_ORDER;
-  return launch_decode(L, c, q, out, nullptr, nullptr, (hipStream_t)stream);
+  return launch_decode(L, c, layer_attn_window(L, layer), q, out, nullptr, nullptr, (hipStream_t)stream);
 }
 
 static int check_append(const mixattn_layout* L, const Cache& c, int layer) {
@@ -377,7 +399,7 @@ int mixattn_append_decode(mixattn_layout* L, int layer, const void* k, const voi
     st = mixattn_append_kv(L, layer, k, v, stream);
     return st != MIXATTN_OK ? st : mixattn_decode(L, layer, q, out, stream);
   }
-  st = launch_decode(L, c, q, out, k, v, (hipStream_t)stream);
+  st = launch_decode(L, c, 0, q, out, k, v, (hipStream_t)stream);
   if (st != MIXATTN_OK) return st;
   c.cur ^= 1;  // the launch wrote n + 1 into the other length array
   for (int b = 0; b < L->batch; ++b) c.len[b] += 1;
@@ -432,7 +454,8 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
   hipStream_t s = (hipStream_t)stream;
   PrefillLaunch p;
   p.q = q; p.out = out; p.k_src = k; p.v_src = v;
-  p.window = c.window; p.batch = L->batch; p.S = seq_len; p.Hq = L->Hq; p.Hkv = L->Hkv; p.G = L->G; p.D = L->D;
+  p.window = L->layers[layer].kind == MIXATTN_SLIDING ? L->layers[layer].window : 0;
+  p.batch = L->batch; p.S = seq_len; p.Hq = L->Hq; p.Hkv = L->Hkv; p.G = L->G; p.D = L->D;
   p.kv_dtype = L->kv_dtype; p.out_dtype = L->out_dtype; p.scale = L->scale;
   p.Kt = p.Vt = nullptr; p.k_base = p.v_base = nullptr; p.k_slots = p.v_slots = nullptr;
   p.waves = (int)L->prefill_waves;
@@ -598,8 +621,9 @@ int64_t mixattn_step_read_bytes(const mixattn_layout* L, int layer) {
   if (!L) return MIXATTN_ERR_NULL;
   if (layer < 0 || layer >= L->n_layers) return MIXATTN_ERR_LAYER;
   const Cache& c = L->caches[L->layer_cache[layer]];
+  const int aw = layer_attn_window(L, layer);
   int64_t tok = 0;
-  for (int b = 0; b < L->batch; ++b) tok += c.window > 0 ? std::min<int64_t>(c.len[b], c.window) : c.len[b];
+  for (int b = 0; b < L->batch; ++b) tok += tokens_read(c, c.len[b], aw);
   return tok * 2 * L->Hkv * L->D * L->elem;
 }
 

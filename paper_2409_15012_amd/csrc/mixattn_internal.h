@@ -103,7 +103,8 @@ namespace mixattn {
 struct DecodeLaunch {
   const void* K; const void* V;
   const int64_t* d_base; const int32_t* d_slots; const int32_t* d_lens;
-  int window;          // 0 = full
+  int window;          // ring size of the cache, 0 = full cache
+  int attn_window;     // > 0: sliding layer reading a full cache (attends the last attn_window positions)
   const void* q; void* out;
   int batch, Hq, Hkv, G, D;
   int kv_dtype, out_dtype;

@@ -43,7 +43,7 @@ def test_validate_config_accepts_the_workloads():
 
 
 @pytest.mark.parametrize("layers,kw,status", [
-    ([(0, 0, 0), (1, 64, 0)], {}, -2),                 # sliding layer reading a full cache
+    ([(1, 64, 0), (0, 0, 0)], {}, -2),                 # full layer reading a sliding cache
     ([(1, 64, 0), (1, 32, 0)], {}, -2),                # sharers with different windows
     ([(1, 0, 0)], {}, -2),                             # window < 1
     ([(2, 0, 0)], {}, -2),                             # unknown kind
@@ -65,6 +65,8 @@ def test_validate_config_rejects(layers, kw, status):
 def test_non_consecutive_sharing_is_a_valid_layout():
     layers = [(0, 0, 7), (1, 8, 3), (0, 0, 7), (1, 8, 3), (1, 8, 9)]
     assert mx.validate_config(layers, 1, 2, 1, 64, [4], "f32", "f32") == 0
+    # a sliding layer may read a full layer's cache (it sees the last `window` positions), with any window
+    assert mx.validate_config([(0, 0, 0), (1, 64, 0), (1, 5, 0)], 1, 2, 1, 64, [4], "f32", "f32") == 0
 
 
 def test_slot_arithmetic_matches_the_oracle():

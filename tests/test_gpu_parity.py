@@ -366,3 +366,40 @@ def test_fused_append_decode_row_major_and_capacity(mx):
         lay.append_decode(0, k, v, q)
     assert ei.value.status == -5 and lay.seq_len(0, 0) == 3 and lay.device_lens(0) == [3, 3]
     lay.close()
+
+
+@pytest.mark.parametrize("kvd,d,Hq,Hkv", [("bf16", 128, 8, 2), ("f32", 64, 4, 2)])
+def test_sliding_layers_reading_a_full_cache(mx, kvd, d, Hq, Hkv):
+    """Mixed-kind sharing group: sliding layers (two different windows) read the cache of a standard layer."""
+    tdt = torch.bfloat16 if kvd == "bf16" else torch.float32
+    layers = [(0, 0, 0), (1, 100, 0), (1, 33, 0), (1, 64, 1), (0, 0, 0)]
+    for S, lens_extra in ((1, 3), (70, 4), (300, 3)):
+        B = 2
+        lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[S + lens_extra] * B, kv_dtype=kvd, out_dtype="f32")
+        lay.set_param(mx.PARAM_CHUNK_KEYS, 64 if S > 100 else 0)
+        ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
+        kv = {}
+        for li in range(len(layers)):
+            wr = lay.writer_of(li)
+            if wr == li:
+                kv[li] = (wl.randn(500 + li, (B, S, Hkv, d), tdt, DEV), wl.randn(600 + li, (B, S, Hkv, d), tdt, DEV))
+            q = wl.randn(700 + li, (B, S, Hq, d), tdt, DEV)
+            k, v = kv[wr]
+            out = lay.prefill(li, q, k, v)
+            ref = ora.prefill(li, to_f64(q), to_f64(k) if wr == li else None, to_f64(v) if wr == li else None)
+            assert_matches(out, ref, kvd, "S %d prefill layer %d" % (S, li))
+        for t in range(lens_extra):
+            for li in range(len(layers)):
+                q = wl.randn(800 + 10 * t + li, (B, Hq, d), tdt, DEV)
+                if lay.writer_of(li) == li:
+                    k = wl.randn(900 + 10 * t + li, (B, Hkv, d), tdt, DEV)
+                    v = wl.randn(950 + 10 * t + li, (B, Hkv, d), tdt, DEV)
+                    ora.append(li, to_f64(k), to_f64(v))
+                    out = lay.append_decode(li, k, v, q)
+                else:
+                    out = lay.decode(li, q)
+                assert_matches(out, ora.decode(li, to_f64(q)), kvd, "S %d step %d layer %d" % (S, t, li))
+        n = S + lens_extra
+        assert lay.step_read_bytes(1) == B * min(n, 100) * 2 * Hkv * d * (2 if kvd == "bf16" else 4)
+        assert lay.step_read_bytes(4) == B * n * 2 * Hkv * d * (2 if kvd == "bf16" else 4)
+        lay.close()

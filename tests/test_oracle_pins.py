@@ -327,3 +327,18 @@ def test_pins_catch_planted_mistakes():
         good.append(0, k, v); bad.append(0, k, v)
     q = rng.standard_normal((B, Hq, d))
     assert np.abs(good.decode(0, q) - bad.decode(0, q)).max() > 1e-3
+
+
+def test_sliding_reader_of_a_full_cache_sees_the_last_window_positions():
+    # extension of the sharing rule: same history, the reader's own mask
+    B, H, d, n, W = 1, 2, 8, 30, 7
+    rng = np.random.default_rng(15)
+    mixed = _stack([(FULL, 0, 0), (SLIDING, W, 0)], B, H, H, d)
+    own = _stack([(SLIDING, W, 0)], B, H, H, d)
+    for _ in range(n):
+        k = rng.standard_normal((B, H, d)); v = rng.standard_normal((B, H, d))
+        mixed.append(0, k, v); own.append(0, k, v)
+        q = rng.standard_normal((B, H, d))
+        np.testing.assert_array_equal(mixed.decode(1, q), own.decode(0, q))
+    with pytest.raises(ValueError):
+        _stack([(SLIDING, W, 0), (FULL, 0, 0)])  # a full layer cannot read a ring
