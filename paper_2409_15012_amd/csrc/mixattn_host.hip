@@ -291,17 +291,27 @@ static inline int layer_attn_window(const mixattn_layout* L, int layer) {
   return (c.kind == MIXATTN_FULL && L->layers[layer].kind == MIXATTN_SLIDING) ? L->layers[layer].window : 0;
 }
 
-static int plan_chunk_blocks(const mixattn_layout* L, const Cache& c, int max_blocks, int extra, int attn_window) {
+static int plan_chunk_blocks(const mixattn_layout* L, Cache& c, int max_blocks, int extra, int attn_window) {
   const double slots = 2.0 * L->n_cus;
   const double us_per_block_bw = 2.0 * kBlockElems * 2 / 7.0e6;  // 16 KiB at 7.0 TB/s
   const double us_per_block_wg = 0.6, us_wg_fixed = 1.0, us_combine = 5.0;
-  std::vector<int> nb(L->batch);
-  double total_blocks = 0;
-  for (int b = 0; b < L->batch; ++b) {
+  auto blocks_of = [&](int b) {
     const int64_t n = tokens_read(c, c.len[b] + extra, attn_window);
-    nb[b] = (int)((n + kBlockKeys - 1) / kBlockKeys) + (attn_window > 0 ? 1 : 0);  // a window may straddle one more block
-    total_blocks += (double)nb[b] * L->Hkv;
+    return (int)((n + kBlockKeys - 1) / kBlockKeys) + (attn_window > 0 ? 1 : 0);  // a window may straddle a block more
+  };
+  // the plan only changes when some sequence crosses a block boundary: memoise on the block counts
+  int64_t sum_nb = 0;
+  int min_nb = INT32_MAX, max_nb = 0;
+  for (int b = 0; b < L->batch; ++b) {
+    const int nb = blocks_of(b);
+    sum_nb += nb;
+    min_nb = std::min(min_nb, nb);
+    max_nb = std::max(max_nb, nb);
   }
+  const int64_t key = ((sum_nb * 1000003 + max_nb) * 1000003 + min_nb) * 131 + attn_window % 131;
+  if (c.plan_key == key && c.plan_max_blocks == max_blocks) return c.plan_chunk_blocks;
+
+  const double total_blocks = (double)sum_nb * L->Hkv;
   const double t_bw = total_blocks * us_per_block_bw;
   int best_t = max_blocks;
   double best_cost = 1e300;
@@ -310,10 +320,17 @@ static int plan_chunk_blocks(const mixattn_layout* L, const Cache& c, int max_bl
     if (chunks > 1 && t < kDecodeMinChunkBlocks) break;
     double wgs = 0;
     int longest = 0;
-    for (int b = 0; b < L->batch; ++b) {
-      const int cb = (nb[b] + t - 1) / t;
-      wgs += (double)cb * L->Hkv;
-      longest = std::max(longest, (nb[b] + cb - 1) / cb);
+    if (min_nb == max_nb) {  // uniform batch: closed form
+      const int cb = (max_nb + t - 1) / t;
+      wgs = (double)cb * L->Hkv * L->batch;
+      longest = (max_nb + cb - 1) / cb;
+    } else {
+      for (int b = 0; b < L->batch; ++b) {
+        const int nb = blocks_of(b);
+        const int cb = (nb + t - 1) / t;
+        wgs += (double)cb * L->Hkv;
+        longest = std::max(longest, (nb + cb - 1) / cb);
+      }
     }
     const double t_long = longest * us_per_block_wg + us_wg_fixed;
     // list-scheduling estimate of the per-workgroup bound over `slots` resident workgroups
@@ -325,7 +342,10 @@ static int plan_chunk_blocks(const mixattn_layout* L, const Cache& c, int max_bl
       best_t = t;
     }
   }
-  return std::max(best_t, 1);
+  c.plan_key = key;
+  c.plan_max_blocks = max_blocks;
+  c.plan_chunk_blocks = std::max(best_t, 1);
+  return c.plan_chunk_blocks;
 }
 
 // Decode launch shared by mixattn_decode and mixattn_append_decode.  `extra` = 1 when a fused launch appends this

@@ -54,6 +54,10 @@ struct Cache {
   int32_t* lens() const { return d_lens2[cur]; }
   int32_t* lens_other() const { return d_lens2[cur ^ 1]; }
   std::vector<int64_t> len;    // host mirror
+  // memo of the last split-K plan (it only changes when a sequence crosses a block boundary)
+  int64_t plan_key = -1;
+  int plan_max_blocks = -1;
+  int plan_chunk_blocks = 0;
 };
 
 struct DecodeScratch {
