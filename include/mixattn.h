@@ -62,8 +62,9 @@ typedef enum {
   MIXATTN_ERR_LAYER = -3,      /* layer / cache / sequence / head / slot index out of range */
   MIXATTN_ERR_NOT_WRITER = -4, /* append, load or k/v commit on a layer that only reads a shared cache */
   MIXATTN_ERR_CAPACITY = -5,   /* a full cache would exceed capacity[b] */
-  MIXATTN_ERR_ORDER = -6,      /* decode on an empty cache; prefill/load on a non-empty cache; reader prefill
-                                  before its writer's; bad seq_len */
+  MIXATTN_ERR_ORDER = -6,      /* decode on an empty cache; load on a non-empty cache; reader prefill before its
+                                  writer's, or of a ring past the first chunk without the staged copy; bad
+                                  seq_len */
   MIXATTN_ERR_ALLOC = -7,      /* device or host allocation failed */
   MIXATTN_ERR_HIP = -8,        /* a HIP runtime call failed (see mixattn_last_hip_error) */
   MIXATTN_ERR_PARAM = -9       /* unknown tuning parameter or value out of range */
@@ -127,15 +128,19 @@ int mixattn_decode(mixattn_layout* L, int layer, const void* q, void* out, void*
 int mixattn_append_decode(mixattn_layout* L, int layer, const void* k, const void* v, const void* q, void* out,
                           void* stream);
 
-/* Prompt attention on empty caches (causal; SLIDING layers also mask keys more than window-1 tokens back).
-   Writer layer: k, v are its prompt keys/values; they are attended over and committed to its cache (FULL: all
-   seq_len positions; SLIDING: the last min(seq_len, window) positions, each at slot p mod window) and every
-   n_b becomes seq_len.  Reader layer: pass the writer's prompt k, v again (attended over, not stored); the
-   writer's prefill must have run (n_b == seq_len).  On the MFMA path (bf16, head_dim 128) a reader may instead
-   pass k = v = NULL to reuse the tile-format copy of the prompt that the most recent mixattn_prefill call on this
-   layout staged, provided that call was for the same cache and seq_len (ORDER otherwise): this is the cheap way
-   to run the readers of a sharing group right after their writer.  On that path V is staged as fp16 (values
-   beyond +-65504 saturate).  Errors: ORDER, CAPACITY, NULL. */
+/* Prompt attention for seq_len new tokens per sequence (causal; SLIDING layers also mask keys more than window-1
+   tokens back).  The tokens follow the n_b tokens the cache already holds, so a prompt may be fed in chunks: query
+   row i of sequence b sits at position n_b + i and attends the cache contents and the chunk.
+   Writer layer: k, v are the chunk's keys/values; they are attended over and committed to its cache (FULL: slots
+   n_b .. n_b+seq_len-1; SLIDING: the ring keeps the last min(n, window) positions, each at slot p mod window) and
+   every n_b grows by seq_len.  Reader layer: runs after its writer's call for the same chunk (its cache then holds
+   n_b >= seq_len tokens, the last seq_len being the chunk); pass the writer's k, v again (attended over, not
+   stored).  On the MFMA path (bf16, head_dim 128) a reader may instead pass k = v = NULL to reuse the tile-format
+   copy that the most recent mixattn_prefill call on this layout staged, provided that call was for the same cache
+   and seq_len (ORDER otherwise): the cheap way to run the readers of a sharing group right after their writer, and
+   the only way for readers of a SLIDING cache past the first chunk (the writer's commit has overwritten ring slots
+   their first rows need; ORDER if k, v are passed there, and on the scalar path).  On the MFMA path V is staged as
+   fp16 (values beyond +-65504 saturate).  Errors: ORDER, CAPACITY, NULL. */
 int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, const void* v, void* out,
                     int seq_len, void* stream);
 

@@ -222,11 +222,15 @@ class OracleStack:
 
     def prefill(self, layer: int, q: np.ndarray, k: Optional[np.ndarray], v: Optional[np.ndarray],
                 rows: Optional[Sequence[Tuple[int, int, int]]] = None) -> np.ndarray:
-        """Prompt attention on empty caches.  q [B, S, Hq, d]; k, v [B, S, Hkv, d].
+        """Prompt attention for S new tokens per sequence.  q [B, S, Hq, d]; k, v [B, S, Hkv, d].
 
-        A writer layer (or any layer in duplicate mode) is given its own k, v and stores
-        them; a reader layer of a shared cache passes k = v = None and attends over the
-        history its writer stored.  rows: optional list of (b, i, j) to compute.
+        The S tokens follow whatever the cache already holds (Section 1: the representation of
+        earlier tokens does not depend on later ones, so a prompt may arrive in chunks): with
+        n_b tokens held before the call, query row i of sequence b sits at position n_b + i.
+        A writer layer (or any layer in duplicate mode) is given its own k, v and stores them
+        first; a reader layer of a shared cache passes k = v = None and attends over the
+        history its writer stored (which already includes this chunk).
+        rows: optional list of (b, i, j) to compute.
         """
         q = np.asarray(q, dtype=np.float64)
         B, S = q.shape[0], q.shape[1]
@@ -236,23 +240,23 @@ class OracleStack:
         if writes:
             if k is None or v is None:
                 raise ValueError("writer layer needs k and v")
-            if any(self.seq_len(layer, b) != 0 for b in range(B)):
-                raise ValueError("prefill needs empty caches")
+            first = [self.seq_len(layer, b) for b in range(B)]
             k = np.asarray(k, dtype=np.float64).reshape(B, S, self.Hkv, self.d)
             v = np.asarray(v, dtype=np.float64).reshape(B, S, self.Hkv, self.d)
             key = self._store_key(layer)
             for b in range(B):
-                self._K[key][b] = k[b].copy()
-                self._V[key][b] = v[b].copy()
+                self._K[key][b] = np.concatenate([self._K[key][b], k[b]], axis=0)
+                self._V[key][b] = np.concatenate([self._V[key][b], v[b]], axis=0)
         else:
-            if any(self.seq_len(layer, b) != S for b in range(B)):
-                raise ValueError("reader prefill needs the writer's prompt in the cache")
+            if any(self.seq_len(layer, b) < S for b in range(B)):
+                raise ValueError("reader prefill needs the writer's chunk in the cache")
+            first = [self.seq_len(layer, b) - S for b in range(B)]
         out = np.full((B, S, self.Hq, self.d), np.nan)
         todo = rows if rows is not None else [
             (b, i, j) for b in range(B) for i in range(S) for j in range(self.Hq)]
         for (b, i, j) in todo:
             K, V = self.history(layer, b)
-            out[b, i, j] = self._attend(layer, b, q[b, i, j], j, i, K, V)
+            out[b, i, j] = self._attend(layer, b, q[b, i, j], j, first[b] + i, K, V)
         return out
 
     def cache_view(self, layer: int, b: int) -> List[Tuple[int, int]]:

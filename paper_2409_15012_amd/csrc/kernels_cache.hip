@@ -82,25 +82,56 @@ hipError_t launch_append_rowmajor(const AppendLaunch& a, hipStream_t s) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Bulk commit.  Destination driven: a workgroup owns one 32-slot block of one (sequence, kv head) and
-// fetches, for each slot, the source token that ends up there:
-//   window == 0 : slot s <- position s                      (valid while s < len)
-//   window  > 0 : slot s <- largest position p < len with p = s (mod window)   (valid while s < min(len, window))
-// Slots of the block that receive nothing are zero-filled so that later MFMA reads see finite data.
+// Bulk store.  Destination driven: a workgroup (tiled) or wavefront (row-major) owns destination slots and
+// fetches, for each slot, the token that ends up there.  A sequence held n_old tokens before the call and
+// receives `add` new ones (n_new = n_old + add); positions n_old .. n_new-1 come from the caller's tensors,
+// earlier positions (chunked prefill only) from an existing cache:
+//   linear (ring == 0): destination index s <-> position p = off + s, valid while p < n_new.
+//                       off = 0 for a full cache or a prompt copy; for the staging copy of a sliding layer's
+//                       chunk, off = max(0, n_old - (stage_window - 1)): the window before the first new token.
+//   ring   (ring  > 0): slot s <-> largest position p < n_new with p = s (mod ring), valid while s < min(n_new, ring).
+// Slots of a touched block that receive nothing are zero-filled so that later MFMA reads see finite data.
 // ------------------------------------------------------------------------------------------------
 // bf16 -> fp16 bit pattern, round to nearest even, magnitudes above the fp16 range saturate to +-65504
 __device__ inline uint16_t bf16_to_f16_sat(uint16_t b) {
   float f = __uint_as_float((uint32_t)b << 16);
-  f = fminf(fmaxf(f, -65504.f), 65504.f);  // NaN stays NaN through the conversion below
-  if (!(f == f)) f = __uint_as_float((uint32_t)b << 16);
+  if (f == f) f = fminf(fmaxf(f, -65504.f), 65504.f);  // NaN passes through
   const _Float16 hval = (_Float16)f;
   return __builtin_bit_cast(uint16_t, hval);
 }
 
-__device__ inline int64_t source_position(int slot, int len, int window) {
-  if (window == 0) return slot < len ? slot : -1;
-  if (slot >= window || slot >= len) return -1;
-  return (int64_t)slot + (int64_t)((len - 1 - slot) / window) * window;
+struct SlotSource {
+  int kind;       // 0: nothing (zero fill), 1: new token `index` of the caller's tensor, 2: slot `index` of the old cache
+  int64_t index;
+};
+
+__device__ inline SlotSource slot_source(const StoreLaunch& a, int s, int n_old, int n_new, int off) {
+  SlotSource r;
+  r.kind = 0;
+  r.index = 0;
+  int64_t p;
+  if (a.window == 0) {
+    p = (int64_t)off + s;
+    if (p >= n_new) return r;
+  } else {
+    if (s >= a.window || s >= n_new) return r;
+    p = (int64_t)s + (int64_t)((n_new - 1 - s) / a.window) * a.window;
+  }
+  if (p >= n_old) {
+    r.kind = 1;
+    r.index = p - n_old;
+  } else if (a.Kold || a.Vold) {
+    r.kind = 2;
+    r.index = a.old_window > 0 ? p % a.old_window : p;
+  }
+  return r;
+}
+
+__device__ inline void store_lengths(const StoreLaunch& a, int b, int& n_old, int& n_new, int& off) {
+  n_old = a.d_n_old ? a.d_n_old[b] - a.old_sub : 0;
+  const int add = a.d_src_len ? a.d_src_len[b] : a.uniform_len;
+  n_new = n_old + add;
+  off = (a.stage_window > 0 && n_old > a.stage_window - 1) ? n_old - (a.stage_window - 1) : 0;
 }
 
 __global__ __launch_bounds__(256) void store_tiled_kernel(StoreLaunch a) {
@@ -109,40 +140,80 @@ __global__ __launch_bounds__(256) void store_tiled_kernel(StoreLaunch a) {
   const int blk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int slots = a.d_slots[b];
   if (blk * kBlockKeys >= slots) return;
-  const int len = a.d_src_len ? a.d_src_len[b] : a.uniform_len;
+  int n_old, n_new, off;
+  store_lengths(a, b, n_old, n_new, off);
+  const int add = n_new - n_old;
   const int64_t first = a.d_src_first ? a.d_src_first[b] : (int64_t)b * a.uniform_len;
-  if (a.d_lens_out && blk == 0 && h == 0 && threadIdx.x == 0) a.d_lens_out[b] = len;
-  // a block no source token maps to is left untouched (never read: it lies beyond the length)
-  const int live = a.window > 0 ? (len < a.window ? len : a.window) : len;
+  if (a.d_lens_out && blk == 0 && h == 0 && threadIdx.x == 0) a.d_lens_out[b] = n_new;
+  // a block no token maps to is left untouched (never read: it lies beyond the length)
+  const int live = a.window > 0 ? (n_new < a.window ? n_new : a.window) : n_new - off;
   if (blk * kBlockKeys >= live) return;
+  // linear store whose old tokens already sit in the destination: blocks made of old tokens only stay as they are
+  if (a.old_is_dest && a.window == 0 && blk * kBlockKeys + kBlockKeys <= n_old - off) return;
+  (void)add;
 
+  const int64_t nblk = slots >> 5;
+  const int64_t blk_elem = (a.d_base[b] + (int64_t)h * nblk + blk) * kBlockElems;
+  uint16_t* Kd = a.K ? (uint16_t*)a.K + blk_elem : nullptr;
+  uint16_t* Vd = a.V ? (uint16_t*)a.V + blk_elem : nullptr;
   const uint16_t* ksrc = (const uint16_t*)a.k_src;
   const uint16_t* vsrc = (const uint16_t*)a.v_src;
+  const uint16_t* kold = (const uint16_t*)a.Kold;
+  const uint16_t* vold = (const uint16_t*)a.Vold;
+  const int64_t old_nblk = (a.Kold || a.Vold) ? (a.old_slots[b] >> 5) : 0;
+  const int64_t old_first = (a.Kold || a.Vold) ? a.old_base[b] + (int64_t)h * old_nblk : 0;
+
+  // Fast path (fp16 copy of a full cache's V, block made of old tokens only): same tile order on both sides,
+  // so the block is converted piece by piece.
+  if (!a.K && a.window == 0 && off == 0 && a.old_window == 0 && vold && !a.old_is_dest &&
+      blk * kBlockKeys + kBlockKeys <= n_old) {
+    const uint16_t* src = vold + (old_first + blk) * kBlockElems;
+    for (int o = threadIdx.x; o < kBlockElems / 8; o += blockDim.x) {
+      uint4 v = *(const uint4*)(src + o * 8);
+      if (a.v_as_f16) {
+        uint16_t* e = (uint16_t*)&v;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e[j] = bf16_to_f16_sat(e[j]);
+      }
+      *(uint4*)(Vd + o * 8) = v;
+    }
+    return;
+  }
+
   for (int i = threadIdx.x; i < kBlockKeys * 16; i += blockDim.x) {
     const int key = i >> 4, c = i & 15;
-    const int64_t p = source_position(blk * kBlockKeys + key, len, a.window);
+    const SlotSource src = slot_source(a, blk * kBlockKeys + key, n_old, n_new, off);
     uint4 kq = make_uint4(0, 0, 0, 0), vq = make_uint4(0, 0, 0, 0);
-    if (p >= 0) {
-      const int64_t off = ((first + p) * a.Hkv + h) * kTiledDim + c * 8;
-      if (a.K) kq = *(const uint4*)(ksrc + off);
-      if (a.V) vq = *(const uint4*)(vsrc + off);
+    if (src.kind == 1) {
+      const int64_t e = ((first + src.index) * a.Hkv + h) * kTiledDim + c * 8;
+      if (Kd) kq = *(const uint4*)(ksrc + e);
+      if (Vd) vq = *(const uint4*)(vsrc + e);
+    } else if (src.kind == 2) {
+      const int64_t be = (old_first + (src.index >> 5)) * kBlockElems;
+      const int within = (int)(src.index & 31);
+      if (Kd && kold) kq = *(const uint4*)(kold + be + k_tile_offset(within, c * 8));
+      if (Vd && vold) {
+        uint16_t e[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e[j] = vold[be + v_tile_offset(within, c * 8 + j)];
+        vq.x = e[0] | ((uint32_t)e[1] << 16);
+        vq.y = e[2] | ((uint32_t)e[3] << 16);
+        vq.z = e[4] | ((uint32_t)e[5] << 16);
+        vq.w = e[6] | ((uint32_t)e[7] << 16);
+      }
     }
     *(uint4*)&sK[key][c * 8] = kq;
     *(uint4*)&sV[key][c * 8] = vq;
   }
   __syncthreads();
-  const int64_t nblk = slots >> 5;
-  const int64_t blk_elem = (a.d_base[b] + (int64_t)h * nblk + blk) * kBlockElems;
-  uint16_t* Kd = (uint16_t*)a.K + blk_elem;
-  uint16_t* Vd = (uint16_t*)a.V + blk_elem;
   for (int o = threadIdx.x; o < kBlockElems / 8; o += blockDim.x) {
     // K piece o = t*256 + c*16 + r  holds key t*16+r, dims c*8..c*8+7
-    if (a.K) {
+    if (Kd) {
       const int t = o >> 8, c = (o >> 4) & 15, r = o & 15;
       *(uint4*)(Kd + o * 8) = *(const uint4*)&sK[t * 16 + r][c * 8];
     }
     // V piece o = nn*64 + g*16 + c  holds dim nn*16+c of keys 16*(j/4) + 4g + j%4, j = 0..7
-    if (a.V) {
+    if (Vd) {
       const int nn = o >> 6, g = (o >> 4) & 3, c = o & 15;
       const int d = nn * 16 + c;
       uint16_t e[8];
@@ -161,22 +232,24 @@ __global__ __launch_bounds__(256) void store_tiled_kernel(StoreLaunch a) {
   }
 }
 
+// Row-major caches: one wavefront per destination slot; old tokens always already sit in the destination.
 template <typename T>
 __global__ __launch_bounds__(256) void store_rowmajor_kernel(StoreLaunch a) {
   const int slot = blockIdx.x * 4 + (threadIdx.x >> 6), h = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x & 63;
   const int slots = a.d_slots[b];
-  const int len = a.d_src_len ? a.d_src_len[b] : a.uniform_len;
+  int n_old, n_new, off;
+  store_lengths(a, b, n_old, n_new, off);
   const int64_t first = a.d_src_first ? a.d_src_first[b] : (int64_t)b * a.uniform_len;
-  if (a.d_lens_out && blockIdx.x == 0 && h == 0 && threadIdx.x == 0) a.d_lens_out[b] = len;
+  if (a.d_lens_out && blockIdx.x == 0 && h == 0 && threadIdx.x == 0) a.d_lens_out[b] = n_new;
   if (slot >= slots) return;
-  const int64_t p = source_position(slot, len, a.window);
-  if (p < 0) return;
-  const int64_t src = ((first + p) * a.Hkv + h) * a.D;
-  const int64_t dst = (a.d_base[b] + (int64_t)h * slots + slot) * a.D;
+  const SlotSource src = slot_source(a, slot, n_old, n_new, off);
+  if (src.kind != 1) return;
+  const int64_t se = ((first + src.index) * a.Hkv + h) * a.D;
+  const int64_t de = (a.d_base[b] + (int64_t)h * slots + slot) * a.D;
   for (int d = lane; d < a.D; d += 64) {
-    ((T*)a.K)[dst + d] = ((const T*)a.k_src)[src + d];
-    ((T*)a.V)[dst + d] = ((const T*)a.v_src)[src + d];
+    ((T*)a.K)[de + d] = ((const T*)a.k_src)[se + d];
+    ((T*)a.V)[de + d] = ((const T*)a.v_src)[se + d];
   }
 }
 

@@ -38,6 +38,9 @@ struct TiledPrefillParams {
   const uint16_t* Vt; const int64_t* v_base; const int32_t* v_slots;  // fp16 tiles
   int window, S, Hq, G;
   float scale_log2;
+  // chunked prefill: sequence b held n_old = d_lens[b] - old_sub tokens before this chunk (d_lens == nullptr: 0).
+  // Key index 0 of the K/V buffers is position 0 (stage_window == 0) or max(0, n_old - (stage_window - 1)).
+  const int32_t* d_lens; int old_sub; int stage_window;
 };
 
 // MFMA row m of a 32-key block holds key pi(m): bits 3 and 4 of m swapped, so that the 8 scores a lane owns per
@@ -97,6 +100,9 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
   const int row = r0 + col;
   const int S = a.S, W = a.window;
   const float c2 = a.scale_log2;
+  // query row i sits at key index i + qoff of the K/V buffers
+  const int n_old = a.d_lens ? a.d_lens[b] - a.old_sub : 0;
+  const int qoff = (a.stage_window > 0 && n_old > a.stage_window - 1) ? a.stage_window - 1 : n_old;
 
   // Q^T fragments: lane (row, hh) holds dims kk*16 + hh*8 .. +7.  With 4 wavefronts each one first copies its 32
   // query rows (8 KiB) into a private slice of stage 1 with coalesced direct loads (4 whole rows per instruction)
@@ -123,13 +129,14 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
     }
   }
 
-  const int nblk_valid = (S + kBlockKeys - 1) / kBlockKeys;
+  const int nblk_valid = (qoff + S + kBlockKeys - 1) / kBlockKeys;
   const u32x4_t* Kg = (const u32x4_t*)(a.Kt + (a.k_base[b] + (int64_t)h * (a.k_slots[b] >> 5)) * kBlockElems);
   const u32x4_t* Vg = (const u32x4_t*)(a.Vt + (a.v_base[b] + (int64_t)h * (a.v_slots[b] >> 5)) * kBlockElems);
 
   const int last_row = min(q0 + kPfRows, S) - 1;
-  const int jt_hi = last_row / kPfKeys;
-  const int jt_lo = W > 0 ? max(0, q0 - W + 1) / kPfKeys : 0;
+  const int jt_hi = (last_row + qoff) / kPfKeys;
+  const int jt_lo = W > 0 ? max(0, q0 + qoff - W + 1) / kPfKeys : 0;
+  const int r0k = r0 + qoff, rowk = row + qoff;  // this wavefront's first row / this lane's row as key indices
 
   floatx16_t o[4];
 #pragma unroll
@@ -178,9 +185,9 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
 
     const int k0 = jt * kPfKeys;
     // whole tile masked for every row of this wavefront?
-    if (k0 > r0 + 31) continue;
-    if (W > 0 && k0 + kPfKeys - 1 < r0 - W + 1) continue;
-    const bool need_mask = (k0 + kPfKeys - 1 > r0) || (W > 0 && k0 < r0 + 31 - W + 1);
+    if (k0 > r0k + 31) continue;
+    if (W > 0 && k0 + kPfKeys - 1 < r0k - W + 1) continue;
+    const bool need_mask = (k0 + kPfKeys - 1 > r0k) || (W > 0 && k0 < r0k + 31 - W + 1);
 
     // the wavefront feeding the matrix pipe wins issue arbitration over its SIMD mate's softmax arithmetic
     __builtin_amdgcn_s_setprio(3);
@@ -204,7 +211,7 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
         for (int i = 0; i < 16; ++i) {
           // register i is MFMA row 8*(i/4) + 4*hh + i%4, which holds key pi(row)
           const int key = k0 + sub * 32 + pf_key_of_row(8 * (i >> 2) + 4 * hh + (i & 3));
-          const bool ok = (key <= row) && (W == 0 || key > row - W);
+          const bool ok = (key <= rowk) && (W == 0 || key > rowk - W);
           s[sub][i] = ok ? s[sub][i] : -INFINITY;
         }
     }
@@ -306,6 +313,7 @@ hipError_t launch_prefill_tiled(const PrefillLaunch& L, hipStream_t s) {
   p.Vt = (const uint16_t*)L.Vt; p.v_base = L.v_base; p.v_slots = L.v_slots;
   p.window = L.window; p.S = L.S; p.Hq = L.Hq; p.G = L.G;
   p.scale_log2 = L.scale * kLog2e;
+  p.d_lens = L.d_lens; p.old_sub = L.old_sub; p.stage_window = L.stage_window;
   // 4 wavefronts (128 query rows) per workgroup by default.  8 wavefronts share each K/V tile among 256 rows: about
   // 4 % faster on a full causal layer alone, but 20 % slower on a W = 1024 layer (a taller workgroup spans more keys
   // than its rows can see) and no faster over the 24-layer stack.
@@ -338,6 +346,10 @@ struct RowPrefillParams {
   const void* q; const void* k; const void* v; void* out;
   int window, S, Hq, Hkv, G, D;
   float scale;
+  // chunked prefill: positions before n_old = d_lens[b] - old_sub come from the row-major cache (slot = position,
+  // or position mod ring for a sliding cache that has not yet received this chunk)
+  const void* Kc; const void* Vc; const int64_t* d_base; const int32_t* d_slots;
+  const int32_t* d_lens; int old_sub; int ring;
 };
 
 template <typename T, typename OutT>
@@ -355,15 +367,28 @@ __global__ __launch_bounds__(256) void prefill_rowmajor_kernel(RowPrefillParams 
     qv[t] = d < D ? pf_load<T>(qp + d) : 0.f;
     acc[t] = 0.f;
   }
-  const int lo = a.window > 0 ? max(0, i - a.window + 1) : 0;
+  const int n_old = a.d_lens ? a.d_lens[b] - a.old_sub : 0;
+  const int pos = n_old + i;  // absolute position of this query row
+  const int lo = a.window > 0 ? max(0, pos - a.window + 1) : 0;
+  const int slots = a.d_lens ? a.d_slots[b] : 0;
   float m = -INFINITY, l = 0.f;
-  for (int p = lo; p <= i; ++p) {
-    const int64_t off = (((int64_t)b * a.S + p) * a.Hkv + h) * D;
+  for (int p = lo; p <= pos; ++p) {
+    const T* kp;
+    const T* vp;
+    if (p >= n_old) {
+      const int64_t off = (((int64_t)b * a.S + (p - n_old)) * a.Hkv + h) * D;
+      kp = (const T*)a.k + off;
+      vp = (const T*)a.v + off;
+    } else {
+      const int64_t off = (a.d_base[b] + (int64_t)h * slots + (a.ring > 0 ? p % a.ring : p)) * D;
+      kp = (const T*)a.Kc + off;
+      vp = (const T*)a.Vc + off;
+    }
     float part = 0.f;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       const int d = lane + 64 * t;
-      if (d < D) part += qv[t] * pf_load<T>((const T*)a.k + off + d);
+      if (d < D) part += qv[t] * pf_load<T>(kp + d);
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o);
@@ -375,7 +400,7 @@ __global__ __launch_bounds__(256) void prefill_rowmajor_kernel(RowPrefillParams 
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       const int d = lane + 64 * t;
-      if (d < D) acc[t] = acc[t] * alpha + pr * pf_load<T>((const T*)a.v + off + d);
+      if (d < D) acc[t] = acc[t] * alpha + pr * pf_load<T>(vp + d);
     }
     m = m_new;
   }
@@ -395,6 +420,8 @@ hipError_t launch_prefill_rowmajor(const PrefillLaunch& L, hipStream_t s) {
   RowPrefillParams p;
   p.q = L.q; p.k = L.k_src; p.v = L.v_src; p.out = L.out;
   p.window = L.window; p.S = L.S; p.Hq = L.Hq; p.Hkv = L.Hkv; p.G = L.G; p.D = L.D; p.scale = L.scale;
+  p.Kc = L.Kc; p.Vc = L.Vc; p.d_base = L.c_base; p.d_slots = L.c_slots; p.d_lens = L.d_lens; p.old_sub = L.old_sub;
+  p.ring = L.ring;
   const dim3 grid((L.S + 3) / 4, L.Hq, L.batch), block(256);
   const bool f32 = L.kv_dtype == MIXATTN_F32, of32 = L.out_dtype == MIXATTN_F32;
   if (f32 && of32) hipLaunchKernelGGL((prefill_rowmajor_kernel<float, float>), grid, block, 0, s, p);

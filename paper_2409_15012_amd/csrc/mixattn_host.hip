@@ -454,9 +454,10 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
   if (!L || !q || !out) return MIXATTN_ERR_NULL;
   if (layer < 0 || layer >= L->n_layers) return MIXATTN_ERR_LAYER;
   if (seq_len < 1) return MIXATTN_ERR_ORDER;
-  Cache& c = L->caches[L->layer_cache[layer]];
-  const bool writer = c.writer == layer;
   const int ci = L->layer_cache[layer];
+  Cache& c = L->caches[ci];
+  const bool writer = c.writer == layer;
+  const bool sliding_cache = c.kind == MIXATTN_SLIDING;
   // a reader may pass k = v = NULL to reuse the prompt copy staged by the latest prefill call, if that call was for
   // the same cache and length (tiled path only)
   const bool reuse_stage = !k && !v;
@@ -466,72 +467,140 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
   } else if (!k || !v) {
     return MIXATTN_ERR_NULL;
   }
+  // n_old: tokens held before this chunk.  A writer appends the chunk; a reader's cache already holds it.
+  bool chunked = false;
+  int64_t max_new = 0, max_old = 0;
   for (int b = 0; b < L->batch; ++b) {
-    if (writer && c.len[b] != 0) return MIXATTN_ERR_ORDER;
-    if (!writer && c.len[b] != seq_len) return MIXATTN_ERR_ORDER;
-    if (c.kind == MIXATTN_FULL && seq_len > L->capacity[b]) return MIXATTN_ERR_CAPACITY;
+    const int64_t n_old = writer ? c.len[b] : c.len[b] - seq_len;
+    if (n_old < 0) return MIXATTN_ERR_ORDER;  // the writer's prefill of this chunk has not run
+    if (c.kind == MIXATTN_FULL && n_old + seq_len > L->capacity[b]) return MIXATTN_ERR_CAPACITY;
+    if (n_old + seq_len > INT32_MAX) return MIXATTN_ERR_CAPACITY;
+    chunked |= n_old > 0;
+    max_new = std::max(max_new, n_old + seq_len);
+    max_old = std::max(max_old, n_old);
   }
+  // Readers of a ring come after their writer's commit, which has overwritten keys the chunk's first rows need:
+  // past the first chunk they can only run from the staged copy.
+  if (chunked && sliding_cache && !writer && !reuse_stage) return MIXATTN_ERR_ORDER;
+  if (chunked && sliding_cache && !writer && !L->tiled) return MIXATTN_ERR_ORDER;
+  const bool simple = !L->tiled || L->prefill_simple != 0;  // scalar kernel on the caller's tensors
+  if (simple && L->tiled && chunked) return MIXATTN_ERR_ORDER;  // the cross-check path keeps to whole prompts
   hipStream_t s = (hipStream_t)stream;
+  const int attn_window = L->layers[layer].kind == MIXATTN_SLIDING ? L->layers[layer].window : 0;
+
   PrefillLaunch p;
   p.q = q; p.out = out; p.k_src = k; p.v_src = v;
-  p.window = L->layers[layer].kind == MIXATTN_SLIDING ? L->layers[layer].window : 0;
+  p.window = attn_window;
   p.batch = L->batch; p.S = seq_len; p.Hq = L->Hq; p.Hkv = L->Hkv; p.G = L->G; p.D = L->D;
   p.kv_dtype = L->kv_dtype; p.out_dtype = L->out_dtype; p.scale = L->scale;
-  p.Kt = p.Vt = nullptr; p.k_base = p.v_base = nullptr; p.k_slots = p.v_slots = nullptr;
   p.waves = (int)L->prefill_waves;
 
-  StoreLaunch st;
-  st.k_src = k; st.v_src = v; st.d_src_first = nullptr; st.d_src_len = nullptr; st.uniform_len = seq_len;
-  st.batch = L->batch; st.Hkv = L->Hkv; st.D = L->D; st.elem = L->elem;
+  // commit of the chunk into this layer's cache (writer): reads lens(), writes n_old + seq_len to lens_other()
+  auto commit = [&]() -> int {
+    StoreLaunch st;
+    st.K = c.K; st.V = c.V; st.d_base = c.d_base; st.d_slots = c.d_slots; st.window = c.window;
+    st.k_src = k; st.v_src = v; st.uniform_len = seq_len;
+    st.d_n_old = c.lens(); st.old_sub = 0;
+    if (L->tiled) {
+      st.Kold = c.K; st.Vold = c.V; st.old_base = c.d_base; st.old_slots = c.d_slots; st.old_window = c.window;
+      st.old_is_dest = 1;
+    }
+    st.d_lens_out = c.lens_other();
+    st.batch = L->batch; st.Hkv = L->Hkv; st.D = L->D; st.elem = L->elem;
+    st.max_slots = (int)(c.window > 0 ? std::min<int64_t>(max_new, c.window) : max_new);
+    HIP_TRY(L->tiled ? launch_store_tiled(st, s) : launch_store_rowmajor(st, s));
+    c.cur ^= 1;
+    for (int b = 0; b < L->batch; ++b) c.len[b] += seq_len;
+    return MIXATTN_OK;
+  };
 
-  if (L->tiled) {
-    const bool simple = L->prefill_simple != 0;  // scalar kernel on the caller's tensors (cross-check path)
-    if (c.kind == MIXATTN_FULL && writer) {
-      st.K = c.K; st.V = c.V; st.d_base = c.d_base; st.d_slots = c.d_slots; st.window = 0;
-      st.d_lens_out = c.lens(); st.max_slots = seq_len;
-      HIP_TRY(launch_store_tiled(st, s));
+  if (!L->tiled || (simple && !chunked)) {
+    // scalar kernel: the chunk from the caller's tensors, earlier positions from the row-major cache as it was
+    // before this chunk (a ring still holds them then, so a sliding writer attends first and commits after)
+    if (!L->tiled) {
+      p.Kc = c.K; p.Vc = c.V; p.c_base = c.d_base; p.c_slots = c.d_slots; p.ring = c.window;
     }
-    if (simple) {
-      HIP_TRY(launch_prefill_rowmajor(p, s));
-    } else {
-      // the MFMA kernel reads V as fp16 from the staging area (every layer) and K either from the full cache
-      // (committed above, or by the writer's prefill) or, for sliding layers, from the staging area
-      if (!reuse_stage) {
-        int e = ensure_stage(L, (seq_len + kBlockKeys - 1) / kBlockKeys);
-        if (e != MIXATTN_OK) return e;
-        L->stage_cache = -1;
-        st.K = c.kind == MIXATTN_FULL ? nullptr : L->stageK;
-        st.V = L->stageV; st.v_as_f16 = 1;
-        st.d_base = L->d_stage_base; st.d_slots = L->d_stage_slots;
-        st.window = 0; st.d_lens_out = nullptr; st.max_slots = seq_len;
-        HIP_TRY(launch_store_tiled(st, s));
-        st.v_as_f16 = 0;
-        L->stage_cache = ci;
-        L->stage_len = seq_len;
-      }
-      if (c.kind == MIXATTN_FULL) {
-        p.Kt = c.K; p.k_base = c.d_base; p.k_slots = c.d_slots;
-      } else {
-        p.Kt = L->stageK; p.k_base = L->d_stage_base; p.k_slots = L->d_stage_slots;
-      }
-      p.Vt = L->stageV; p.v_base = L->d_stage_base; p.v_slots = L->d_stage_slots;
-      HIP_TRY(launch_prefill_tiled(p, s));
+    if (writer && !sliding_cache) {
+      int e = commit();
+      if (e != MIXATTN_OK) return e;
     }
-    if (writer && c.kind == MIXATTN_SLIDING) {
-      st.K = c.K; st.V = c.V; st.d_base = c.d_base; st.d_slots = c.d_slots; st.window = c.window;
-      st.d_lens_out = c.lens(); st.max_slots = std::min(seq_len, c.window);
-      HIP_TRY(launch_store_tiled(st, s));
-    }
-  } else {
+    const bool lens_hold_chunk = !(writer && sliding_cache);
+    p.d_lens = (!L->tiled && chunked) ? c.lens() : nullptr;
+    p.old_sub = lens_hold_chunk ? seq_len : 0;
     HIP_TRY(launch_prefill_rowmajor(p, s));
-    if (writer) {
-      st.K = c.K; st.V = c.V; st.d_base = c.d_base; st.d_slots = c.d_slots; st.window = c.window;
-      st.d_lens_out = c.lens(); st.max_slots = c.window > 0 ? std::min(seq_len, c.window) : seq_len;
-      HIP_TRY(launch_store_rowmajor(st, s));
+    if (writer && sliding_cache) {
+      int e = commit();
+      if (e != MIXATTN_OK) return e;
     }
+    return MIXATTN_OK;
   }
-  if (writer)
-    for (int b = 0; b < L->batch; ++b) c.len[b] = seq_len;
+
+  // ---- MFMA path
+  if (!sliding_cache) {
+    // K from the full cache itself (commit first), V from an fp16 copy of positions 0 .. n_new-1 in the staging area
+    if (writer) {
+      int e = commit();
+      if (e != MIXATTN_OK) return e;
+    }
+    if (!reuse_stage) {
+      int e = ensure_stage(L, (max_new + kBlockKeys - 1) / kBlockKeys);
+      if (e != MIXATTN_OK) return e;
+      L->stage_cache = -1;
+      StoreLaunch st;
+      st.K = nullptr; st.V = L->stageV; st.v_as_f16 = 1;
+      st.d_base = L->d_stage_base; st.d_slots = L->d_stage_slots; st.window = 0;
+      st.k_src = k; st.v_src = v; st.uniform_len = seq_len;
+      if (chunked) {
+        st.d_n_old = c.lens(); st.old_sub = seq_len;  // lengths already include the chunk
+        st.Vold = c.V; st.old_base = c.d_base; st.old_slots = c.d_slots; st.old_window = 0;
+      }
+      st.batch = L->batch; st.Hkv = L->Hkv; st.D = L->D; st.elem = L->elem;
+      st.max_slots = (int)max_new;
+      HIP_TRY(launch_store_tiled(st, s));
+      L->stage_cache = ci;
+      L->stage_len = seq_len;
+    }
+    p.Kt = c.K; p.k_base = c.d_base; p.k_slots = c.d_slots;
+    p.Vt = L->stageV; p.v_base = L->d_stage_base; p.v_slots = L->d_stage_slots;
+    p.stage_window = 0;
+    p.d_lens = chunked ? c.lens() : nullptr; p.old_sub = seq_len;
+    HIP_TRY(launch_prefill_tiled(p, s));
+    return MIXATTN_OK;
+  }
+
+  // sliding cache: K and V from a staging copy of positions max(0, n_old - (W-1)) .. n_new-1, built from the ring
+  // (before it receives the chunk) and the chunk
+  const int W = c.window;
+  if (!reuse_stage) {
+    const int64_t span = std::min<int64_t>(max_old, W - 1) + seq_len;
+    int e = ensure_stage(L, (span + kBlockKeys - 1) / kBlockKeys);
+    if (e != MIXATTN_OK) return e;
+    L->stage_cache = -1;
+    StoreLaunch st;
+    st.K = L->stageK; st.V = L->stageV; st.v_as_f16 = 1;
+    st.d_base = L->d_stage_base; st.d_slots = L->d_stage_slots; st.window = 0;
+    st.stage_window = W;
+    st.k_src = k; st.v_src = v; st.uniform_len = seq_len;
+    if (chunked) {  // writer (readers past the first chunk always reuse): lengths do not include the chunk yet
+      st.d_n_old = c.lens(); st.old_sub = 0;
+      st.Kold = c.K; st.Vold = c.V; st.old_base = c.d_base; st.old_slots = c.d_slots; st.old_window = W;
+    }
+    st.batch = L->batch; st.Hkv = L->Hkv; st.D = L->D; st.elem = L->elem;
+    st.max_slots = (int)span;
+    HIP_TRY(launch_store_tiled(st, s));
+    L->stage_cache = ci;
+    L->stage_len = seq_len;
+  }
+  p.Kt = L->stageK; p.k_base = L->d_stage_base; p.k_slots = L->d_stage_slots;
+  p.Vt = L->stageV; p.v_base = L->d_stage_base; p.v_slots = L->d_stage_slots;
+  p.stage_window = W;
+  p.d_lens = chunked ? c.lens() : nullptr;
+  p.old_sub = writer ? 0 : seq_len;
+  HIP_TRY(launch_prefill_tiled(p, s));
+  if (writer) {
+    int e = commit();
+    if (e != MIXATTN_OK) return e;
+  }
   return MIXATTN_OK;
 }
 

@@ -124,18 +124,28 @@ struct DecodeLaunch {
 hipError_t launch_decode_tiled(const DecodeLaunch& a, hipStream_t s);
 hipError_t launch_decode_rowmajor(const DecodeLaunch& a, hipStream_t s);
 
-struct StoreLaunch {  // bulk commit of prompt / packed k,v into a cache or the staging area
-  void* K; void* V;            // tiled path: either may be nullptr (that tensor is skipped)
+// Bulk store of tokens into a cache or the staging area (prompt commit, bulk load, prefill staging).  A sequence
+// holds n_old tokens before and n_old + add after; see kernels_cache.hip for the slot <-> position maps.
+struct StoreLaunch {
+  void* K = nullptr; void* V = nullptr;  // destination; tiled path: either may be nullptr (that tensor is skipped)
   int v_as_f16 = 0;            // tiled path: store V converted to fp16 (prefill staging), saturating at +-65504
-  const int64_t* d_base; const int32_t* d_slots;
-  int window;             // 0 = position p -> slot p; >0 = ring (keep last min(len, window), slot p mod window)
-  const void* k_src; const void* v_src;  // [tokens, Hkv, D]
-  const int64_t* d_src_first;  // [batch] first packed token index of each sequence, or nullptr => b * uniform_len
-  const int32_t* d_src_len;    // [batch] tokens of each sequence, or nullptr => uniform_len
-  int uniform_len;
-  int32_t* d_lens_out;         // device lengths to set (nullptr: leave)
-  int batch, Hkv, D, elem;
-  int max_slots;               // max over b of slots that can receive data (grid size)
+  const int64_t* d_base = nullptr; const int32_t* d_slots = nullptr;  // destination geometry
+  int window = 0;              // 0 = linear destination; > 0 = ring of that many slots
+  int stage_window = 0;        // linear only: > 0 = destination index 0 is position max(0, n_old - (stage_window-1))
+  const void* k_src = nullptr; const void* v_src = nullptr;  // new tokens, [tokens, Hkv, D]
+  const int64_t* d_src_first = nullptr;  // [batch] first packed token of each sequence; nullptr => b * uniform_len
+  const int32_t* d_src_len = nullptr;    // [batch] new tokens of each sequence; nullptr => uniform_len
+  int uniform_len = 0;
+  const int32_t* d_n_old = nullptr;      // [batch] device lengths; n_old = d_n_old[b] - old_sub; nullptr => 0
+  int old_sub = 0;
+  // tokens before n_old (tiled path): read from this tile-format cache; nullptr => none are needed
+  const void* Kold = nullptr; const void* Vold = nullptr;
+  const int64_t* old_base = nullptr; const int32_t* old_slots = nullptr;
+  int old_window = 0;          // ring size of the old cache (0 = full cache)
+  int old_is_dest = 0;         // the old cache is the destination itself: blocks without new tokens are skipped
+  int32_t* d_lens_out = nullptr;  // device lengths to set to n_old + add (nullptr: leave)
+  int batch = 0, Hkv = 0, D = 0, elem = 0;
+  int max_slots = 0;           // max over b of destination slots that can receive data (grid size)
 };
 hipError_t launch_store_tiled(const StoreLaunch& a, hipStream_t s);
 hipError_t launch_store_rowmajor(const StoreLaunch& a, hipStream_t s);
@@ -155,17 +165,22 @@ hipError_t launch_gather_row(const void* K, const void* V, int64_t base, int32_t
                              int D, int elem, bool tiled, void* dst, hipStream_t s);
 
 struct PrefillLaunch {
-  const void* q; void* out;
+  const void* q = nullptr; void* out = nullptr;
   // tiled path: K in tile format (the full cache itself or the staging area), V in tile format as fp16 (staging)
-  const void* Kt; const int64_t* k_base; const int32_t* k_slots;
-  const void* Vt; const int64_t* v_base; const int32_t* v_slots;
-  // row-major path: the caller's prompt tensors
-  const void* k_src; const void* v_src;
-  int window;  // 0 = full causal
-  int batch, S, Hq, Hkv, G, D;
-  int kv_dtype, out_dtype;
-  float scale;
-  int waves;  // wavefronts per workgroup on the tiled path: 4, 8, or 0 = default (4)
+  const void* Kt = nullptr; const int64_t* k_base = nullptr; const int32_t* k_slots = nullptr;
+  const void* Vt = nullptr; const int64_t* v_base = nullptr; const int32_t* v_slots = nullptr;
+  int stage_window = 0;  // > 0: key index 0 of Kt/Vt is position max(0, n_old - (stage_window - 1))
+  // row-major path: the caller's chunk tensors, and the row-major cache for positions before the chunk
+  const void* k_src = nullptr; const void* v_src = nullptr;
+  const void* Kc = nullptr; const void* Vc = nullptr; const int64_t* c_base = nullptr; const int32_t* c_slots = nullptr;
+  int ring = 0;          // row-major: ring size of that cache (0 = full)
+  // chunked prefill: n_old = d_lens[b] - old_sub tokens were held before this chunk (nullptr: empty caches)
+  const int32_t* d_lens = nullptr; int old_sub = 0;
+  int window = 0;  // attention window of the layer, 0 = full causal
+  int batch = 0, S = 0, Hq = 0, Hkv = 0, G = 0, D = 0;
+  int kv_dtype = 0, out_dtype = 0;
+  float scale = 0.f;
+  int waves = 0;  // wavefronts per workgroup on the tiled path: 4, 8, or 0 = default (4)
 };
 hipError_t launch_prefill_tiled(const PrefillLaunch& a, hipStream_t s);
 hipError_t launch_prefill_rowmajor(const PrefillLaunch& a, hipStream_t s);

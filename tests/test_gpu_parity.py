@@ -294,9 +294,9 @@ def test_error_paths_leave_state_untouched(mx):
     with pytest.raises(mx.MixAttnError) as e:
         lay.append_kv(0, k, k)
     assert e.value.status == -5 and lay.seq_len(0, 0) == 2 and lay.device_lens(0) == [2]
-    with pytest.raises(mx.MixAttnError) as e:
+    with pytest.raises(mx.MixAttnError) as e:  # a further chunk of one token would exceed the capacity of 2
         lay.prefill(0, q.view(1, 1, Hq, d), k.view(1, 1, Hkv, d), k.view(1, 1, Hkv, d))
-    assert e.value.status == -6
+    assert e.value.status == -5 and lay.seq_len(0, 0) == 2
     with pytest.raises(mx.MixAttnError) as e:
         lay.decode(5, q)
     assert e.value.status == -3
@@ -403,3 +403,91 @@ def test_sliding_layers_reading_a_full_cache(mx, kvd, d, Hq, Hkv):
         assert lay.step_read_bytes(1) == B * min(n, 100) * 2 * Hkv * d * (2 if kvd == "bf16" else 4)
         assert lay.step_read_bytes(4) == B * n * 2 * Hkv * d * (2 if kvd == "bf16" else 4)
         lay.close()
+
+
+@pytest.mark.parametrize("kvd,d,Hq,Hkv,W,chunks", [
+    ("bf16", 128, 8, 2, 64, [40, 1, 31, 100, 200]),     # chunk edges inside blocks, chunks longer than the window
+    ("bf16", 128, 8, 2, 100, [300, 17, 129]),
+    ("bf16", 128, 4, 4, 1024, [700, 500, 90]),          # window longer than the first chunks
+    ("f32", 64, 4, 2, 24, [10, 1, 50, 7]),              # scalar path
+])
+def test_chunked_prefill_against_oracle(mx, kvd, d, Hq, Hkv, W, chunks):
+    """A prompt fed in chunks: every chunk's rows against the oracle, caches bit-exact, then decode steps."""
+    tdt = torch.bfloat16 if kvd == "bf16" else torch.float32
+    tiled = kvd == "bf16"
+    B = 2
+    # full (cache 0), sliding writer (1), its reader, sliding reader of the full cache, full reader
+    layers = [(0, 0, 0), (1, W, 1), (1, W, 1), (1, W, 0), (0, 0, 0)]
+    total = sum(chunks)
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[total + 2] * B, kv_dtype=kvd, out_dtype="f32")
+    ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
+    seed = 4000 + W
+    for ci_, S in enumerate(chunks):
+        kv = {}
+        for li in range(len(layers)):
+            wr = lay.writer_of(li)
+            if wr == li:
+                kv[li] = (wl.randn(seed + 100 * ci_ + li, (B, S, Hkv, d), tdt, DEV),
+                          wl.randn(seed + 100 * ci_ + 50 + li, (B, S, Hkv, d), tdt, DEV))
+            q = wl.randn(seed + 100 * ci_ + 70 + li, (B, S, Hq, d), tdt, DEV)
+            k, v = kv[wr]
+            ring_reader = li == 2
+            if ring_reader and not tiled:
+                if ci_ > 0:  # the scalar path cannot serve a ring's reader past the first chunk
+                    with pytest.raises(mx.MixAttnError) as ei:
+                        lay.prefill(li, q, k, v)
+                    assert ei.value.status == -6
+                    ora.prefill(li, to_f64(q), None, None)
+                    continue
+                out = lay.prefill(li, q, k, v)
+            elif ring_reader:
+                if ci_ > 0:
+                    with pytest.raises(mx.MixAttnError) as ei:  # needs the staged copy
+                        lay.prefill(li, q, k, v)
+                    assert ei.value.status == -6
+                out = lay.prefill(li, q, None, None)
+            else:
+                out = lay.prefill(li, q, k, v)
+            ref = ora.prefill(li, to_f64(q), to_f64(k) if wr == li else None, to_f64(v) if wr == li else None)
+            assert_matches(out, ref, kvd, "chunk %d layer %d" % (ci_, li))
+        for li in (0, 1):
+            _check_cache(lay, ora, li, heads=[0, Hkv - 1])
+    for t in range(2):
+        for li in range(len(layers)):
+            q = wl.randn(seed + 9000 + 10 * t + li, (B, Hq, d), tdt, DEV)
+            if lay.writer_of(li) == li:
+                k = wl.randn(seed + 9100 + 10 * t + li, (B, Hkv, d), tdt, DEV)
+                v = wl.randn(seed + 9200 + 10 * t + li, (B, Hkv, d), tdt, DEV)
+                ora.append(li, to_f64(k), to_f64(v))
+                out = lay.append_decode(li, k, v, q)
+            else:
+                out = lay.decode(li, q)
+            assert_matches(out, ora.decode(li, to_f64(q)), kvd, "decode %d layer %d" % (t, li))
+    lay.close()
+
+
+def test_chunked_prefill_ragged_history(mx):
+    """Sequences that already hold different numbers of tokens (bulk-loaded) receive one more chunk."""
+    B, Hq, Hkv, d, W, S = 3, 8, 2, 128, 48, 70
+    lens = [5, 130, 47]
+    layers = [(0, 0, 0), (1, W, 1), (1, W, 1)]
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[n + S for n in lens], kv_dtype="bf16", out_dtype="f32")
+    ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
+    for li in (0, 1):
+        k = wl.randn(60 + li, (sum(lens), Hkv, d), torch.bfloat16, DEV)
+        v = wl.randn(70 + li, (sum(lens), Hkv, d), torch.bfloat16, DEV)
+        lay.load_kv(li, k, v, lens)
+        ora.load(li, to_f64(k), to_f64(v), lens)
+    kv = {}
+    for li in range(3):
+        wr = lay.writer_of(li)
+        if wr == li:
+            kv[li] = (wl.randn(80 + li, (B, S, Hkv, d), torch.bfloat16, DEV), wl.randn(90 + li, (B, S, Hkv, d), torch.bfloat16, DEV))
+        q = wl.randn(95 + li, (B, S, Hq, d), torch.bfloat16, DEV)
+        k, v = kv[wr]
+        out = lay.prefill(li, q, k, v) if wr == li else lay.prefill(li, q, None, None)
+        ref = ora.prefill(li, to_f64(q), to_f64(k) if wr == li else None, to_f64(v) if wr == li else None)
+        assert_matches(out, ref, "bf16", "layer %d" % li)
+    for li in (0, 1):
+        _check_cache(lay, ora, li, heads=[1])
+    lay.close()

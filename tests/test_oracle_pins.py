@@ -342,3 +342,26 @@ def test_sliding_reader_of_a_full_cache_sees_the_last_window_positions():
         np.testing.assert_array_equal(mixed.decode(1, q), own.decode(0, q))
     with pytest.raises(ValueError):
         _stack([(SLIDING, W, 0), (FULL, 0, 0)])  # a full layer cannot read a ring
+
+
+def test_chunked_prefill_equals_one_shot_and_equals_appends():
+    # Section 1: earlier tokens are unaffected by later ones, so feeding a prompt in chunks changes nothing
+    B, Hq, Hkv, d, S, W = 2, 4, 2, 8, 23, 6
+    rng = np.random.default_rng(16)
+    q = rng.standard_normal((B, S, Hq, d))
+    k = rng.standard_normal((B, S, Hkv, d)); v = rng.standard_normal((B, S, Hkv, d))
+    layers = [(FULL, 0, 0), (SLIDING, W, 1), (SLIDING, W, 1)]
+    whole = _stack(layers, B, Hq, Hkv, d)
+    ref = [whole.prefill(0, q, k, v), whole.prefill(1, q, k, v), whole.prefill(2, q, None, None)]
+    parts = _stack(layers, B, Hq, Hkv, d)
+    got = [[], [], []]
+    for (a, b) in ((0, 5), (5, 6), (6, 17), (17, 23)):
+        got[0].append(parts.prefill(0, q[:, a:b], k[:, a:b], v[:, a:b]))
+        got[1].append(parts.prefill(1, q[:, a:b], k[:, a:b], v[:, a:b]))
+        got[2].append(parts.prefill(2, q[:, a:b], None, None))
+    for li in range(3):
+        np.testing.assert_array_equal(np.concatenate(got[li], axis=1), ref[li])
+    # and a decode step after the chunks sees the same history
+    qd = rng.standard_normal((B, Hq, d))
+    for li in range(3):
+        np.testing.assert_array_equal(parts.decode(li, qd), whole.decode(li, qd))
