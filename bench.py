@@ -38,6 +38,7 @@ def parse():
     ap.add_argument("--chunk-keys", type=int, default=0)
     ap.add_argument("--fused-combine", type=int, default=-1)
     ap.add_argument("--prefill-waves", type=int, default=0)
+    ap.add_argument("--chunks", type=int, default=1, help="prefill32k: feed the prompt in this many equal chunks")
     ap.add_argument("--skip-standard", action="store_true", help="ragged64: time the MixAttention stack only")
     ap.add_argument("--two-call-append", action="store_true",
                     help="writer layers call append_kv and decode separately instead of append_decode")
@@ -242,22 +243,34 @@ def run_prefill(args, mx, wl, torch, w):
     out = torch.empty((B, S, Hq, d), dtype=lay.out_torch, device=dev)
     writer_of = [lay.writer_of(li) for li in range(len(w.layers))]
 
+    n_chunks = max(1, args.chunks)
+    assert S % n_chunks == 0
+    C = S // n_chunks
+
     def step(events=None):
         lay.reset()
-        for li in range(len(w.layers)):
-            k, v = kv[writer_of[li]]
-            if writer_of[li] != li:
-                k = v = None  # readers follow their writer directly: reuse the staged prompt
-            if events is not None and li == 0:
-                e0 = torch.cuda.Event(enable_timing=True)
-                e1 = torch.cuda.Event(enable_timing=True)
-                e0.record()
-                lay.prefill(li, q, k, v, out)
-                e1.record()
-                events.append((e0, e1))
-            else:
-                lay.prefill(li, q, k, v, out)
+        for ch in range(n_chunks):  # chunk by chunk through the whole stack, as a serving loop would
+            sl = slice(ch * C, (ch + 1) * C)
+            for li in range(len(w.layers)):
+                k, v = kv[writer_of[li]]
+                kk, vv = k[:, sl], v[:, sl]
+                if n_chunks > 1:
+                    kk, vv = kk.contiguous(), vv.contiguous()
+                if writer_of[li] != li:
+                    kk = vv = None  # readers follow their writer directly: reuse the staged prompt
+                qq = q[:, sl].contiguous() if n_chunks > 1 else q
+                oo = out[:, sl] if n_chunks == 1 else out_chunk
+                timed = events is not None and li == 0 and ch == n_chunks - 1
+                if timed:
+                    e0 = torch.cuda.Event(enable_timing=True)
+                    e1 = torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                lay.prefill(li, qq, kk, vv, oo)
+                if timed:
+                    e1.record()
+                    events.append((e0, e1))
 
+    out_chunk = torch.empty((B, C, Hq, d), dtype=lay.out_torch, device=dev) if n_chunks > 1 else None
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -330,9 +343,9 @@ def main():
             "metric": "prefill attention TFLOP/s (unmasked pairs only), 24-layer MixAttention stack",
             "value": r["tflops"], "unit": "TFLOP/s", "ms_per_step": r["ms_per_step"],
             "config": {"workload": w.name, "batch": 1, "seq_len": w.prefill_len, "window": 1024,
-                       "out_dtype": args.out_dtype},
+                       "out_dtype": args.out_dtype, "chunks": max(1, args.chunks)},
             "useful_flops_per_step": r["flops"],
-            "roofline": {"kernel": "prefill_tiled_kernel (full causal layer, incl. cache commit)", "bound": "mfma",
+            "roofline": None if args.chunks > 1 else {"kernel": "prefill_tiled_kernel (full causal layer, incl. cache commit)", "bound": "mfma",
                          "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                          "frac": ach / MFMA_BF16_PEAK_TFLOPS, "launch_ms": r["full_layer_ms"], "traffic": None},
         })
