@@ -187,11 +187,6 @@ def cpu_baseline_decode(wl, torch, w, budget_s=15.0):
     """
     import numpy as np
     from oracle.mixattn_oracle import LayerSpec, OracleStack
-    try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        threads = 1
     G, d = w.n_q_heads // w.n_kv_heads, w.head_dim
     n = w.context
     W = max(t[1] for t in w.layers)
@@ -205,6 +200,7 @@ def cpu_baseline_decode(wl, torch, w, budget_s=15.0):
     t_full = t_slide = 0.0
     reps = 0
     t_start = time.perf_counter()
+    cpu_start = time.process_time()
     while time.perf_counter() - t_start < budget_s:
         a = time.perf_counter()
         ora.decode(0, q)
@@ -214,6 +210,9 @@ def cpu_baseline_decode(wl, torch, w, budget_s=15.0):
         t_full += b - a
         t_slide += c - b
         reps += 1
+    wall = time.perf_counter() - t_start
+    # threads the oracle's numpy calls actually kept busy: CPU time over wall time
+    threads = max(1, int(round((time.process_time() - cpu_start) / wall)))
     t_full /= reps
     t_slide /= reps
     n_full = sum(1 for t in w.layers if t[0] == wl.FULL)

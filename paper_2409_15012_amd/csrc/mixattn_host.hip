@@ -252,16 +252,21 @@ int mixattn_reset(mixattn_layout* L, void* stream) {
   return MIXATTN_OK;
 }
 
+static int check_append(const mixattn_layout* L, const Cache& c, int layer) {
+  if (c.writer != layer) return MIXATTN_ERR_NOT_WRITER;
+  for (int b = 0; b < L->batch; ++b) {
+    if (c.kind == MIXATTN_FULL && c.len[b] + 1 > L->capacity[b]) return MIXATTN_ERR_CAPACITY;
+    if (c.len[b] + 1 > INT32_MAX) return MIXATTN_ERR_CAPACITY;
+  }
+  return MIXATTN_OK;
+}
+
 int mixattn_append_kv(mixattn_layout* L, int layer, const void* k, const void* v, void* stream) {
   if (!L || !k || !v) return MIXATTN_ERR_NULL;
   if (layer < 0 || layer >= L->n_layers) return MIXATTN_ERR_LAYER;
   Cache& c = L->caches[L->layer_cache[layer]];
-  if (c.writer != layer) return MIXATTN_ERR_NOT_WRITER;
-  if (c.kind == MIXATTN_FULL)
-    for (int b = 0; b < L->batch; ++b)
-      if (c.len[b] + 1 > L->capacity[b]) return MIXATTN_ERR_CAPACITY;
-  for (int b = 0; b < L->batch; ++b)
-    if (c.len[b] + 1 > INT32_MAX) return MIXATTN_ERR_CAPACITY;
+  const int st = check_append(L, c, layer);
+  if (st != MIXATTN_OK) return st;
   AppendLaunch a;
   a.K = c.K; a.V = c.V; a.d_base = c.d_base; a.d_slots = c.d_slots; a.d_lens = c.lens();
   a.window = c.window; a.k = k; a.v = v;
@@ -397,15 +402,6 @@ int mixattn_decode(mixattn_layout* L, int layer, const void* q, void* out, void*
   for (int b = 0; b < L->batch; ++b)
     if (c.len[b] < 1) return MIXATTN_ERR_ORDER;
   return launch_decode(L, c, layer_attn_window(L, layer), q, out, nullptr, nullptr, (hipStream_t)stream);
-}
-
-static int check_append(const mixattn_layout* L, const Cache& c, int layer) {
-  if (c.writer != layer) return MIXATTN_ERR_NOT_WRITER;
-  for (int b = 0; b < L->batch; ++b) {
-    if (c.kind == MIXATTN_FULL && c.len[b] + 1 > L->capacity[b]) return MIXATTN_ERR_CAPACITY;
-    if (c.len[b] + 1 > INT32_MAX) return MIXATTN_ERR_CAPACITY;
-  }
-  return MIXATTN_OK;
 }
 
 int mixattn_append_decode(mixattn_layout* L, int layer, const void* k, const void* v, const void* q, void* out,
