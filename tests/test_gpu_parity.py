@@ -491,3 +491,32 @@ def test_chunked_prefill_ragged_history(mx):
     for li in (0, 1):
         _check_cache(lay, ora, li, heads=[1])
     lay.close()
+
+
+@pytest.mark.parametrize("qscale,vscale", [(6.0, 1.0), (0.01, 1.0), (1.0, 300.0), (3.0, 1e-3)])
+def test_peaked_flat_and_scaled_inputs(mx, qscale, vscale):
+    """Score ranges far from N(0,1): sharply peaked rows (large q), nearly uniform rows (tiny q), large and tiny
+    values.  Exercises the running-maximum updates, the accumulator rescale and the reduced-precision P.V products."""
+    B, Hq, Hkv, d, S, W = 2, 8, 2, 128, 450, 200
+    layers = [(0, 0, 0), (1, W, 1)]
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[S + 3] * B, kv_dtype="bf16", out_dtype="f32")
+    ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
+    for li in range(2):
+        q = (wl.randn(300 + li, (B, S, Hq, d), torch.float32, DEV) * qscale).to(torch.bfloat16)
+        k = wl.randn(310 + li, (B, S, Hkv, d), torch.bfloat16, DEV)
+        v = (wl.randn(320 + li, (B, S, Hkv, d), torch.float32, DEV) * vscale).to(torch.bfloat16)
+        out = lay.prefill(li, q, k, v)
+        ref = ora.prefill(li, to_f64(q), to_f64(k), to_f64(v))
+        assert not torch.isnan(out).any()
+        max_abs, rel_l2 = errors(out, ref)
+        assert rel_l2 <= 1e-3 and max_abs <= 2e-3 * max(1.0, vscale), (li, max_abs, rel_l2)
+    for t in range(3):
+        for li in range(2):
+            q = (wl.randn(330 + 10 * t + li, (B, Hq, d), torch.float32, DEV) * qscale).to(torch.bfloat16)
+            k = wl.randn(340 + 10 * t + li, (B, Hkv, d), torch.bfloat16, DEV)
+            v = (wl.randn(350 + 10 * t + li, (B, Hkv, d), torch.float32, DEV) * vscale).to(torch.bfloat16)
+            ora.append(li, to_f64(k), to_f64(v))
+            out = lay.append_decode(li, k, v, q)
+            max_abs, rel_l2 = errors(out, ora.decode(li, to_f64(q)))
+            assert rel_l2 <= 1e-3 and max_abs <= 2e-3 * max(1.0, vscale), (t, li, max_abs, rel_l2)
+    lay.close()
