@@ -189,20 +189,40 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
     if (W > 0 && k0 + kPfKeys - 1 < r0k - W + 1) continue;
     const bool need_mask = (k0 + kPfKeys - 1 > r0k) || (W > 0 && k0 < r0k + 31 - W + 1);
 
+    // All 16 K fragments of the tile are requested from LDS before the first MFMA (the scheduling barrier keeps the
+    // compiler from sinking each read next to its use, which would expose the LDS latency sixteen times).
+    bf16x8_t kf[2][8];
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      const uint16_t* kb = sK(buf) + sub * kBlockElems + (key_row >> 4) * 2048 + (key_row & 15) * 8;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) kf[sub][kk] = *(const bf16x8_t*)(kb + (2 * kk + hh) * 128);
+    }
+    __builtin_amdgcn_sched_barrier(0);
     // the wavefront feeding the matrix pipe wins issue arbitration over its SIMD mate's softmax arithmetic
     __builtin_amdgcn_s_setprio(3);
     floatx16_t s[2];
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
+    for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
       for (int i = 0; i < 16; ++i) s[sub][i] = 0.f;
-      const uint16_t* kb = sK(buf) + sub * kBlockElems + (key_row >> 4) * 2048 + (key_row & 15) * 8;
 #pragma unroll
-      for (int kk = 0; kk < 8; ++kk) {
-        const bf16x8_t kf = *(const bf16x8_t*)(kb + (2 * kk + hh) * 128);
-        s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[sub], 0, 0, 0);
+    for (int sub = 0; sub < 2; ++sub)  // fragments are consumed in the order they were requested
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk)
+        s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[sub][kk], qf[kk], s[sub], 0, 0, 0);
+    // The 16 V fragments are requested now, so that they arrive while the softmax arithmetic runs.
+    halfx8_t vf[2][2][4];
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        // dims 32*db + col, keys of piece g = 2u + hh
+        const uint16_t* vb = sV(buf) + sub * kBlockElems + (col >> 4) * 512 + ((2 * u + hh) * 16 + (col & 15)) * 8;
+#pragma unroll
+        for (int db = 0; db < 4; ++db) vf[sub][u][db] = *(const halfx8_t*)(vb + db * 1024);
       }
-    }
+    __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_setprio(0);
     if (need_mask) {
 #pragma unroll
@@ -249,13 +269,9 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
           pw[jp] = pf_pack_f16(p0, p1);
         }
         const halfx8_t pf = __builtin_bit_cast(halfx8_t, pw);
-        // V fragment of this slab: dims 32*db + col, keys of piece g = 2u + hh
-        const uint16_t* vb = sV(buf) + sub * kBlockElems + (col >> 4) * 512 + ((2 * u + hh) * 16 + (col & 15)) * 8;
 #pragma unroll
-        for (int db = 0; db < 4; ++db) {
-          const halfx8_t vf = *(const halfx8_t*)(vb + db * 1024);
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf, o[db], 0, 0, 0);
-        }
+        for (int db = 0; db < 4; ++db)
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[sub][u][db], pf, o[db], 0, 0, 0);
       }
     }
     lsum += psum;
