@@ -180,7 +180,7 @@ struct PrefillLaunch {
   int batch = 0, S = 0, Hq = 0, Hkv = 0, G = 0, D = 0;
   int kv_dtype = 0, out_dtype = 0;
   float scale = 0.f;
-  int waves = 0;  // wavefronts per workgroup on the tiled path: 4, 8, or 0 = default (4)
+  int waves = 0;  // wavefronts per workgroup on the tiled path: 4, 8, or 0 = by layer kind (8 full, 4 sliding)
 };
 hipError_t launch_prefill_tiled(const PrefillLaunch& a, hipStream_t s);
 hipError_t launch_prefill_rowmajor(const PrefillLaunch& a, hipStream_t s);
