@@ -326,7 +326,7 @@ def main():
         })
         if r["full_layer_ms"]:
             ach = r["full_layer_bytes"] / (r["full_layer_ms"] * 1e-3) / 1e9
-            line["roofline"] = {"kernel": "decode_tiled_kernel<bf16 out, full> (one full-attention layer; plus its combine launch when split)",
+            line["roofline"] = {"kernel": "decode_tiled_kernel<out, full, fused append> (one full-attention layer; plus its combine launch when split)",
                                 "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                 "frac": ach / HBM_PEAK_GBS, "launch_ms": r["full_layer_ms"],
                                 "bytes_per_launch": r["full_layer_bytes"],
