@@ -240,7 +240,12 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
     for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[0][i]);
 #pragma unroll
     for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[1][i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    // the other half of the row lives in lane l ^ 32: exchanged with the lane-swap instruction (vector ALU), not with
+    // an LDS permute, whose result would queue behind the V fragments requested just before
+    {
+      const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+      mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+    }
     const float m_new = fmaxf(m, mx);
     // rescale only when some row of the wavefront saw a new maximum (rare after the first tiles)
     if (__any(m_new > m)) {
