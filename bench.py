@@ -38,6 +38,7 @@ def parse():
     ap.add_argument("--chunk-keys", type=int, default=0)
     ap.add_argument("--fused-combine", type=int, default=-1)
     ap.add_argument("--prefill-waves", type=int, default=0)
+    ap.add_argument("--prefill-heads", type=int, default=0)
     ap.add_argument("--chunks", type=int, default=1, help="prefill32k: feed the prompt in this many equal chunks")
     ap.add_argument("--skip-standard", action="store_true", help="ragged64: time the MixAttention stack only")
     ap.add_argument("--two-call-append", action="store_true",
@@ -233,6 +234,8 @@ def run_prefill(args, mx, wl, torch, w):
     lay = mx.Layout(w.layers, B, Hq, Hkv, d, capacity=[S] * B, kv_dtype="bf16", out_dtype=args.out_dtype)
     if args.prefill_waves:
         lay.set_param(mx.PARAM_PREFILL_WAVES, args.prefill_waves)
+    if args.prefill_heads:
+        lay.set_param(mx.PARAM_PREFILL_HEADS, args.prefill_heads)
     # one q per layer kind is enough to time (values do not change the cost); K/V per writer layer
     q = wl.randn(wl.layer_seed(w.seed, 0, "q"), (B, S, Hq, d), torch.bfloat16, dev)
     kv = {}

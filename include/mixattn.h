@@ -180,7 +180,9 @@ typedef enum {
   MIXATTN_PARAM_FUSED_COMBINE = 1, /* 1: the last workgroup of a (sequence, kv head) merges the split-K partials
                                       itself; 0: separate combine launch */
   MIXATTN_PARAM_PREFILL_SIMPLE = 2, /* 1: force the scalar prefill kernel (testing) */
-  MIXATTN_PARAM_PREFILL_WAVES = 3   /* wavefronts per MFMA prefill workgroup: 4, 8, or 0 = by layer kind (8 full, 4 sliding) */
+  MIXATTN_PARAM_PREFILL_WAVES = 3,  /* wavefronts per MFMA prefill workgroup: 4, 8, or 0 = by layer kind (8 full, 4 sliding) */
+  MIXATTN_PARAM_PREFILL_HEADS = 4   /* query heads of one KV head served by one MFMA prefill workgroup: 1, 2, 4, or
+                                       0 = as many as divide the group size */
 } mixattn_param;
 int mixattn_set_param(mixattn_layout* L, int param, int64_t value);
 int mixattn_get_param(const mixattn_layout* L, int param, int64_t* value);

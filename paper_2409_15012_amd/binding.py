@@ -18,7 +18,7 @@ _lib = None
 
 FULL, SLIDING = 0, 1
 F32, BF16 = 0, 1
-PARAM_CHUNK_KEYS, PARAM_FUSED_COMBINE, PARAM_PREFILL_SIMPLE, PARAM_PREFILL_WAVES = 0, 1, 2, 3
+PARAM_CHUNK_KEYS, PARAM_FUSED_COMBINE, PARAM_PREFILL_SIMPLE, PARAM_PREFILL_WAVES, PARAM_PREFILL_HEADS = 0, 1, 2, 3, 4
 
 EXPORTS = [
     "mixattn_validate_config", "mixattn_create_layout", "mixattn_destroy_layout", "mixattn_reset",

@@ -41,6 +41,7 @@ struct TiledPrefillParams {
   // chunked prefill: sequence b held n_old = d_lens[b] - old_sub tokens before this chunk (d_lens == nullptr: 0).
   // Key index 0 of the K/V buffers is position 0 (stage_window == 0) or max(0, n_old - (stage_window - 1)).
   const int32_t* d_lens; int old_sub; int stage_window;
+  int hg;  // query heads per workgroup (all of one KV head): 1, 2 or 4, divides G and the wavefront count
 };
 
 // MFMA row m of a 32-key block holds key pi(m): bits 3 and 4 of m swapped, so that the 8 scores a lane owns per
@@ -67,7 +68,6 @@ __device__ inline uint32_t pf_pack_bf16(float lo, float hi) {
 
 template <typename OutT, int NW>
 __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillParams a) {
-  constexpr int kPfRows = 32 * NW;  // query rows per workgroup
   // two stages of one 64-key tile each (2 blocks of K, 2 blocks of V), filled by direct global->LDS loads
   // 64 KiB: stage s holds K at smem + s*16384 and V at smem + s*16384 + 8192 (elements).  Before the first tile
   // lands in stage 1 that stage stages the query rows; after the last tile the whole array stages the output rows.
@@ -75,28 +75,35 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
   auto sK = [&](int buf) { return smem + buf * (4 * kBlockElems); };
   auto sV = [&](int buf) { return smem + buf * (4 * kBlockElems) + 2 * kBlockElems; };
 
+  // A workgroup serves hg query heads of one KV head (they read the same K/V tiles) with NW / hg wavefronts each, so
+  // it spans 32 * NW / hg query rows: the more heads, the shorter the row span, the fewer keys a sliding-window
+  // tile walks beyond its window, and the more MFMAs share each tile load and barrier.
   // Workgroup ids go round-robin over the 8 XCDs, each with its own L2.  Map them so that one XCD works on the
-  // query tiles of one head at a time (ids = 8*slot + xcd): its L2 then holds one head's K/V stream, not eight.
-  const int n_qt = (a.S + kPfRows - 1) / kPfRows;
-  int qt, hq;
+  // query tiles of one head group at a time (ids = 8*slot + xcd): its L2 then holds one K/V stream, not eight.
+  const int wph = NW / a.hg;       // wavefronts per head
+  const int rows_wg = 32 * wph;    // query rows per workgroup
+  const int n_qt = (a.S + rows_wg - 1) / rows_wg;
+  const int n_hg = a.Hq / a.hg;
+  int qt, hgi;
   {
     const int id = blockIdx.x + gridDim.x * blockIdx.y;
-    if ((a.Hq & 7) == 0) {
+    if ((n_hg & 7) == 0) {
       const int xcd = id & 7, slot = id >> 3;
-      hq = xcd + 8 * (slot / n_qt);
+      hgi = xcd + 8 * (slot / n_qt);
       qt = n_qt - 1 - (slot % n_qt);  // longest rows first
     } else {
-      hq = id / n_qt;
+      hgi = id / n_qt;
       qt = n_qt - 1 - (id % n_qt);
     }
   }
   const int b = blockIdx.z;
-  const int h = hq / a.G;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int hq = hgi * a.hg + wave / wph;  // this wavefront's query head
+  const int h = hq / a.G;
   const int col = lane & 31, hh = lane >> 5;
-  const int q0 = qt * kPfRows;
-  const int r0 = q0 + wave * 32;  // first row of this wavefront
+  const int q0 = qt * rows_wg;
+  const int r0 = q0 + (wave % wph) * 32;  // first row of this wavefront
   const int row = r0 + col;
   const int S = a.S, W = a.window;
   const float c2 = a.scale_log2;
@@ -133,7 +140,7 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
   const u32x4_t* Kg = (const u32x4_t*)(a.Kt + (a.k_base[b] + (int64_t)h * (a.k_slots[b] >> 5)) * kBlockElems);
   const u32x4_t* Vg = (const u32x4_t*)(a.Vt + (a.v_base[b] + (int64_t)h * (a.v_slots[b] >> 5)) * kBlockElems);
 
-  const int last_row = min(q0 + kPfRows, S) - 1;
+  const int last_row = min(q0 + rows_wg, S) - 1;
   const int jt_hi = (last_row + qoff) / kPfKeys;
   const int jt_lo = W > 0 ? max(0, q0 + qoff - W + 1) / kPfKeys : 0;
   const int r0k = r0 + qoff, rowk = row + qoff;  // this wavefront's first row / this lane's row as key indices
@@ -340,12 +347,17 @@ hipError_t launch_prefill_tiled(const PrefillLaunch& L, hipStream_t s) {
   // its rows can see (8 is about 20 % slower at W = 1024).
   const bool f32 = L.out_dtype == MIXATTN_F32;
   const int waves = L.waves ? L.waves : (L.window == 0 ? 8 : 4);
+  // query heads per workgroup: the largest of 4, 2, 1 that divides the group size (and the wavefront count), unless set
+  int hg = L.heads;
+  if (hg <= 0) hg = (L.G % 4 == 0) ? 4 : (L.G % 2 == 0) ? 2 : 1;
+  if (L.G % hg != 0 || waves % hg != 0) hg = 1;
+  p.hg = hg;
+  const int rows_wg = 32 * waves / hg;
+  const dim3 grid((L.S + rows_wg - 1) / rows_wg, L.Hq / hg, L.batch), block(64 * waves);
   if (waves == 8) {
-    const dim3 grid((L.S + 255) / 256, L.Hq, L.batch), block(512);
     if (f32) hipLaunchKernelGGL((prefill_tiled_kernel<float, 8>), grid, block, 0, s, p);
     else hipLaunchKernelGGL((prefill_tiled_kernel<uint16_t, 8>), grid, block, 0, s, p);
   } else {
-    const dim3 grid((L.S + 127) / 128, L.Hq, L.batch), block(256);
     if (f32) hipLaunchKernelGGL((prefill_tiled_kernel<float, 4>), grid, block, 0, s, p);
     else hipLaunchKernelGGL((prefill_tiled_kernel<uint16_t, 4>), grid, block, 0, s, p);
   }

@@ -490,6 +490,7 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
   p.batch = L->batch; p.S = seq_len; p.Hq = L->Hq; p.Hkv = L->Hkv; p.G = L->G; p.D = L->D;
   p.kv_dtype = L->kv_dtype; p.out_dtype = L->out_dtype; p.scale = L->scale;
   p.waves = (int)L->prefill_waves;
+  p.heads = (int)L->prefill_heads;
 
   // commit of the chunk into this layer's cache (writer): reads lens(), writes n_old + seq_len to lens_other()
   auto commit = [&]() -> int {
@@ -731,6 +732,10 @@ int mixattn_set_param(mixattn_layout* L, int param, int64_t value) {
       if (value != 0 && value != 4 && value != 8) return MIXATTN_ERR_PARAM;
       L->prefill_waves = value;
       return MIXATTN_OK;
+    case MIXATTN_PARAM_PREFILL_HEADS:
+      if (value != 0 && value != 1 && value != 2 && value != 4) return MIXATTN_ERR_PARAM;
+      L->prefill_heads = value;
+      return MIXATTN_OK;
     default: return MIXATTN_ERR_PARAM;
   }
 }
@@ -742,6 +747,7 @@ int mixattn_get_param(const mixattn_layout* L, int param, int64_t* value) {
     case MIXATTN_PARAM_FUSED_COMBINE: *value = L->fused_combine; return MIXATTN_OK;
     case MIXATTN_PARAM_PREFILL_SIMPLE: *value = L->prefill_simple; return MIXATTN_OK;
     case MIXATTN_PARAM_PREFILL_WAVES: *value = L->prefill_waves; return MIXATTN_OK;
+    case MIXATTN_PARAM_PREFILL_HEADS: *value = L->prefill_heads; return MIXATTN_OK;
     default: return MIXATTN_ERR_PARAM;
   }
 }

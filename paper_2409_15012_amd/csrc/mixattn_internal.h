@@ -97,6 +97,7 @@ struct mixattn_layout {
   int64_t fused_combine = 0;
   int64_t prefill_simple = 0;
   int64_t prefill_waves = 0; // 0 = automatic
+  int64_t prefill_heads = 0; // 0 = automatic
   int device = 0;
   int n_cus = 256;
 };
@@ -181,6 +182,7 @@ struct PrefillLaunch {
   int kv_dtype = 0, out_dtype = 0;
   float scale = 0.f;
   int waves = 0;  // wavefronts per workgroup on the tiled path: 4, 8, or 0 = by layer kind (8 full, 4 sliding)
+  int heads = 0;  // query heads of one KV head per workgroup on the tiled path: 1, 2, 4, or 0 = as many as divide G
 };
 hipError_t launch_prefill_tiled(const PrefillLaunch& a, hipStream_t s);
 hipError_t launch_prefill_rowmajor(const PrefillLaunch& a, hipStream_t s);

@@ -137,6 +137,34 @@ def test_bf16_decode_bf16_output(mx):
     lay.close()
 
 
+# --------------------------------------------------------------------------- MFMA prefill, every workgroup shape
+@pytest.mark.parametrize("waves,heads", [(4, 1), (4, 2), (4, 4), (8, 1), (8, 2), (8, 4)])
+def test_bf16_prefill_workgroup_shapes(mx, waves, heads):
+    """The MFMA prefill kernel with 4 or 8 wavefronts serving 1, 2 or 4 query heads of a KV head per workgroup:
+    same results for every shape (S spans several query tiles of every shape and ends ragged)."""
+    d, S, W, Hq, Hkv, B = 128, 333, 96, 8, 2, 2
+    layers = _mixed_layers(W)
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[S + 2] * B, kv_dtype="bf16", out_dtype="f32")
+    lay.set_param(mx.PARAM_PREFILL_WAVES, waves)
+    lay.set_param(mx.PARAM_PREFILL_HEADS, heads)
+    ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
+    kv = {}
+    for li in range(len(layers)):
+        wr = lay.writer_of(li)
+        if wr == li:
+            kv[li] = (wl.randn(7000 + li, (B, S, Hkv, d), torch.bfloat16, DEV),
+                      wl.randn(7050 + li, (B, S, Hkv, d), torch.bfloat16, DEV))
+        q = wl.randn(7100 + li, (B, S, Hq, d), torch.bfloat16, DEV)
+        k, v = kv[wr]
+        out = lay.prefill(li, q, k, v)
+        ref = ora.prefill(li, to_f64(q), to_f64(k) if wr == li else None, to_f64(v) if wr == li else None)
+        assert_matches(out, ref, "bf16", "prefill layer %d (waves %d, heads %d)" % (li, waves, heads))
+    with pytest.raises(mx.MixAttnError) as ei:
+        lay.set_param(mx.PARAM_PREFILL_HEADS, 3)
+    assert ei.value.status == -9
+    lay.close()
+
+
 # --------------------------------------------------------------------------- bf16 prefill, small shapes
 @pytest.mark.parametrize("S,W,Hq,Hkv,B", [
     (1, 64, 8, 2, 1), (31, 48, 8, 2, 2), (100, 48, 8, 2, 2), (129, 64, 4, 4, 1), (300, 200, 8, 2, 2),
