@@ -8,8 +8,9 @@
 // fragment is one 16-byte LDS read per lane.  Scores use the bf16 MFMA (exact products of the bf16 inputs); the
 // probabilities are rounded to fp16 (11 significant bits) and multiply fp16 V on the fp16 MFMA: a bf16 rounding
 // of P would by itself cost about 1.6e-3 relative L2 error.
-// A workgroup of NW wavefronts owns 32*NW query rows of one query head (32 rows per wavefront) and walks the
-// 64-key tiles its rows can see, skipping tiles that are masked for all of them:
+// A workgroup of NW wavefronts (32 query rows each) serves hg query heads of one KV head, NW/hg wavefronts and
+// 32*NW/hg query rows per head, and walks the 64-key tiles its rows can see; a wavefront skips the tiles that are
+// masked for all of its rows:
 //   scores^T[key, row]  = K (A, 32 keys x 16 dims) x Q^T (B, 16 dims x 32 rows),  8 k-steps per 32-key block
 //   out^T[dim, row]    += V^T (A, 32 dims x 16 keys) x P^T (B, 16 keys x 32 rows), both fp16
 // Lane l holds query row l%32 in both products, so the online-softmax state and the accumulator rescale are
