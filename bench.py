@@ -8,7 +8,8 @@ path for one generated token per sequence: 8 KV appends (writer layers, fused in
 
 Other workloads (--workload): decode4k (batch 8, context 4096), prefill32k (batch 1, 32768-token prompt through
 the 24 layers), ragged64 (batch 64, context lengths uniform in [1024, 65536], MixAttention stack next to the
-all-full 24-layer stack).
+all-full 24-layer stack), variants (decode step by layer layout), gen31k (31000-token prompts prefilled, then
+1000 tokens generated, batch 32: the shape of the paper's inference-speed measurement, attention stack only).
 
 Everything on the timed path runs in libmixattn's kernels; torch provides device memory, the stream and events.
 The CPU oracle is used only for the `cpu_baseline` leg (and never feeds the GPU path).
@@ -33,7 +34,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="decode32k", choices=["decode32k", "decode4k", "prefill32k", "ragged64", "variants"])
+    ap.add_argument("--workload", default="decode32k", choices=["decode32k", "decode4k", "prefill32k", "ragged64", "variants", "gen31k"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-keys", type=int, default=0)
     ap.add_argument("--fused-combine", type=int, default=-1)
@@ -41,6 +42,10 @@ def parse():
     ap.add_argument("--prefill-heads", type=int, default=0)
     ap.add_argument("--chunks", type=int, default=1, help="prefill32k: feed the prompt in this many equal chunks")
     ap.add_argument("--skip-standard", action="store_true", help="ragged64: time the MixAttention stack only")
+    ap.add_argument("--with-standard", action="store_true", help="gen31k: also run the standard 24-layer stack")
+    ap.add_argument("--gen-batch", type=int, default=32)
+    ap.add_argument("--gen-prompt", type=int, default=31000)
+    ap.add_argument("--gen-new", type=int, default=1000)
     ap.add_argument("--two-call-append", action="store_true",
                     help="writer layers call append_kv and decode separately instead of append_decode")
     ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
@@ -293,6 +298,64 @@ def run_prefill(args, mx, wl, torch, w):
             "full_layer_ms": full_ms, "full_layer_flops": 4 * d * pairs_full * Hq * B}
 
 
+def run_generation(args, mx, wl, torch, layers, label):
+    """Prompt prefill followed by a generation loop through the attention stack (Section 4, "Inference Speed and
+    Memory Consumption": 31000 input and 1000 output tokens per request).  Every sequence of the batch has the same
+    prompt length; one K/V prompt tensor pair and one set of per-token tensors are reused for all layers (values do
+    not change the cost)."""
+    dev = "cuda:0"
+    B, S, T = args.gen_batch, args.gen_prompt, args.gen_new
+    Hq, Hkv, d = 32, 8, 128
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[S + T] * B, kv_dtype="bf16", out_dtype=args.out_dtype)
+    writer_of = [lay.writer_of(li) for li in range(len(layers))]
+    q = wl.randn(1, (B, S, Hq, d), torch.bfloat16, dev)
+    k = wl.randn(2, (B, S, Hkv, d), torch.bfloat16, dev)
+    v = wl.randn(3, (B, S, Hkv, d), torch.bfloat16, dev)
+    out = torch.empty((B, S, Hq, d), dtype=lay.out_torch, device=dev)
+    q1 = wl.randn(4, (B, Hq, d), torch.bfloat16, dev)
+    k1 = wl.randn(5, (B, Hkv, d), torch.bfloat16, dev)
+    v1 = wl.randn(6, (B, Hkv, d), torch.bfloat16, dev)
+    out1 = torch.empty((B, Hq, d), dtype=lay.out_torch, device=dev)
+
+    def prefill():
+        for li in range(len(layers)):
+            if writer_of[li] == li:
+                lay.prefill(li, q, k, v, out)
+            else:
+                # a reader directly after its writer reuses the staged prompt; otherwise it is handed K/V again
+                direct = writer_of[li] == li - 1 or (li > 0 and writer_of[li - 1] == writer_of[li])
+                lay.prefill(li, q, None if direct else k, None if direct else v, out)
+
+    def decode_step():
+        for li in range(len(layers)):
+            if writer_of[li] == li:
+                lay.append_decode(li, k1, v1, q1, out1)
+            else:
+                lay.decode(li, q1, out1)
+
+    # warm-up on the same layout (kernels, planner memo), then the timed run from empty caches
+    prefill()
+    for _ in range(3):
+        decode_step()
+    torch.cuda.synchronize()
+    lay.reset()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    prefill()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(T):
+        decode_step()
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    r = {"label": label, "batch": B, "prompt": S, "new_tokens": T, "prefill_s": t1 - t0, "decode_s": t2 - t1,
+         "total_s": t2 - t0, "output_tokens_per_s": B * T / (t2 - t0), "decode_only_tokens_per_s": B * T / (t2 - t1),
+         "ms_per_decode_step": (t2 - t1) * 1e3 / T, "kv_bytes_resident": lay.kv_bytes_live(),
+         "kv_bytes_allocated": lay.kv_bytes_allocated()}
+    lay.close()
+    return r
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -372,6 +435,24 @@ def main():
                      "unit": "tokens/s", "ms_per_step": base_row["ms_per_step"],
                      "config": {"workload": "layout variants at " + w.name, "batch": w.batch, "context": w.context},
                      "layouts": rows})
+    elif args.workload == "gen31k":
+        r_mix = run_generation(args, mx, wl, torch, wl.layout_mix24(), "mix24")
+        line = dict(base)
+        line.update({
+            "metric": "output tokens/s, %d-token prompts + %d generated tokens, batch %d, attention stack only "
+                      "(prefill + generation loop)" % (args.gen_prompt, args.gen_new, args.gen_batch),
+            "value": r_mix["output_tokens_per_s"], "unit": "tokens/s", "steps": args.gen_new, "warmup": 3,
+            "ms_per_step": r_mix["ms_per_decode_step"],
+            "config": {"workload": "gen_b%d_in%d_out%d" % (args.gen_batch, args.gen_prompt, args.gen_new),
+                       "batch": args.gen_batch, "prompt": args.gen_prompt, "new_tokens": args.gen_new,
+                       "window": 1024, "out_dtype": args.out_dtype},
+            "mix": r_mix,
+        })
+        if args.with_standard:
+            r_std = run_generation(args, mx, wl, torch, wl.layout_full24(), "standard24")
+            line["standard"] = r_std
+            line["total_time_ratio_standard_over_mix"] = r_std["total_s"] / r_mix["total_s"]
+            line["kv_bytes_ratio_standard_over_mix"] = r_std["kv_bytes_resident"] / r_mix["kv_bytes_resident"]
     else:  # ragged64
         w = wl.config(4)
         r_mix = run_decode(args, mx, wl, torch, w)
