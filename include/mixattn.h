@@ -144,6 +144,16 @@ int mixattn_append_decode(mixattn_layout* L, int layer, const void* k, const voi
 int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, const void* v, void* out,
                     int seq_len, void* stream);
 
+/* mixattn_prefill with a chunk length of its own per sequence (a serving batch mixes prompts of many lengths;
+   Section 4 measures 300 mixed requests).  seq_lens: host [batch], each >= 0, at least one > 0; a sequence with 0
+   takes no part (its caches are left as they are).  q, out: device, packed by sequence
+   [sum(seq_lens), n_q_heads, head_dim]; k, v: device [sum(seq_lens), n_kv_heads, head_dim] in the same order.
+   Everything else as mixattn_prefill: row i of sequence b sits at position n_b + i, writers commit, readers follow
+   their writer's call for the same chunk and may pass k = v = NULL (MFMA path) when the staged copy was made for
+   the same cache and the same seq_lens.  Errors: ORDER (negative or all-zero seq_lens, ...), CAPACITY, NULL. */
+int mixattn_prefill_varlen(mixattn_layout* L, int layer, const void* q, const void* k, const void* v, void* out,
+                           const int32_t* seq_lens, void* stream);
+
 /* Bulk fill of an empty cache without attention (sets up decode workloads and ragged batches).  Writer layers
    only.  k, v: device, packed [sum(seq_lens), n_kv_heads, head_dim]; seq_lens: host [batch], each >= 0.  n_b
    becomes seq_lens[b]; the cache ends in exactly the state seq_lens[b] appends would leave.  The host array is

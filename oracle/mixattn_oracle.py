@@ -259,6 +259,39 @@ class OracleStack:
             out[b, i, j] = self._attend(layer, b, q[b, i, j], j, first[b] + i, K, V)
         return out
 
+    def prefill_ragged(self, layer: int, q: np.ndarray, k: Optional[np.ndarray], v: Optional[np.ndarray],
+                       seq_lens: Sequence[int]) -> np.ndarray:
+        """prefill() with a chunk length of its own per sequence (Section 4 serves requests of mixed
+        lengths).  q [T, Hq, d], k, v [T, Hkv, d] packed by sequence, T = sum(seq_lens); a
+        sequence with length 0 takes no part.  Row i of sequence b sits at position n_b + i."""
+        q = np.asarray(q, dtype=np.float64)
+        lens = [int(x) for x in seq_lens]
+        if len(lens) != self.B or any(x < 0 for x in lens) or q.shape[0] != sum(lens):
+            raise ValueError("seq_lens do not match the batch or the packed rows")
+        first = np.concatenate([[0], np.cumsum(lens)]).astype(int)
+        writes = self.duplicate or self.is_writer(layer)
+        if writes:
+            if k is None or v is None:
+                raise ValueError("writer layer needs k and v")
+            k = np.asarray(k, dtype=np.float64).reshape(-1, self.Hkv, self.d)
+            v = np.asarray(v, dtype=np.float64).reshape(-1, self.Hkv, self.d)
+            start = [self.seq_len(layer, b) for b in range(self.B)]
+            key = self._store_key(layer)
+            for b in range(self.B):
+                self._K[key][b] = np.concatenate([self._K[key][b], k[first[b]:first[b + 1]]], axis=0)
+                self._V[key][b] = np.concatenate([self._V[key][b], v[first[b]:first[b + 1]]], axis=0)
+        else:
+            if any(self.seq_len(layer, b) < lens[b] for b in range(self.B)):
+                raise ValueError("reader prefill needs the writer's chunk in the cache")
+            start = [self.seq_len(layer, b) - lens[b] for b in range(self.B)]
+        out = np.full((q.shape[0], self.Hq, self.d), np.nan)
+        for b in range(self.B):
+            K, V = self.history(layer, b)
+            for i in range(lens[b]):
+                for j in range(self.Hq):
+                    out[first[b] + i, j] = self._attend(layer, b, q[first[b] + i, j], j, start[b] + i, K, V)
+        return out
+
     def cache_view(self, layer: int, b: int) -> List[Tuple[int, int]]:
         """[(slot, position)] for every valid slot of the cache `layer` reads, sequence b."""
         sp = self.layers[self.writer[self.layers[layer].cache_id]]  # the writer's kind decides the storage

@@ -22,7 +22,8 @@ PARAM_CHUNK_KEYS, PARAM_FUSED_COMBINE, PARAM_PREFILL_SIMPLE, PARAM_PREFILL_WAVES
 
 EXPORTS = [
     "mixattn_validate_config", "mixattn_create_layout", "mixattn_destroy_layout", "mixattn_reset",
-    "mixattn_append_kv", "mixattn_decode", "mixattn_append_decode", "mixattn_prefill", "mixattn_load_kv", "mixattn_n_caches",
+    "mixattn_append_kv", "mixattn_decode", "mixattn_append_decode", "mixattn_prefill", "mixattn_prefill_varlen",
+    "mixattn_load_kv", "mixattn_n_caches",
     "mixattn_cache_of", "mixattn_seq_len", "mixattn_slot_of", "mixattn_slot_for", "mixattn_read_cache",
     "mixattn_read_device_lens", "mixattn_kv_bytes_allocated", "mixattn_kv_bytes_live", "mixattn_step_read_bytes",
     "mixattn_set_param", "mixattn_get_param", "mixattn_strerror", "mixattn_last_hip_error", "mixattn_version",
@@ -66,6 +67,7 @@ def load():
     lib.mixattn_decode.argtypes = [vp, i32, vp, vp, vp]
     lib.mixattn_append_decode.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     lib.mixattn_prefill.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
+    lib.mixattn_prefill_varlen.argtypes = [vp, i32, vp, vp, vp, vp, C.POINTER(C.c_int32), vp]
     lib.mixattn_load_kv.argtypes = [vp, i32, vp, vp, C.POINTER(C.c_int32), vp]
     lib.mixattn_n_caches.argtypes = [vp]
     lib.mixattn_cache_of.argtypes = [vp, i32, C.POINTER(C.c_int), C.POINTER(C.c_int)]
@@ -216,6 +218,24 @@ class Layout:
             self._dtype_check(out, self.out_torch, (B, S, self.Hq, self.d))
         self._check(self.lib.mixattn_prefill(self.h, layer, _ptr(q), _ptr(k), _ptr(v), _ptr(out), S, _stream()),
                     "mixattn_prefill")
+        return out
+
+    def prefill_varlen(self, layer: int, q: torch.Tensor, k: Optional[torch.Tensor], v: Optional[torch.Tensor],
+                       seq_lens: Sequence[int], out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        total = int(sum(seq_lens))
+        self._dtype_check(q, self.kv_torch, (total, self.Hq, self.d))
+        for t in (k, v):
+            if t is not None:
+                self._dtype_check(t, self.kv_torch, (total, self.Hkv, self.d))
+        if out is None:
+            out = torch.empty((total, self.Hq, self.d), dtype=self.out_torch, device=q.device)
+        else:
+            self._dtype_check(out, self.out_torch, (total, self.Hq, self.d))
+        if len(seq_lens) != self.batch:
+            raise ValueError("seq_lens needs one entry per sequence")
+        lens = (C.c_int32 * self.batch)(*[int(x) for x in seq_lens])
+        self._check(self.lib.mixattn_prefill_varlen(self.h, layer, _ptr(q), _ptr(k), _ptr(v), _ptr(out), lens,
+                                                    _stream()), "mixattn_prefill_varlen")
         return out
 
     def load_kv(self, layer: int, k: torch.Tensor, v: torch.Tensor, seq_lens: Sequence[int]):

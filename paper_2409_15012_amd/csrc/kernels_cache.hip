@@ -18,6 +18,37 @@ hipError_t launch_fill_i32(int32_t* p, int32_t value, int64_t n, hipStream_t s) 
   return hipGetLastError();
 }
 
+// Per-sequence tables (first packed row, row count) written by a kernel that carries the values in its arguments:
+// stream-ordered, no host synchronisation and no pinned staging buffer to recycle.
+struct SeqTableChunk {
+  int64_t first[64];
+  int32_t len[64];
+};
+__global__ __launch_bounds__(64) void set_seq_tables_kernel(int64_t* d_first, int32_t* d_len, SeqTableChunk c, int base,
+                                                            int n) {
+  const int i = threadIdx.x;
+  if (i < n) {
+    d_first[base + i] = c.first[i];
+    d_len[base + i] = c.len[i];
+  }
+}
+
+hipError_t launch_set_seq_tables(int64_t* d_first, int32_t* d_len, const int64_t* first, const int32_t* len, int n,
+                                 hipStream_t s) {
+  for (int base = 0; base < n; base += 64) {
+    SeqTableChunk c;
+    const int m = n - base < 64 ? n - base : 64;
+    for (int i = 0; i < 64; ++i) {
+      c.first[i] = i < m ? first[base + i] : 0;
+      c.len[i] = i < m ? len[base + i] : 0;
+    }
+    hipLaunchKernelGGL(set_seq_tables_kernel, dim3(1), dim3(64), 0, s, d_first, d_len, c, base, m);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
 // ------------------------------------------------------------------------------------------------
 // Append one token per sequence.  One workgroup per sequence so that the length is read once, used by
 // every thread, and bumped by one thread after all stores of this workgroup were issued.
@@ -128,8 +159,8 @@ __device__ inline SlotSource slot_source(const StoreLaunch& a, int s, int n_old,
 }
 
 __device__ inline void store_lengths(const StoreLaunch& a, int b, int& n_old, int& n_new, int& off) {
-  n_old = a.d_n_old ? a.d_n_old[b] - a.old_sub : 0;
   const int add = a.d_src_len ? a.d_src_len[b] : a.uniform_len;
+  n_old = a.d_n_old ? a.d_n_old[b] - (a.old_sub ? add : 0) : 0;
   n_new = n_old + add;
   off = (a.stage_window > 0 && n_old > a.stage_window - 1) ? n_old - (a.stage_window - 1) : 0;
 }

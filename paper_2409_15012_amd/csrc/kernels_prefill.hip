@@ -39,9 +39,13 @@ struct TiledPrefillParams {
   const uint16_t* Vt; const int64_t* v_base; const int32_t* v_slots;  // fp16 tiles
   int window, S, Hq, G;
   float scale_log2;
-  // chunked prefill: sequence b held n_old = d_lens[b] - old_sub tokens before this chunk (d_lens == nullptr: 0).
-  // Key index 0 of the K/V buffers is position 0 (stage_window == 0) or max(0, n_old - (stage_window - 1)).
+  // chunked prefill: sequence b held n_old = d_lens[b] - (old_sub ? chunk length : 0) tokens before this chunk
+  // (d_lens == nullptr: 0).  Key index 0 of the K/V buffers is position 0 (stage_window == 0) or
+  // max(0, n_old - (stage_window - 1)).
   const int32_t* d_lens; int old_sub; int stage_window;
+  // chunks of different lengths: sequence b's rows are q_first[b] .. + q_len[b] - 1 of the packed q / out tensors
+  // (nullptr: rows b*S .. b*S + S - 1); S is then the longest chunk
+  const int64_t* q_first; const int32_t* q_len;
   int hg;  // query heads per workgroup (all of one KV head): 1, 2 or 4, divides G and the wavefront count
 };
 
@@ -106,10 +110,13 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
   const int q0 = qt * rows_wg;
   const int r0 = q0 + (wave % wph) * 32;  // first row of this wavefront
   const int row = r0 + col;
-  const int S = a.S, W = a.window;
+  const int S = a.q_len ? a.q_len[b] : a.S;  // this sequence's chunk length
+  const int W = a.window;
+  if (q0 >= S) return;                         // the whole workgroup: nothing before this touches a barrier
+  const int64_t qrow0 = a.q_first ? a.q_first[b] : (int64_t)b * a.S;  // first row of the sequence in q / out
   const float c2 = a.scale_log2;
   // query row i sits at key index i + qoff of the K/V buffers
-  const int n_old = a.d_lens ? a.d_lens[b] - a.old_sub : 0;
+  const int n_old = a.d_lens ? a.d_lens[b] - (a.old_sub ? S : 0) : 0;
   const int qoff = (a.stage_window > 0 && n_old > a.stage_window - 1) ? a.stage_window - 1 : n_old;
 
   // Q^T fragments: lane (row, hh) holds dims kk*16 + hh*8 .. +7.  With 4 wavefronts each one first copies its 32
@@ -123,12 +130,12 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int r = min(r0 + 4 * i + (lane >> 4), S - 1);  // rows past the prompt re-read the last row (never stored)
-      const uint16_t* src = a.q + (((int64_t)b * S + r) * a.Hq + hq) * kTiledDim + (lane & 15) * 8;
+      const uint16_t* src = a.q + ((qrow0 + r) * a.Hq + hq) * kTiledDim + (lane & 15) * 8;
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                        (__attribute__((address_space(3))) void*)(slice + i * 512), 16, 0, 0);
     }
   } else {
-    const uint16_t* qp = a.q + (((int64_t)b * S + row) * a.Hq + hq) * kTiledDim + hh * 8;
+    const uint16_t* qp = a.q + ((qrow0 + row) * a.Hq + hq) * kTiledDim + hh * 8;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
       u32x4_t raw = {0u, 0u, 0u, 0u};
@@ -312,10 +319,10 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
       const int rl = 4 * i + (lane >> 4);
       const u32x4_t v = *(const u32x4_t*)(slice + rl * kRowPitch + (lane & 15) * 8);
       if (r0 + rl < S)
-        *(u32x4_t*)((uint16_t*)a.out + (((int64_t)b * S + r0 + rl) * a.Hq + hq) * kTiledDim + (lane & 15) * 8) = v;
+        *(u32x4_t*)((uint16_t*)a.out + ((qrow0 + r0 + rl) * a.Hq + hq) * kTiledDim + (lane & 15) * 8) = v;
     }
   } else if (row < S) {
-    OutT* op = (OutT*)a.out + (((int64_t)b * S + row) * a.Hq + hq) * kTiledDim;
+    OutT* op = (OutT*)a.out + ((qrow0 + row) * a.Hq + hq) * kTiledDim;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -343,6 +350,7 @@ hipError_t launch_prefill_tiled(const PrefillLaunch& L, hipStream_t s) {
   p.window = L.window; p.S = L.S; p.Hq = L.Hq; p.G = L.G;
   p.scale_log2 = L.scale * kLog2e;
   p.d_lens = L.d_lens; p.old_sub = L.old_sub; p.stage_window = L.stage_window;
+  p.q_first = L.d_q_first; p.q_len = L.d_q_len;
   // Full causal layers: 8 wavefronts (256 query rows) share each K/V tile, which halves the tile loads per row
   // (about 6 % faster).  Sliding layers: 4 wavefronts (128 rows), because a taller workgroup spans more keys than
   // its rows can see (8 is about 20 % slower at W = 1024).
@@ -384,6 +392,8 @@ struct RowPrefillParams {
   // or position mod ring for a sliding cache that has not yet received this chunk)
   const void* Kc; const void* Vc; const int64_t* d_base; const int32_t* d_slots;
   const int32_t* d_lens; int old_sub; int ring;
+  // chunks of different lengths: rows q_first[b] .. + q_len[b] - 1 of the packed tensors (nullptr: uniform S)
+  const int64_t* q_first; const int32_t* q_len;
 };
 
 template <typename T, typename OutT>
@@ -391,9 +401,11 @@ __global__ __launch_bounds__(256) void prefill_rowmajor_kernel(RowPrefillParams 
   const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int hq = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x & 63;
-  if (i >= a.S) return;
+  const int S = a.q_len ? a.q_len[b] : a.S;
+  if (i >= S) return;
+  const int64_t qrow0 = a.q_first ? a.q_first[b] : (int64_t)b * a.S;
   const int h = hq / a.G, D = a.D;
-  const T* qp = (const T*)a.q + (((int64_t)b * a.S + i) * a.Hq + hq) * D;
+  const T* qp = (const T*)a.q + ((qrow0 + i) * a.Hq + hq) * D;
   float qv[4], acc[4];
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
@@ -401,7 +413,7 @@ __global__ __launch_bounds__(256) void prefill_rowmajor_kernel(RowPrefillParams 
     qv[t] = d < D ? pf_load<T>(qp + d) : 0.f;
     acc[t] = 0.f;
   }
-  const int n_old = a.d_lens ? a.d_lens[b] - a.old_sub : 0;
+  const int n_old = a.d_lens ? a.d_lens[b] - (a.old_sub ? S : 0) : 0;
   const int pos = n_old + i;  // absolute position of this query row
   const int lo = a.window > 0 ? max(0, pos - a.window + 1) : 0;
   const int slots = a.d_lens ? a.d_slots[b] : 0;
@@ -410,7 +422,7 @@ __global__ __launch_bounds__(256) void prefill_rowmajor_kernel(RowPrefillParams 
     const T* kp;
     const T* vp;
     if (p >= n_old) {
-      const int64_t off = (((int64_t)b * a.S + (p - n_old)) * a.Hkv + h) * D;
+      const int64_t off = ((qrow0 + (p - n_old)) * a.Hkv + h) * D;
       kp = (const T*)a.k + off;
       vp = (const T*)a.v + off;
     } else {
@@ -438,7 +450,7 @@ __global__ __launch_bounds__(256) void prefill_rowmajor_kernel(RowPrefillParams 
     }
     m = m_new;
   }
-  OutT* op = (OutT*)a.out + (((int64_t)b * a.S + i) * a.Hq + hq) * D;
+  OutT* op = (OutT*)a.out + ((qrow0 + i) * a.Hq + hq) * D;
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
     const int d = lane + 64 * t;
@@ -456,6 +468,7 @@ hipError_t launch_prefill_rowmajor(const PrefillLaunch& L, hipStream_t s) {
   p.window = L.window; p.S = L.S; p.Hq = L.Hq; p.Hkv = L.Hkv; p.G = L.G; p.D = L.D; p.scale = L.scale;
   p.Kc = L.Kc; p.Vc = L.Vc; p.d_base = L.c_base; p.d_slots = L.c_slots; p.d_lens = L.d_lens; p.old_sub = L.old_sub;
   p.ring = L.ring;
+  p.q_first = L.d_q_first; p.q_len = L.d_q_len;
   const dim3 grid((L.S + 3) / 4, L.Hq, L.batch), block(256);
   const bool f32 = L.kv_dtype == MIXATTN_F32, of32 = L.out_dtype == MIXATTN_F32;
   if (f32 && of32) hipLaunchKernelGGL((prefill_rowmajor_kernel<float, float>), grid, block, 0, s, p);

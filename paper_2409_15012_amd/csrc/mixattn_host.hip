@@ -56,7 +56,8 @@ void free_layout(mixattn_layout* L) {
     if (c.d_slots) (void)hipFree(c.d_slots);
   }
   void* ptrs[] = {L->d_lens_all, L->scratch.acc, L->scratch.ml, L->scratch.counters, L->stageK, L->stageV,
-                  L->d_stage_lens, L->d_stage_src, L->d_readback, L->d_stage_base, L->d_stage_slots};
+                  L->d_stage_lens, L->d_stage_src, L->d_readback, L->d_stage_base, L->d_stage_slots,
+                  L->d_q_first, L->d_q_len};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   delete L;
@@ -225,6 +226,8 @@ int mixattn_create_layout(const mixattn_config* cfg, mixattn_layout** out) {
   }
   if (st == MIXATTN_OK) st = dev_alloc((void**)&L->d_stage_lens, sizeof(int32_t) * B);
   if (st == MIXATTN_OK) st = dev_alloc((void**)&L->d_stage_src, sizeof(int64_t) * B);
+  if (st == MIXATTN_OK) st = dev_alloc((void**)&L->d_q_first, sizeof(int64_t) * B);
+  if (st == MIXATTN_OK) st = dev_alloc((void**)&L->d_q_len, sizeof(int32_t) * B);
   if (st == MIXATTN_OK) st = dev_alloc((void**)&L->d_stage_base, sizeof(int64_t) * B);
   if (st == MIXATTN_OK) st = dev_alloc((void**)&L->d_stage_slots, sizeof(int32_t) * B);
   if (st == MIXATTN_OK) st = dev_alloc(&L->d_readback, 2 * kMaxHeadDim * sizeof(float));
@@ -445,11 +448,12 @@ static int ensure_stage(mixattn_layout* L, int64_t blocks_per_head) {
   return MIXATTN_OK;
 }
 
-int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, const void* v, void* out,
-                    int seq_len, void* stream) {
-  if (!L || !q || !out) return MIXATTN_ERR_NULL;
-  if (layer < 0 || layer >= L->n_layers) return MIXATTN_ERR_LAYER;
-  if (seq_len < 1) return MIXATTN_ERR_ORDER;
+// Prompt attention for a chunk of lens[b] tokens per sequence (varlen) or seq_len tokens for every sequence
+// (lens == nullptr).  In the varlen case seq_len is the longest chunk and q / k / v / out are packed by sequence.
+static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void* k, const void* v, void* out,
+                        const int32_t* lens, int seq_len, void* stream) {
+  const bool varlen = lens != nullptr;
+  auto len_of = [&](int b) -> int64_t { return varlen ? lens[b] : seq_len; };
   const int ci = L->layer_cache[layer];
   Cache& c = L->caches[ci];
   const bool writer = c.writer == layer;
@@ -459,7 +463,9 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
   const bool reuse_stage = !k && !v;
   if (reuse_stage) {
     if (writer || !L->tiled || L->prefill_simple) return MIXATTN_ERR_NULL;
-    if (L->stage_cache != ci || L->stage_len != seq_len) return MIXATTN_ERR_ORDER;
+    if (L->stage_cache != ci || (int)L->stage_lens.size() != L->batch) return MIXATTN_ERR_ORDER;
+    for (int b = 0; b < L->batch; ++b)
+      if (L->stage_lens[b] != len_of(b)) return MIXATTN_ERR_ORDER;
   } else if (!k || !v) {
     return MIXATTN_ERR_NULL;
   }
@@ -467,12 +473,12 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
   bool chunked = false;
   int64_t max_new = 0, max_old = 0;
   for (int b = 0; b < L->batch; ++b) {
-    const int64_t n_old = writer ? c.len[b] : c.len[b] - seq_len;
+    const int64_t n_old = writer ? c.len[b] : c.len[b] - len_of(b);
     if (n_old < 0) return MIXATTN_ERR_ORDER;  // the writer's prefill of this chunk has not run
-    if (c.kind == MIXATTN_FULL && n_old + seq_len > L->capacity[b]) return MIXATTN_ERR_CAPACITY;
-    if (n_old + seq_len > INT32_MAX) return MIXATTN_ERR_CAPACITY;
+    if (c.kind == MIXATTN_FULL && n_old + len_of(b) > L->capacity[b]) return MIXATTN_ERR_CAPACITY;
+    if (n_old + len_of(b) > INT32_MAX) return MIXATTN_ERR_CAPACITY;
     chunked |= n_old > 0;
-    max_new = std::max(max_new, n_old + seq_len);
+    max_new = std::max(max_new, n_old + len_of(b));
     max_old = std::max(max_old, n_old);
   }
   // Readers of a ring come after their writer's commit, which has overwritten keys the chunk's first rows need:
@@ -483,6 +489,31 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
   if (simple && L->tiled && chunked) return MIXATTN_ERR_ORDER;  // the cross-check path keeps to whole prompts
   hipStream_t s = (hipStream_t)stream;
   const int attn_window = L->layers[layer].kind == MIXATTN_SLIDING ? L->layers[layer].window : 0;
+  // per-sequence row tables of a varlen call (every kernel of this call reads them after this point of the stream)
+  const int64_t* d_first = nullptr;
+  const int32_t* d_len = nullptr;
+  if (varlen) {
+    std::vector<int64_t> first(L->batch);
+    int64_t run = 0;
+    for (int b = 0; b < L->batch; ++b) {
+      first[b] = run;
+      run += lens[b];
+    }
+    HIP_TRY(launch_set_seq_tables(L->d_q_first, L->d_q_len, first.data(), lens, L->batch, s));
+    d_first = L->d_q_first;
+    d_len = L->d_q_len;
+  }
+  // where the chunk's tokens sit in the caller's tensors
+  auto set_source = [&](StoreLaunch& st) {
+    st.k_src = k; st.v_src = v;
+    st.uniform_len = varlen ? 0 : seq_len;
+    st.d_src_first = d_first; st.d_src_len = d_len;
+  };
+  auto remember_stage = [&]() {
+    L->stage_cache = ci;
+    L->stage_lens.resize(L->batch);
+    for (int b = 0; b < L->batch; ++b) L->stage_lens[b] = (int32_t)len_of(b);
+  };
 
   PrefillLaunch p;
   p.q = q; p.out = out; p.k_src = k; p.v_src = v;
@@ -491,12 +522,13 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
   p.kv_dtype = L->kv_dtype; p.out_dtype = L->out_dtype; p.scale = L->scale;
   p.waves = (int)L->prefill_waves;
   p.heads = (int)L->prefill_heads;
+  p.d_q_first = d_first; p.d_q_len = d_len;
 
   // commit of the chunk into this layer's cache (writer): reads lens(), writes n_old + seq_len to lens_other()
   auto commit = [&]() -> int {
     StoreLaunch st;
     st.K = c.K; st.V = c.V; st.d_base = c.d_base; st.d_slots = c.d_slots; st.window = c.window;
-    st.k_src = k; st.v_src = v; st.uniform_len = seq_len;
+    set_source(st);
     st.d_n_old = c.lens(); st.old_sub = 0;
     if (L->tiled) {
       st.Kold = c.K; st.Vold = c.V; st.old_base = c.d_base; st.old_slots = c.d_slots; st.old_window = c.window;
@@ -507,7 +539,7 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
     st.max_slots = (int)(c.window > 0 ? std::min<int64_t>(max_new, c.window) : max_new);
     HIP_TRY(L->tiled ? launch_store_tiled(st, s) : launch_store_rowmajor(st, s));
     c.cur ^= 1;
-    for (int b = 0; b < L->batch; ++b) c.len[b] += seq_len;
+    for (int b = 0; b < L->batch; ++b) c.len[b] += len_of(b);
     return MIXATTN_OK;
   };
 
@@ -523,7 +555,7 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
     }
     const bool lens_hold_chunk = !(writer && sliding_cache);
     p.d_lens = (!L->tiled && chunked) ? c.lens() : nullptr;
-    p.old_sub = lens_hold_chunk ? seq_len : 0;
+    p.old_sub = lens_hold_chunk ? 1 : 0;
     HIP_TRY(launch_prefill_rowmajor(p, s));
     if (writer && sliding_cache) {
       int e = commit();
@@ -546,21 +578,20 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
       StoreLaunch st;
       st.K = nullptr; st.V = L->stageV; st.v_as_f16 = 1;
       st.d_base = L->d_stage_base; st.d_slots = L->d_stage_slots; st.window = 0;
-      st.k_src = k; st.v_src = v; st.uniform_len = seq_len;
+      set_source(st);
       if (chunked) {
-        st.d_n_old = c.lens(); st.old_sub = seq_len;  // lengths already include the chunk
+        st.d_n_old = c.lens(); st.old_sub = 1;  // lengths already include the chunk
         st.Vold = c.V; st.old_base = c.d_base; st.old_slots = c.d_slots; st.old_window = 0;
       }
       st.batch = L->batch; st.Hkv = L->Hkv; st.D = L->D; st.elem = L->elem;
       st.max_slots = (int)max_new;
       HIP_TRY(launch_store_tiled(st, s));
-      L->stage_cache = ci;
-      L->stage_len = seq_len;
+      remember_stage();
     }
     p.Kt = c.K; p.k_base = c.d_base; p.k_slots = c.d_slots;
     p.Vt = L->stageV; p.v_base = L->d_stage_base; p.v_slots = L->d_stage_slots;
     p.stage_window = 0;
-    p.d_lens = chunked ? c.lens() : nullptr; p.old_sub = seq_len;
+    p.d_lens = chunked ? c.lens() : nullptr; p.old_sub = 1;
     HIP_TRY(launch_prefill_tiled(p, s));
     return MIXATTN_OK;
   }
@@ -577,7 +608,7 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
     st.K = L->stageK; st.V = L->stageV; st.v_as_f16 = 1;
     st.d_base = L->d_stage_base; st.d_slots = L->d_stage_slots; st.window = 0;
     st.stage_window = W;
-    st.k_src = k; st.v_src = v; st.uniform_len = seq_len;
+    set_source(st);
     if (chunked) {  // writer (readers past the first chunk always reuse): lengths do not include the chunk yet
       st.d_n_old = c.lens(); st.old_sub = 0;
       st.Kold = c.K; st.Vold = c.V; st.old_base = c.d_base; st.old_slots = c.d_slots; st.old_window = W;
@@ -585,20 +616,40 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
     st.batch = L->batch; st.Hkv = L->Hkv; st.D = L->D; st.elem = L->elem;
     st.max_slots = (int)span;
     HIP_TRY(launch_store_tiled(st, s));
-    L->stage_cache = ci;
-    L->stage_len = seq_len;
+    remember_stage();
   }
   p.Kt = L->stageK; p.k_base = L->d_stage_base; p.k_slots = L->d_stage_slots;
   p.Vt = L->stageV; p.v_base = L->d_stage_base; p.v_slots = L->d_stage_slots;
   p.stage_window = W;
   p.d_lens = chunked ? c.lens() : nullptr;
-  p.old_sub = writer ? 0 : seq_len;
+  p.old_sub = writer ? 0 : 1;
   HIP_TRY(launch_prefill_tiled(p, s));
   if (writer) {
     int e = commit();
     if (e != MIXATTN_OK) return e;
   }
   return MIXATTN_OK;
+}
+
+int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, const void* v, void* out,
+                    int seq_len, void* stream) {
+  if (!L || !q || !out) return MIXATTN_ERR_NULL;
+  if (layer < 0 || layer >= L->n_layers) return MIXATTN_ERR_LAYER;
+  if (seq_len < 1) return MIXATTN_ERR_ORDER;
+  return prefill_impl(L, layer, q, k, v, out, nullptr, seq_len, stream);
+}
+
+int mixattn_prefill_varlen(mixattn_layout* L, int layer, const void* q, const void* k, const void* v, void* out,
+                           const int32_t* seq_lens, void* stream) {
+  if (!L || !q || !out || !seq_lens) return MIXATTN_ERR_NULL;
+  if (layer < 0 || layer >= L->n_layers) return MIXATTN_ERR_LAYER;
+  int max_len = 0;
+  for (int b = 0; b < L->batch; ++b) {
+    if (seq_lens[b] < 0) return MIXATTN_ERR_ORDER;
+    max_len = std::max(max_len, seq_lens[b]);
+  }
+  if (max_len < 1) return MIXATTN_ERR_ORDER;
+  return prefill_impl(L, layer, q, k, v, out, seq_lens, max_len, stream);
 }
 
 int mixattn_load_kv(mixattn_layout* L, int layer, const void* k, const void* v, const int32_t* seq_lens,

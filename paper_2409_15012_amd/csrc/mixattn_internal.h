@@ -86,11 +86,13 @@ struct mixattn_layout {
   void* stageV = nullptr;
   int64_t stage_blocks = 0;  // blocks per (b, h) currently allocated
   int stage_cache = -1;      // cache whose prompt the staging area holds (-1: none)
-  int stage_len = 0;         // its prompt length
+  std::vector<int32_t> stage_lens;  // its chunk length per sequence
   int64_t* d_stage_base = nullptr;   // [batch] geometry tables of the staging area
   int32_t* d_stage_slots = nullptr;  // [batch]
   int32_t* d_stage_lens = nullptr;  // [batch] device copy of seq_lens for load_kv / prefill commits
   int64_t* d_stage_src = nullptr;   // [batch] device: first packed token of each sequence
+  int64_t* d_q_first = nullptr;     // [batch] device: first packed row of each sequence in a varlen prefill call
+  int32_t* d_q_len = nullptr;       // [batch] device: chunk length of each sequence in a varlen prefill call
   void* d_readback = nullptr;       // 2 * kMaxHeadDim elements for mixattn_read_cache
   // tuning
   int64_t chunk_keys = 0;
@@ -137,8 +139,8 @@ struct StoreLaunch {
   const int64_t* d_src_first = nullptr;  // [batch] first packed token of each sequence; nullptr => b * uniform_len
   const int32_t* d_src_len = nullptr;    // [batch] new tokens of each sequence; nullptr => uniform_len
   int uniform_len = 0;
-  const int32_t* d_n_old = nullptr;      // [batch] device lengths; n_old = d_n_old[b] - old_sub; nullptr => 0
-  int old_sub = 0;
+  const int32_t* d_n_old = nullptr;      // [batch] device lengths; nullptr => n_old = 0
+  int old_sub = 0;                       // 1: d_n_old already include the new tokens (n_old = d_n_old[b] - add)
   // tokens before n_old (tiled path): read from this tile-format cache; nullptr => none are needed
   const void* Kold = nullptr; const void* Vold = nullptr;
   const int64_t* old_base = nullptr; const int32_t* old_slots = nullptr;
@@ -162,6 +164,9 @@ hipError_t launch_append_tiled(const AppendLaunch& a, hipStream_t s);
 hipError_t launch_append_rowmajor(const AppendLaunch& a, hipStream_t s);
 
 hipError_t launch_fill_i32(int32_t* p, int32_t value, int64_t n, hipStream_t s);
+// d_first[i] = first[i], d_len[i] = len[i] for i < n (host arrays; the values travel in the kernel arguments)
+hipError_t launch_set_seq_tables(int64_t* d_first, int32_t* d_len, const int64_t* first, const int32_t* len, int n,
+                                 hipStream_t s);
 hipError_t launch_gather_row(const void* K, const void* V, int64_t base, int32_t slots, int kv_head, int64_t slot,
                              int D, int elem, bool tiled, void* dst, hipStream_t s);
 
@@ -176,7 +181,10 @@ struct PrefillLaunch {
   const void* Kc = nullptr; const void* Vc = nullptr; const int64_t* c_base = nullptr; const int32_t* c_slots = nullptr;
   int ring = 0;          // row-major: ring size of that cache (0 = full)
   // chunked prefill: n_old = d_lens[b] - old_sub tokens were held before this chunk (nullptr: empty caches)
-  const int32_t* d_lens = nullptr; int old_sub = 0;
+  const int32_t* d_lens = nullptr; int old_sub = 0;  // old_sub: 1 = d_lens already include this chunk
+  // chunks of different lengths: rows d_q_first[b] .. + d_q_len[b] - 1 of the packed q / out (and k_src / v_src)
+  // tensors; nullptr: uniform, rows b*S .. b*S + S - 1.  S is the longest chunk.
+  const int64_t* d_q_first = nullptr; const int32_t* d_q_len = nullptr;
   int window = 0;  // attention window of the layer, 0 = full causal
   int batch = 0, S = 0, Hq = 0, Hkv = 0, G = 0, D = 0;
   int kv_dtype = 0, out_dtype = 0;

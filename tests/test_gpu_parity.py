@@ -521,6 +521,63 @@ def test_chunked_prefill_ragged_history(mx):
     lay.close()
 
 
+@pytest.mark.parametrize("kvd,d,Hq,Hkv,W", [("bf16", 128, 8, 2, 48), ("bf16", 128, 8, 2, 200), ("f32", 64, 4, 4, 40)])
+def test_varlen_prefill_against_oracle(mx, kvd, d, Hq, Hkv, W):
+    """Chunks of a different length per sequence (packed tensors), twice in a row so that the second call lands on
+    ragged histories; one sequence sits out each call.  MFMA path (bf16, d 128) and scalar path (fp32)."""
+    layers = [(0, 0, 0), (1, W, 1), (1, W, 1), (0, 0, 0)]
+    calls = [[333, 0, 70, 1], [64, 129, 0, 300]]
+    B = 4
+    cap = [sum(c[b] for c in calls) + 1 for b in range(B)]
+    tdt = torch.bfloat16 if kvd == "bf16" else torch.float32
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=cap, kv_dtype=kvd, out_dtype="f32")
+    ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
+    for ci, lens in enumerate(calls):
+        T = sum(lens)
+        kv = {}
+        for li in range(len(layers)):
+            wr = lay.writer_of(li)
+            if wr == li:
+                kv[li] = (wl.randn(500 + 10 * ci + li, (T, Hkv, d), tdt, DEV),
+                          wl.randn(600 + 10 * ci + li, (T, Hkv, d), tdt, DEV))
+            q = wl.randn(700 + 10 * ci + li, (T, Hq, d), tdt, DEV)
+            k, v = kv[wr]
+            reuse = kvd == "bf16" and wr == li - 1  # reader right after its writer: the staged copy
+            if kvd == "f32" and wr != li and layers[li][0] == 1 and ci > 0:
+                # scalar path: a ring reader past the first chunk has lost keys its first rows need
+                with pytest.raises(mx.MixAttnError) as ei:
+                    lay.prefill_varlen(li, q, k, v, lens)
+                assert ei.value.status == -6
+                ora.prefill_ragged(li, to_f64(q), None, None, lens)
+                continue
+            out = lay.prefill_varlen(li, q, None if reuse else k, None if reuse else v, lens)
+            ref = ora.prefill_ragged(li, to_f64(q), to_f64(k) if wr == li else None, to_f64(v) if wr == li else None,
+                                     lens)
+            assert_matches(out, ref, kvd, "call %d layer %d" % (ci, li))
+        for b in range(B):
+            assert lay.seq_len(0, b) == sum(c[b] for c in calls[:ci + 1])
+    for li in (0, 1):
+        _check_cache(lay, ora, li, heads=[Hkv - 1])
+    # and the decode step that follows sees the ragged histories
+    for li in range(len(layers)):
+        if lay.writer_of(li) == li:
+            k = wl.randn(800 + li, (B, Hkv, d), tdt, DEV)
+            v = wl.randn(810 + li, (B, Hkv, d), tdt, DEV)
+            lay.append_kv(li, k, v)
+            ora.append(li, to_f64(k), to_f64(v))
+        q = wl.randn(820 + li, (B, Hq, d), tdt, DEV)
+        assert_matches(lay.decode(li, q), ora.decode(li, to_f64(q)), kvd, "decode layer %d" % li)
+    # error paths: negative length, all zero, wrong staged lengths
+    q1 = wl.randn(1, (3, Hq, d), tdt, DEV)
+    k1 = wl.randn(2, (3, Hkv, d), tdt, DEV)
+    for bad, status in (([3, -1, 1, 0], -6), ([0, 0, 0, 0], -6)):
+        with pytest.raises((mx.MixAttnError, ValueError)) as ei:
+            lay.prefill_varlen(0, q1, k1, k1, bad)
+        if isinstance(ei.value, mx.MixAttnError):
+            assert ei.value.status == status
+    lay.close()
+
+
 @pytest.mark.parametrize("qscale,vscale", [(6.0, 1.0), (0.01, 1.0), (1.0, 300.0), (3.0, 1e-3)])
 def test_peaked_flat_and_scaled_inputs(mx, qscale, vscale):
     """Score ranges far from N(0,1): sharply peaked rows (large q), nearly uniform rows (tiny q), large and tiny

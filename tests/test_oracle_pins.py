@@ -365,3 +365,43 @@ def test_chunked_prefill_equals_one_shot_and_equals_appends():
     qd = rng.standard_normal((B, Hq, d))
     for li in range(3):
         np.testing.assert_array_equal(parts.decode(li, qd), whole.decode(li, qd))
+
+
+def test_ragged_prefill_equals_token_by_token_decode_and_brute_force():
+    # chunks of different lengths per sequence: every row must equal the decode step after that many appends on a
+    # batch-of-one stack (decode is pinned by the closed forms above), and a sliding row must equal the plain
+    # definition written out over the last W positions
+    Hq, Hkv, d, W = 4, 2, 8, 5
+    layers = [(FULL, 0, 0), (SLIDING, W, 1), (SLIDING, W, 1)]
+    rng = np.random.default_rng(21)
+    first_lens, second_lens = [7, 0, 3], [2, 9, 0]
+    B = len(first_lens)
+    ragged = _stack(layers, B, Hq, Hkv, d)
+    singles = [_stack(layers, 1, Hq, Hkv, d) for _ in range(B)]
+    hist = [[np.zeros((0, Hkv, d)), np.zeros((0, Hkv, d))] for _ in range(B)]  # K, V of the sliding cache
+    for lens in (first_lens, second_lens):
+        T = sum(lens)
+        q = rng.standard_normal((T, Hq, d))
+        kv = {li: (rng.standard_normal((T, Hkv, d)), rng.standard_normal((T, Hkv, d))) for li in (0, 1)}
+        out = {0: ragged.prefill_ragged(0, q, kv[0][0], kv[0][1], lens),
+               1: ragged.prefill_ragged(1, q, kv[1][0], kv[1][1], lens),
+               2: ragged.prefill_ragged(2, q, None, None, lens)}
+        row = 0
+        for b in range(B):
+            for i in range(lens[b]):
+                for li in (0, 1):
+                    singles[b].append(li, kv[li][0][row][None], kv[li][1][row][None])
+                for li in (0, 1, 2):
+                    np.testing.assert_allclose(out[li][row], singles[b].decode(li, q[row][None])[0], rtol=0, atol=1e-12)
+                hist[b][0] = np.concatenate([hist[b][0], kv[1][0][row][None]])
+                hist[b][1] = np.concatenate([hist[b][1], kv[1][1][row][None]])
+                K, V = hist[b][0][-W:], hist[b][1][-W:]
+                for j in range(Hq):
+                    s = K[:, j // (Hq // Hkv)] @ q[row, j] / math.sqrt(d)
+                    w = np.exp(s - s.max())
+                    np.testing.assert_allclose(out[2][row, j], (w[:, None] * V[:, j // (Hq // Hkv)]).sum(0) / w.sum(),
+                                               rtol=0, atol=1e-12)
+                row += 1
+    assert [ragged.seq_len(0, b) for b in range(B)] == [9, 9, 3]
+    with pytest.raises(ValueError):
+        ragged.prefill_ragged(0, np.zeros((3, Hq, d)), np.zeros((3, Hkv, d)), np.zeros((3, Hkv, d)), [1, 1])
