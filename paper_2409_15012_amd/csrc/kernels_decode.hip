@@ -133,7 +133,8 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
     const u32x4_t* vp = Vb + (int64_t)blk * (kBlockElems / 8);
     // A full cache is streamed once per launch and is far larger than any cache level: nontemporal loads (+12 %
     // on a pure read stream).  A ring is read again by the next layers of its sharing group and is a few hundred
-    // MiB at most: plain loads are 4-7 % faster on a working set of that size.
+    // MiB at most: plain loads are 4-7 % faster on a working set of that size.  (Nontemporal loads only in the
+    // writer's launch, which finds the ring cold, were measured too: the writer gains 2 us, each reader loses 2.)
 #pragma unroll
     for (int i = 0; i < 8; ++i) kd[i] = RING ? kp[i * 64] : __builtin_nontemporal_load(kp + i * 64);
 #pragma unroll
