@@ -188,7 +188,8 @@ int64_t mixattn_step_read_bytes(const mixattn_layout* L, int layer);
 typedef enum {
   MIXATTN_PARAM_CHUNK_KEYS = 0, /* split-K chunk length in keys for decode (multiple of 32; 0 = automatic) */
   MIXATTN_PARAM_FUSED_COMBINE = 1, /* 1: the last workgroup of a (sequence, kv head) merges the split-K partials
-                                      itself; 0: separate combine launch */
+                                      itself (partials exchanged with device-coherent accesses, no fence);
+                                      0 (default): separate combine launch, which measures faster */
   MIXATTN_PARAM_PREFILL_SIMPLE = 2, /* 1: force the scalar prefill kernel (testing) */
   MIXATTN_PARAM_PREFILL_WAVES = 3,  /* wavefronts per MFMA prefill workgroup: 4, 8, or 0 = by layer kind (8 full, 4 sliding) */
   MIXATTN_PARAM_PREFILL_HEADS = 4   /* query heads of one KV head served by one MFMA prefill workgroup: 1, 2, 4, or

@@ -55,6 +55,14 @@ struct TiledDecodeParams {
   const uint16_t* k_new; const uint16_t* v_new; uint16_t* Kw; uint16_t* Vw; int32_t* d_lens_out;
 };
 
+// device-scope coherent accesses (relaxed atomics): they go past the XCD-private L2
+__device__ inline void coherent_store(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline float coherent_load(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // merges the split-K partials of one (sequence, query head): thread d handles one output dim
 template <typename OutT>
 __device__ inline void merge_partials(const float* p_acc, const float* p_ml, int n_chunks_b, int d, OutT* out) {
@@ -311,6 +319,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
   __syncthreads();
 
   const bool direct = (a.n_chunks == 1);
+  const bool fused = !direct && a.fused_combine;
   for (int idx = tid; idx < G * kTiledDim; idx += NW * 64) {
     const int hd = idx >> 7, d = idx & 127;
     float M = s_m[0][hd];
@@ -328,31 +337,52 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
       store_out<OutT>((OutT*)a.out + row * kTiledDim + d, acc / L);
     } else {
       const int64_t pr = row * kMaxChunks + c;
-      a.p_acc[pr * kTiledDim + d] = acc;
-      if (d == 0) {
-        a.p_ml[2 * pr] = M;
-        a.p_ml[2 * pr + 1] = L;
+      if (fused) {  // read by another workgroup of this launch, maybe on another XCD: device-coherent stores
+        coherent_store(a.p_acc + pr * kTiledDim + d, acc);
+        if (d == 0) {
+          coherent_store(a.p_ml + 2 * pr, M);
+          coherent_store(a.p_ml + 2 * pr + 1, L);
+        }
+      } else {
+        a.p_acc[pr * kTiledDim + d] = acc;
+        if (d == 0) {
+          a.p_ml[2 * pr] = M;
+          a.p_ml[2 * pr + 1] = L;
+        }
       }
     }
   }
-  if (direct || !a.fused_combine) return;
+  if (!fused) return;
 
-  // ---- fused combine: the workgroup that arrives last for this (sequence, kv head) merges all chunks
-  __threadfence();
+  // ---- fused combine: the workgroup that arrives last for this (sequence, kv head) merges all chunks.
+  // No fence: a device-scope fence writes back and invalidates the whole L2 of the XCD, which throws away the K/V
+  // stream of every other workgroup on it (5x slower).  Instead the partials are written and read with
+  // device-coherent accesses (they bypass the XCD-private L2), each thread waits until its own stores have been
+  // acknowledged, and the arrival counter is a device-scope atomic.
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
   __syncthreads();
   if (tid == 0) {
-    const uint32_t prev = atomicAdd(&a.counters[b * a.Hkv + h], 1u);
+    uint32_t* cnt = a.counters + b * a.Hkv + h;
+    const uint32_t prev = __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s_last = (prev == (uint32_t)(n_chunks_b - 1));
-    if (s_last) a.counters[b * a.Hkv + h] = 0u;  // ready for the next launch on this stream
+    if (s_last) __hip_atomic_store(cnt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next launch
   }
   __syncthreads();
   if (!s_last) return;
-  __threadfence();
   for (int idx = tid; idx < G * kTiledDim; idx += NW * 64) {
     const int hd = idx >> 7, d = idx & 127;
     const int64_t row = (int64_t)b * a.Hq + (int64_t)h * G + hd;
-    merge_partials<OutT>(a.p_acc + row * kMaxChunks * kTiledDim, a.p_ml + row * kMaxChunks * 2, n_chunks_b, d,
-                         (OutT*)a.out + row * kTiledDim);
+    const float* p_acc = a.p_acc + row * kMaxChunks * kTiledDim;
+    const float* p_ml = a.p_ml + row * kMaxChunks * 2;
+    float M = -INFINITY;
+    for (int cc = 0; cc < n_chunks_b; ++cc) M = fmaxf(M, coherent_load(p_ml + 2 * cc));
+    float L = 0.f, acc = 0.f;
+    for (int cc = 0; cc < n_chunks_b; ++cc) {
+      const float w = fast_exp2(coherent_load(p_ml + 2 * cc) - M);
+      L += coherent_load(p_ml + 2 * cc + 1) * w;
+      acc += coherent_load(p_acc + (int64_t)cc * kTiledDim + d) * w;
+    }
+    store_out<OutT>((OutT*)a.out + row * kTiledDim + d, acc / L);
   }
 }
 
