@@ -4,7 +4,9 @@
 Default workload ("decode32k"): the 24-layer MixAttention stack (layers 0 and 12 full, 22 sliding-window layers
 W = 1024 in six sharing groups), bf16, batch 32, 32768 tokens of context per sequence.  One step = the whole hot
 path for one generated token per sequence: 8 KV appends (writer layers, fused into their decode launch unless
---two-call-append) + 24 decode attentions, with every input already resident in HBM.  Prints ONE JSON line (see README for the fields).
+--two-call-append) + 24 decode attentions, with every input already resident in HBM.  Prints ONE JSON line:
+metric / value / unit / ms_per_step / config, `roofline` (the full-attention decode launch against the 8 TB/s HBM
+peak, timed with events inside the timed region) and `cpu_baseline` (the CPU oracle on a bounded sample).
 
 Other workloads (--workload): decode4k (batch 8, context 4096), prefill32k (batch 1, 32768-token prompt through
 the 24 layers), ragged64 (batch 64, context lengths uniform in [1024, 65536], MixAttention stack next to the
