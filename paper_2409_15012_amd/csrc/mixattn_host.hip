@@ -302,7 +302,9 @@ static inline int layer_attn_window(const mixattn_layout* L, int layer) {
 static int plan_chunk_blocks(const mixattn_layout* L, Cache& c, int max_blocks, int extra, int attn_window) {
   const double slots = 2.0 * L->n_cus;
   const double us_per_block_bw = 2.0 * kBlockElems * 2 / 7.0e6;  // 16 KiB at 7.0 TB/s
-  const double us_per_block_wg = 0.6, us_wg_fixed = 1.0, us_combine = 5.0;
+  // A wavefront keeps two blocks in flight: a workgroup that is not held back by the memory system takes about
+  // 0.25 us per block.  (Workgroups of 8 wavefronts were measured as well: no gain, one CU cannot pull much more.)
+  const double us_per_block_wg = 0.25, us_wg_fixed = 1.0, us_combine = 5.0;
   auto blocks_of = [&](int b) {
     const int64_t n = tokens_read(c, c.len[b] + extra, attn_window);
     return (int)((n + kBlockKeys - 1) / kBlockKeys) + (attn_window > 0 ? 1 : 0);  // a window may straddle a block more
