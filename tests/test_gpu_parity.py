@@ -82,6 +82,9 @@ def _mixed_layers(W):
     (4, 4, 100, [129, 4000], 128, 1),                  # G = 1
     (8, 1, 1024, [1500, 1023, 2048], 0, 1),            # G = 8
     (6, 2, 33, [77, 3], 0, 1),                         # G = 3
+    (8, 2, 1, [1, 2, 40], 0, 0),                       # window of one key: every sliding layer returns v of its token
+    (8, 2, 2, [1, 2, 3, 65], 0, 0),
+    (8, 2, 31, [30, 31, 32, 1000], 0, 0),              # window just under one block
 ])
 def test_bf16_decode_against_oracle(mx, Hq, Hkv, W, lens, chunk, fused):
     B, d = len(lens), 128
@@ -168,7 +171,7 @@ def test_bf16_prefill_workgroup_shapes(mx, waves, heads):
 # --------------------------------------------------------------------------- bf16 prefill, small shapes
 @pytest.mark.parametrize("S,W,Hq,Hkv,B", [
     (1, 64, 8, 2, 1), (31, 48, 8, 2, 2), (100, 48, 8, 2, 2), (129, 64, 4, 4, 1), (300, 200, 8, 2, 2),
-    (700, 100, 8, 1, 1), (257, 1024, 6, 2, 1),
+    (700, 100, 8, 1, 1), (257, 1024, 6, 2, 1), (70, 1, 8, 2, 2), (130, 2, 8, 2, 1), (96, 31, 8, 2, 1),
 ])
 @pytest.mark.parametrize("simple", [0, 1])
 def test_bf16_prefill_then_decode_against_oracle(mx, S, W, Hq, Hkv, B, simple):
@@ -338,6 +341,8 @@ def test_error_paths_leave_state_untouched(mx):
     (8, 2, 48, [5, 47, 48, 49, 95, 96, 700], 32),                 # window not a multiple of the block
     (32, 8, 1024, [1023, 1024, 1025, 4095, 4096, 2000], 0),
     (8, 1, 100, [3000, 99], 256),
+    (8, 2, 1, [1, 5, 64], 0),                                      # window of one key
+    (8, 2, 2, [1, 2, 31, 32, 33], 0),
 ])
 def test_fused_append_decode_against_oracle(mx, Hq, Hkv, W, lens, chunk):
     """mixattn_append_decode == append + decode: outputs against the oracle, cache rows and lengths bit-exact,
