@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--gen-batch", type=int, default=32)
     ap.add_argument("--gen-prompt", type=int, default=31000)
     ap.add_argument("--gen-new", type=int, default=1000)
+    ap.add_argument("--page-tokens", type=int, default=0,
+                    help="hold full-attention caches as pools of pages of this many tokens (0: contiguous)")
     ap.add_argument("--two-call-append", action="store_true",
                     help="writer layers call append_kv and decode separately instead of append_decode")
     ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
@@ -69,10 +71,19 @@ def _traffic_from_profiles(kernel_tag):
     return None
 
 
-def build_decode_stack(mx, wl, torch, layers, batch, Hq, Hkv, d, seq_lens, extra, out_dtype, dev, seed):
+def _paging(page_tokens, capacity):
+    """Layout keyword arguments for a pool that holds exactly every sequence at its capacity."""
+    if not page_tokens:
+        return {}
+    return {"page_tokens": page_tokens,
+            "pool_tokens": sum((c + page_tokens - 1) // page_tokens for c in capacity) * page_tokens}
+
+
+def build_decode_stack(mx, wl, torch, layers, batch, Hq, Hkv, d, seq_lens, extra, out_dtype, dev, seed, page_tokens=0):
     """Creates a layout, fills every writer cache with seq_lens[b] seeded tokens, returns (layout, per-layer inputs)."""
-    lay = mx.Layout(layers, batch, Hq, Hkv, d, capacity=[n + extra for n in seq_lens], kv_dtype="bf16",
-                    out_dtype=out_dtype)
+    capacity = [n + extra for n in seq_lens]
+    lay = mx.Layout(layers, batch, Hq, Hkv, d, capacity=capacity, kv_dtype="bf16", out_dtype=out_dtype,
+                    **_paging(page_tokens, capacity))
     total = int(sum(seq_lens))
     qs, ks, vs = [], [], []
     for li in range(len(layers)):
@@ -110,7 +121,7 @@ def run_decode(args, mx, wl, torch, w, layers=None, label=None):
     # the first timed step decodes at exactly the workload's context length
     seq_lens = [max(1, n - 1 - args.warmup) for n in w.seq_lens]
     lay, qs, ks, vs = build_decode_stack(mx, wl, torch, layers, B, Hq, Hkv, d, seq_lens, total_steps + 1,
-                                         args.out_dtype, dev, w.seed)
+                                         args.out_dtype, dev, w.seed, args.page_tokens)
     if args.chunk_keys:
         lay.set_param(mx.PARAM_CHUNK_KEYS, args.chunk_keys)
     if args.fused_combine >= 0:
@@ -238,7 +249,8 @@ def cpu_baseline_decode(wl, torch, w, budget_s=15.0):
 def run_prefill(args, mx, wl, torch, w):
     dev = "cuda:0"
     B, S, Hq, Hkv, d = w.batch, w.prefill_len, w.n_q_heads, w.n_kv_heads, w.head_dim
-    lay = mx.Layout(w.layers, B, Hq, Hkv, d, capacity=[S] * B, kv_dtype="bf16", out_dtype=args.out_dtype)
+    lay = mx.Layout(w.layers, B, Hq, Hkv, d, capacity=[S] * B, kv_dtype="bf16", out_dtype=args.out_dtype,
+                    **_paging(args.page_tokens, [S] * B))
     if args.prefill_waves:
         lay.set_param(mx.PARAM_PREFILL_WAVES, args.prefill_waves)
     if args.prefill_heads:
@@ -308,7 +320,8 @@ def run_generation(args, mx, wl, torch, layers, label):
     dev = "cuda:0"
     B, S, T = args.gen_batch, args.gen_prompt, args.gen_new
     Hq, Hkv, d = 32, 8, 128
-    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[S + T] * B, kv_dtype="bf16", out_dtype=args.out_dtype)
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[S + T] * B, kv_dtype="bf16", out_dtype=args.out_dtype,
+                    **_paging(args.page_tokens, [S + T] * B))
     writer_of = [lay.writer_of(li) for li in range(len(layers))]
     q = wl.randn(1, (B, S, Hq, d), torch.bfloat16, dev)
     k = wl.randn(2, (B, S, Hkv, d), torch.bfloat16, dev)
@@ -386,7 +399,7 @@ def main():
             "config": {"workload": w.name, "batch": w.batch, "context": w.context, "window": 1024,
                        "layers": "24: 0,12 full; 22 sliding in groups {1-4,5-8,9-11},{13-16,17-20,21-23}",
                        "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
-                       "out_dtype": args.out_dtype, "only": args.only or "all"},
+                       "out_dtype": args.out_dtype, "only": args.only or "all", "page_tokens": args.page_tokens},
             "kv_bytes_read_per_step": r["kv_bytes_per_step"],
             "kv_bytes_resident": r["kv_bytes_resident"],
             "decode_attn_logical_GBps": r["logical_gbs"],
@@ -410,7 +423,7 @@ def main():
             "metric": "prefill attention TFLOP/s (unmasked pairs only), 24-layer MixAttention stack",
             "value": r["tflops"], "unit": "TFLOP/s", "ms_per_step": r["ms_per_step"],
             "config": {"workload": w.name, "batch": 1, "seq_len": w.prefill_len, "window": 1024,
-                       "out_dtype": args.out_dtype, "chunks": max(1, args.chunks)},
+                       "out_dtype": args.out_dtype, "chunks": max(1, args.chunks), "page_tokens": args.page_tokens},
             "useful_flops_per_step": r["flops"],
             "roofline": None if args.chunks > 1 else {"kernel": "prefill_tiled_kernel (full causal layer, incl. cache commit)", "bound": "mfma",
                          "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -447,7 +460,7 @@ def main():
             "ms_per_step": r_mix["ms_per_decode_step"],
             "config": {"workload": "gen_b%d_in%d_out%d" % (args.gen_batch, args.gen_prompt, args.gen_new),
                        "batch": args.gen_batch, "prompt": args.gen_prompt, "new_tokens": args.gen_new,
-                       "window": 1024, "out_dtype": args.out_dtype},
+                       "window": 1024, "out_dtype": args.out_dtype, "page_tokens": args.page_tokens},
             "mix": r_mix,
         })
         if args.with_standard:

@@ -104,11 +104,24 @@ int mixattn_validate_config(const mixattn_config* cfg);
 /* Builds the layout: resolves cache ids to caches and writers, allocates zero-filled caches, length arrays and
    split-K scratch with hipMalloc on the current device.  *out receives the handle (untouched on error). */
 int mixattn_create_layout(const mixattn_config* cfg, mixattn_layout** out);
+/* The same layout with its FULL caches held in pages, as serving engines do (Section 4 measures through one): each
+   FULL cache is a pool of pool_tokens / page_tokens pages of page_tokens tokens (all KV heads), shared by the
+   sequences; a sequence takes a page from the pool whenever it grows into one (append, prefill, load) and gives all
+   of them back on mixattn_reset / mixattn_release_sequence, so memory follows the tokens held, not the capacities.
+   capacity[b] stays the most tokens sequence b may hold (it sizes the page table).  Ring caches are unaffected.
+   page_tokens: a power of two, >= 32.  MFMA path only (bf16, head_dim 128, group size <= 8), LAYOUT otherwise.
+   A call that needs more pages than the pool has left returns CAPACITY and changes nothing.  Results, cache
+   contents (mixattn_read_cache) and every other call are the same as for a contiguous layout. */
+int mixattn_create_layout_paged(const mixattn_config* cfg, int page_tokens, int64_t pool_tokens,
+                                mixattn_layout** out);
 int mixattn_destroy_layout(mixattn_layout* L);
 
 /* Empties every cache (lengths to zero; cache bytes are left as they are and never read again before being
    overwritten).  Enqueued on `stream`. */
 int mixattn_reset(mixattn_layout* L, void* stream);
+/* Empties sequence b in every cache (its slot of the batch can take a new request; a paged layout returns its pages
+   to the pools).  Enqueued on `stream`.  Errors: LAYER (b out of range). */
+int mixattn_release_sequence(mixattn_layout* L, int b, void* stream);
 
 /* Appends one token per sequence to the cache `layer` writes (Section 3: a sliding cache keeps the past
    `window` tokens).  k, v: device [batch, n_kv_heads, head_dim].  Token at absolute position p = n_b goes to

@@ -203,6 +203,14 @@ class OracleStack:
             self._V[key][b] = np.concatenate([self._V[key][b], v_packed[off:off + n]], axis=0)
             off += n
 
+    def release_sequence(self, b: int):
+        """Sequence b starts over in every cache (its slot of the batch takes a new request)."""
+        if not 0 <= b < self.B:
+            raise ValueError("no such sequence")
+        for key in self._K:
+            self._K[key][b] = np.zeros((0, self.Hkv, self.d))
+            self._V[key][b] = np.zeros((0, self.Hkv, self.d))
+
     def decode(self, layer: int, q: np.ndarray, rows: Optional[Sequence[Tuple[int, int]]] = None) -> np.ndarray:
         """q [B, Hq, d] -> out [B, Hq, d]; the query of sequence b sits at position n_b - 1
         (the group's writer has already appended this step's token).

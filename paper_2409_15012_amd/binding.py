@@ -21,7 +21,8 @@ F32, BF16 = 0, 1
 PARAM_CHUNK_KEYS, PARAM_FUSED_COMBINE, PARAM_PREFILL_SIMPLE, PARAM_PREFILL_WAVES, PARAM_PREFILL_HEADS = 0, 1, 2, 3, 4
 
 EXPORTS = [
-    "mixattn_validate_config", "mixattn_create_layout", "mixattn_destroy_layout", "mixattn_reset",
+    "mixattn_validate_config", "mixattn_create_layout", "mixattn_create_layout_paged", "mixattn_destroy_layout",
+    "mixattn_reset", "mixattn_release_sequence",
     "mixattn_append_kv", "mixattn_decode", "mixattn_append_decode", "mixattn_prefill", "mixattn_prefill_varlen",
     "mixattn_load_kv", "mixattn_n_caches",
     "mixattn_cache_of", "mixattn_seq_len", "mixattn_slot_of", "mixattn_slot_for", "mixattn_read_cache",
@@ -61,6 +62,8 @@ def load():
     vp, i32, i64 = C.c_void_p, C.c_int, C.c_int64
     lib.mixattn_validate_config.argtypes = [C.POINTER(Config)]
     lib.mixattn_create_layout.argtypes = [C.POINTER(Config), C.POINTER(vp)]
+    lib.mixattn_create_layout_paged.argtypes = [C.POINTER(Config), i32, i64, C.POINTER(vp)]
+    lib.mixattn_release_sequence.argtypes = [vp, i32, vp]
     lib.mixattn_destroy_layout.argtypes = [vp]
     lib.mixattn_reset.argtypes = [vp, vp]
     lib.mixattn_append_kv.argtypes = [vp, i32, vp, vp, vp]
@@ -139,7 +142,7 @@ class Layout:
     """Owns one mixattn_layout handle.  Methods mirror the C entry points one to one."""
 
     def __init__(self, layers, batch, n_q_heads, n_kv_heads, head_dim, capacity=None, kv_dtype="bf16",
-                 out_dtype="f32", softmax_scale: float = 0.0):
+                 out_dtype="f32", softmax_scale: float = 0.0, page_tokens: int = 0, pool_tokens: int = 0):
         self.lib = load()
         self.layers = [tuple(int(x) for x in t) for t in layers]
         self.batch, self.Hq, self.Hkv, self.d = batch, n_q_heads, n_kv_heads, head_dim
@@ -149,7 +152,10 @@ class Layout:
         cfg, self._keep = make_config(self.layers, batch, n_q_heads, n_kv_heads, head_dim, capacity, kv_dtype,
                                       out_dtype, softmax_scale)
         h = C.c_void_p()
-        st = self.lib.mixattn_create_layout(C.byref(cfg), C.byref(h))
+        if page_tokens:
+            st = self.lib.mixattn_create_layout_paged(C.byref(cfg), int(page_tokens), int(pool_tokens), C.byref(h))
+        else:
+            st = self.lib.mixattn_create_layout(C.byref(cfg), C.byref(h))
         if st != 0:
             raise MixAttnError(st, "mixattn_create_layout")
         self.h = h
@@ -175,6 +181,9 @@ class Layout:
             raise ValueError("expected %s %s, got %s %s" % (want, tuple(shape), t.dtype, tuple(t.shape)))
 
     # -- hot path
+    def release_sequence(self, b: int):
+        self._check(self.lib.mixattn_release_sequence(self.h, int(b), _stream()), "mixattn_release_sequence")
+
     def reset(self):
         self._check(self.lib.mixattn_reset(self.h, _stream()), "mixattn_reset")
 

@@ -49,6 +49,30 @@ hipError_t launch_set_seq_tables(int64_t* d_first, int32_t* d_len, const int64_t
   return hipSuccess;
 }
 
+struct ScatterChunk {
+  int64_t index[64];
+  int32_t value[64];
+};
+__global__ __launch_bounds__(64) void scatter_i32_kernel(int32_t* table, ScatterChunk c, int n) {
+  const int i = threadIdx.x;
+  if (i < n) table[c.index[i]] = c.value[i];
+}
+
+hipError_t launch_scatter_i32(int32_t* table, const int64_t* index, const int32_t* value, int n, hipStream_t s) {
+  for (int base = 0; base < n; base += 64) {
+    ScatterChunk c;
+    const int m = n - base < 64 ? n - base : 64;
+    for (int i = 0; i < 64; ++i) {
+      c.index[i] = i < m ? index[base + i] : 0;
+      c.value[i] = i < m ? value[base + i] : 0;
+    }
+    hipLaunchKernelGGL(scatter_i32_kernel, dim3(1), dim3(64), 0, s, table, c, m);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
 // ------------------------------------------------------------------------------------------------
 // Append one token per sequence.  One workgroup per sequence so that the length is read once, used by
 // every thread, and bumped by one thread after all stores of this workgroup were issued.
@@ -59,7 +83,6 @@ __global__ __launch_bounds__(256) void append_tiled_kernel(AppendLaunch a) {
   const int slot = a.window > 0 ? n % a.window : n;
   if (slot >= a.d_slots[b]) return;  // host checks capacity first; never taken for a consistent layout
   const int blk = slot >> 5, key = slot & 31;
-  const int64_t nblk = a.d_slots[b] >> 5;
   const uint16_t* ks = (const uint16_t*)a.k + (int64_t)b * a.Hkv * kTiledDim;
   const uint16_t* vs = (const uint16_t*)a.v + (int64_t)b * a.Hkv * kTiledDim;
   uint16_t* Kd = (uint16_t*)a.K;
@@ -67,14 +90,14 @@ __global__ __launch_bounds__(256) void append_tiled_kernel(AppendLaunch a) {
   // K: 16-byte pieces (8 dims of one key stay together)
   for (int i = threadIdx.x; i < a.Hkv * 16; i += blockDim.x) {
     const int h = i >> 4, c = i & 15;
-    const int64_t blk_elem = (a.d_base[b] + (int64_t)h * nblk + blk) * kBlockElems;
+    const int64_t blk_elem = tiled_block_index(a.d_base, a.d_slots, a.pages, a.Hkv, b, h, blk) * kBlockElems;
     const uint4 val = *(const uint4*)(ks + h * kTiledDim + c * 8);
     *(uint4*)(Kd + blk_elem + k_tile_offset(key, c * 8)) = val;
   }
   // V: single elements (the 8 neighbours of an element in memory are other keys)
   for (int i = threadIdx.x; i < a.Hkv * kTiledDim; i += blockDim.x) {
     const int h = i >> 7, d = i & 127;
-    const int64_t blk_elem = (a.d_base[b] + (int64_t)h * nblk + blk) * kBlockElems;
+    const int64_t blk_elem = tiled_block_index(a.d_base, a.d_slots, a.pages, a.Hkv, b, h, blk) * kBlockElems;
     Vd[blk_elem + v_tile_offset(key, d)] = vs[h * kTiledDim + d];
   }
   __syncthreads();
@@ -183,22 +206,23 @@ __global__ __launch_bounds__(256) void store_tiled_kernel(StoreLaunch a) {
   if (a.old_is_dest && a.window == 0 && blk * kBlockKeys + kBlockKeys <= n_old - off) return;
   (void)add;
 
-  const int64_t nblk = slots >> 5;
-  const int64_t blk_elem = (a.d_base[b] + (int64_t)h * nblk + blk) * kBlockElems;
+  const int64_t blk_elem = tiled_block_index(a.d_base, a.d_slots, a.pages, a.Hkv, b, h, blk) * kBlockElems;
   uint16_t* Kd = a.K ? (uint16_t*)a.K + blk_elem : nullptr;
   uint16_t* Vd = a.V ? (uint16_t*)a.V + blk_elem : nullptr;
   const uint16_t* ksrc = (const uint16_t*)a.k_src;
   const uint16_t* vsrc = (const uint16_t*)a.v_src;
   const uint16_t* kold = (const uint16_t*)a.Kold;
   const uint16_t* vold = (const uint16_t*)a.Vold;
-  const int64_t old_nblk = (a.Kold || a.Vold) ? (a.old_slots[b] >> 5) : 0;
-  const int64_t old_first = (a.Kold || a.Vold) ? a.old_base[b] + (int64_t)h * old_nblk : 0;
+  const bool has_old = a.Kold || a.Vold;
+  auto old_block = [&](int ob) -> int64_t {  // block ob of this (sequence, head) in the old cache
+    return tiled_block_index(a.old_base, a.old_slots, a.old_pages, a.Hkv, b, h, ob);
+  };
 
   // Fast path (fp16 copy of a full cache's V, block made of old tokens only): same tile order on both sides,
   // so the block is converted piece by piece.
   if (!a.K && a.window == 0 && off == 0 && a.old_window == 0 && vold && !a.old_is_dest &&
       blk * kBlockKeys + kBlockKeys <= n_old) {
-    const uint16_t* src = vold + (old_first + blk) * kBlockElems;
+    const uint16_t* src = vold + old_block(blk) * kBlockElems;
     for (int o = threadIdx.x; o < kBlockElems / 8; o += blockDim.x) {
       uint4 v = *(const uint4*)(src + o * 8);
       if (a.v_as_f16) {
@@ -220,7 +244,7 @@ __global__ __launch_bounds__(256) void store_tiled_kernel(StoreLaunch a) {
       if (Kd) kq = *(const uint4*)(ksrc + e);
       if (Vd) vq = *(const uint4*)(vsrc + e);
     } else if (src.kind == 2) {
-      const int64_t be = (old_first + (src.index >> 5)) * kBlockElems;
+      const int64_t be = has_old ? old_block((int)(src.index >> 5)) * kBlockElems : 0;
       const int within = (int)(src.index & 31);
       if (Kd && kold) kq = *(const uint4*)(kold + be + k_tile_offset(within, c * 8));
       if (Vd && vold) {

@@ -43,6 +43,7 @@ constexpr int kDecodeWaves = 4;
 struct TiledDecodeParams {
   const uint16_t* K; const uint16_t* V;
   const int64_t* d_base; const int32_t* d_slots; const int32_t* d_lens;
+  PageTable pages;
   int window;       // ring size of a sliding cache (RING)
   int attn_window;  // WINDOWED: a sliding layer reading a full cache attends its last attn_window positions
   const uint16_t* q; void* out;
@@ -125,10 +126,25 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
     }
   }
 
+  // Block blk of this (sequence, kv head) sits at block index block_at(blk) of the cache: consecutive blocks when
+  // the cache is contiguous; in a paged full cache the page id is looked up when the wavefront enters a new page
+  // (its blocks are 4 apart, so a page of 2^shift blocks serves 2^shift / 4 consecutive iterations).
   const int64_t nblk = a.d_slots[b] >> 5;
   const int64_t first_blk = a.d_base[b] + (int64_t)h * nblk;
-  const u32x4_t* Kb = (const u32x4_t*)(a.K + first_blk * kBlockElems) + lane;
-  const u32x4_t* Vb = (const u32x4_t*)(a.V + first_blk * kBlockElems) + lane;
+  const bool paged = !RING && a.pages.ids != nullptr;
+  int cur_page = -1;
+  int64_t cur_page_first = 0;
+  auto block_at = [&](int blk) -> int64_t {
+    if (!paged) return first_blk + blk;
+    const int pi = blk >> a.pages.shift;
+    if (pi != cur_page) {
+      cur_page = pi;
+      cur_page_first = ((int64_t)a.pages.ids[(int64_t)b * a.pages.max_pages + pi] * a.Hkv + h) << a.pages.shift;
+    }
+    return cur_page_first + (blk & ((1 << a.pages.shift) - 1));
+  };
+  const u32x4_t* Kb = (const u32x4_t*)a.K + lane;
+  const u32x4_t* Vb = (const u32x4_t*)a.V + lane;
 
   floatx4_t o[8];
 #pragma unroll
@@ -137,8 +153,9 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
 
   u32x4_t kr[2][8], vr[2][8];
   auto load_block = [&](int blk, u32x4_t* kd, u32x4_t* vd) {
-    const u32x4_t* kp = Kb + (int64_t)blk * (kBlockElems / 8);
-    const u32x4_t* vp = Vb + (int64_t)blk * (kBlockElems / 8);
+    const int64_t at = block_at(blk) * (kBlockElems / 8);
+    const u32x4_t* kp = Kb + at;
+    const u32x4_t* vp = Vb + at;
     // A full cache is streamed once per launch and is far larger than any cache level: nontemporal loads (+12 %
     // on a pure read stream).  A ring is read again by the next layers of its sharing group and is a few hundred
     // MiB at most: plain loads are 4-7 % faster on a working set of that size.  (Nontemporal loads only in the
@@ -285,8 +302,9 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
       }
       compute_last(new_blk, kr[0], vr[0]);
       // the token goes to the cache for the launches that follow (no other wavefront of this launch reads the block)
-      uint16_t* Kd = a.Kw + (first_blk + new_blk) * kBlockElems;
-      uint16_t* Vd = a.Vw + (first_blk + new_blk) * kBlockElems;
+      const int64_t new_at = block_at(new_blk) * kBlockElems;
+      uint16_t* Kd = a.Kw + new_at;
+      uint16_t* Vd = a.Vw + new_at;
       if (lane < 16) *(u32x4_t*)(Kd + k_tile_offset(new_key, lane * 8)) = *(const u32x4_t*)(kn + lane * 8);
       Vd[v_tile_offset(new_key, lane)] = vn[lane];
       Vd[v_tile_offset(new_key, lane + 64)] = vn[lane + 64];
@@ -404,6 +422,7 @@ hipError_t launch_decode_tiled(const DecodeLaunch& L, hipStream_t s) {
   TiledDecodeParams p;
   p.K = (const uint16_t*)L.K; p.V = (const uint16_t*)L.V;
   p.d_base = L.d_base; p.d_slots = L.d_slots; p.d_lens = L.d_lens;
+  p.pages = L.pages;
   p.window = L.window; p.attn_window = L.attn_window;
   p.q = (const uint16_t*)L.q; p.out = L.out;
   p.Hq = L.Hq; p.Hkv = L.Hkv; p.G = L.G;

@@ -36,6 +36,8 @@ __device__ inline uint32_t pf_bf16_bits_rn(float f) {
 struct TiledPrefillParams {
   const uint16_t* q; void* out;
   const uint16_t* Kt; const int64_t* k_base; const int32_t* k_slots;  // bf16 tiles
+  PageTable k_pages;                                                   // ... of a paged full cache
+  int Hkv;
   const uint16_t* Vt; const int64_t* v_base; const int32_t* v_slots;  // fp16 tiles
   int window, S, Hq, G;
   float scale_log2;
@@ -145,7 +147,7 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
   }
 
   const int nblk_valid = (qoff + S + kBlockKeys - 1) / kBlockKeys;
-  const u32x4_t* Kg = (const u32x4_t*)(a.Kt + (a.k_base[b] + (int64_t)h * (a.k_slots[b] >> 5)) * kBlockElems);
+  const u32x4_t* Kt = (const u32x4_t*)a.Kt;
   const u32x4_t* Vg = (const u32x4_t*)(a.Vt + (a.v_base[b] + (int64_t)h * (a.v_slots[b] >> 5)) * kBlockElems);
 
   const int last_row = min(q0 + rows_wg, S) - 1;
@@ -172,7 +174,8 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
       uint16_t* lk = sK(buf) + (T * i + wave * 64) * 8;
       uint16_t* lv = sV(buf) + (T * i + wave * 64) * 8;
       if (kb < nblk_valid) {
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Kg + (int64_t)kb * 512 + in_block),
+        const int64_t k_at = tiled_block_index(a.k_base, a.k_slots, a.k_pages, a.Hkv, b, h, kb);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Kt + k_at * 512 + in_block),
                                          (__attribute__((address_space(3))) void*)lk, 16, 0, 0);
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Vg + (int64_t)kb * 512 + in_block),
                                          (__attribute__((address_space(3))) void*)lv, 16, 0, 0);
@@ -346,6 +349,7 @@ hipError_t launch_prefill_tiled(const PrefillLaunch& L, hipStream_t s) {
   TiledPrefillParams p;
   p.q = (const uint16_t*)L.q; p.out = L.out;
   p.Kt = (const uint16_t*)L.Kt; p.k_base = L.k_base; p.k_slots = L.k_slots;
+  p.k_pages = L.k_pages; p.Hkv = L.Hkv;
   p.Vt = (const uint16_t*)L.Vt; p.v_base = L.v_base; p.v_slots = L.v_slots;
   p.window = L.window; p.S = L.S; p.Hq = L.Hq; p.G = L.G;
   p.scale_log2 = L.scale * kLog2e;

@@ -54,6 +54,7 @@ void free_layout(mixattn_layout* L) {
     if (c.V) (void)hipFree(c.V);
     if (c.d_base) (void)hipFree(c.d_base);
     if (c.d_slots) (void)hipFree(c.d_slots);
+    if (c.d_pages) (void)hipFree(c.d_pages);
   }
   void* ptrs[] = {L->d_lens_all, L->scratch.acc, L->scratch.ml, L->scratch.counters, L->stageK, L->stageV,
                   L->d_stage_lens, L->d_stage_src, L->d_readback, L->d_stage_base, L->d_stage_slots,
@@ -133,10 +134,17 @@ int mixattn_validate_config(const mixattn_config* cfg) {
   return MIXATTN_OK;
 }
 
-int mixattn_create_layout(const mixattn_config* cfg, mixattn_layout** out) {
+// page_tokens == 0: contiguous caches.  Otherwise the FULL caches are pools of pool_tokens / page_tokens pages.
+static int create_layout_impl(const mixattn_config* cfg, int page_tokens, int64_t pool_tokens, mixattn_layout** out) {
   if (!out) return MIXATTN_ERR_NULL;
   int st = mixattn_validate_config(cfg);
   if (st != MIXATTN_OK) return st;
+  if (page_tokens != 0) {
+    // whole blocks per page, a power of two of them (the kernels split a block index with a shift and a mask)
+    if (page_tokens < kBlockKeys || (page_tokens & (page_tokens - 1)) != 0) return MIXATTN_ERR_LAYOUT;
+    if (pool_tokens < page_tokens || pool_tokens / page_tokens > INT32_MAX) return MIXATTN_ERR_LAYOUT;
+    if (!use_tiled(cfg->kv_dtype, cfg->head_dim, cfg->n_q_heads / cfg->n_kv_heads)) return MIXATTN_ERR_LAYOUT;
+  }
   mixattn_layout* L = new (std::nothrow) mixattn_layout();
   if (!L) return MIXATTN_ERR_ALLOC;
   if (!hip_ok(hipGetDevice(&L->device))) {
@@ -194,6 +202,7 @@ int mixattn_create_layout(const mixattn_config* cfg, mixattn_layout** out) {
     c.d_lens2[1] = c.d_lens2[0] + B;
     c.cur = 0;
     int64_t run = 0;  // blocks (tiled) or rows (row-major) before sequence b
+    int64_t max_cap = 0;
     for (int b = 0; b < B; ++b) {
       const int64_t want = c.kind == MIXATTN_SLIDING ? c.window : L->capacity[b];
       const int64_t slots = L->tiled ? (want + kBlockKeys - 1) / kBlockKeys * kBlockKeys : want;
@@ -201,8 +210,26 @@ int mixattn_create_layout(const mixattn_config* cfg, mixattn_layout** out) {
       c.slots[b] = (int32_t)slots;
       c.base[b] = run;
       run += (int64_t)L->Hkv * (L->tiled ? slots / kBlockKeys : slots);
+      max_cap = std::max(max_cap, want);
     }
     if (st != MIXATTN_OK) break;
+    c.paged = page_tokens != 0 && c.kind == MIXATTN_FULL;
+    if (c.paged) {
+      const int page_blocks = page_tokens / kBlockKeys;
+      c.page_shift = 0;
+      while ((1 << c.page_shift) < page_blocks) ++c.page_shift;
+      const int64_t n_pages = pool_tokens / page_tokens;
+      c.max_pages = (int)((max_cap + page_tokens - 1) / page_tokens);
+      c.free_pages.resize(n_pages);
+      for (int64_t i = 0; i < n_pages; ++i) c.free_pages[i] = (int32_t)(n_pages - 1 - i);  // page 0 is handed out first
+      c.seq_pages.assign(B, std::vector<int32_t>());
+      run = n_pages * L->Hkv * page_blocks;  // blocks in the pool
+      if ((st = dev_alloc((void**)&c.d_pages, sizeof(int32_t) * (size_t)B * c.max_pages)) != MIXATTN_OK) break;
+      if (!hip_ok(hipMemset(c.d_pages, 0, sizeof(int32_t) * (size_t)B * c.max_pages))) {
+        st = MIXATTN_ERR_HIP;
+        break;
+      }
+    }
     c.total_elems = L->tiled ? run * kBlockElems : run * L->D;
     const size_t bytes = (size_t)c.total_elems * L->elem;
     if ((st = dev_alloc(&c.K, bytes)) != MIXATTN_OK) break;
@@ -240,6 +267,52 @@ int mixattn_create_layout(const mixattn_config* cfg, mixattn_layout** out) {
   return MIXATTN_OK;
 }
 
+int mixattn_create_layout(const mixattn_config* cfg, mixattn_layout** out) {
+  return create_layout_impl(cfg, 0, 0, out);
+}
+
+int mixattn_create_layout_paged(const mixattn_config* cfg, int page_tokens, int64_t pool_tokens,
+                                mixattn_layout** out) {
+  if (page_tokens < 1) return MIXATTN_ERR_LAYOUT;
+  return create_layout_impl(cfg, page_tokens, pool_tokens, out);
+}
+
+// Paged caches: make sure sequence b owns pages for want[b] tokens (all sequences or none: a failed call leaves the
+// tables as they were).  New table entries reach the device through a small kernel on `s`, ahead of the kernels
+// that use them.
+static int reserve_pages(mixattn_layout* L, Cache& c, const std::vector<int64_t>& want, hipStream_t s) {
+  if (!c.paged) return MIXATTN_OK;
+  const int64_t page_tokens = (int64_t)kBlockKeys << c.page_shift;
+  int64_t need = 0;
+  for (int b = 0; b < L->batch; ++b) {
+    const int64_t pages = (want[b] + page_tokens - 1) / page_tokens;
+    if (pages > c.max_pages) return MIXATTN_ERR_CAPACITY;
+    need += std::max<int64_t>(0, pages - (int64_t)c.seq_pages[b].size());
+  }
+  if (need == 0) return MIXATTN_OK;
+  if (need > (int64_t)c.free_pages.size()) return MIXATTN_ERR_CAPACITY;  // the pool is exhausted
+  std::vector<int64_t> index;
+  std::vector<int32_t> value;
+  for (int b = 0; b < L->batch; ++b) {
+    const int64_t pages = (want[b] + page_tokens - 1) / page_tokens;
+    while ((int64_t)c.seq_pages[b].size() < pages) {
+      const int32_t pg = c.free_pages.back();
+      c.free_pages.pop_back();
+      index.push_back((int64_t)b * c.max_pages + (int64_t)c.seq_pages[b].size());
+      value.push_back(pg);
+      c.seq_pages[b].push_back(pg);
+    }
+  }
+  HIP_TRY(launch_scatter_i32(c.d_pages, index.data(), value.data(), (int)index.size(), s));
+  return MIXATTN_OK;
+}
+
+static void release_pages(Cache& c, int b) {
+  if (!c.paged) return;
+  for (auto it = c.seq_pages[b].rbegin(); it != c.seq_pages[b].rend(); ++it) c.free_pages.push_back(*it);
+  c.seq_pages[b].clear();
+}
+
 int mixattn_destroy_layout(mixattn_layout* L) {
   if (!L) return MIXATTN_ERR_NULL;
   (void)hipDeviceSynchronize();
@@ -250,7 +323,25 @@ int mixattn_destroy_layout(mixattn_layout* L) {
 int mixattn_reset(mixattn_layout* L, void* stream) {
   if (!L) return MIXATTN_ERR_NULL;
   HIP_TRY(launch_fill_i32(L->d_lens_all, 0, (int64_t)L->caches.size() * 2 * L->batch, (hipStream_t)stream));
-  for (auto& c : L->caches) std::fill(c.len.begin(), c.len.end(), 0);
+  for (auto& c : L->caches) {
+    std::fill(c.len.begin(), c.len.end(), 0);
+    for (int b = 0; b < L->batch; ++b) release_pages(c, b);
+  }
+  L->stage_cache = -1;
+  return MIXATTN_OK;
+}
+
+int mixattn_release_sequence(mixattn_layout* L, int b, void* stream) {
+  if (!L) return MIXATTN_ERR_NULL;
+  if (b < 0 || b >= L->batch) return MIXATTN_ERR_LAYER;
+  for (auto& c : L->caches) {
+    // both length arrays: a fused append may have left the current one either way round
+    HIP_TRY(launch_fill_i32(c.d_lens2[0] + b, 0, 1, (hipStream_t)stream));
+    HIP_TRY(launch_fill_i32(c.d_lens2[1] + b, 0, 1, (hipStream_t)stream));
+    c.len[b] = 0;
+    c.plan_key = -1;
+    release_pages(c, b);
+  }
   L->stage_cache = -1;
   return MIXATTN_OK;
 }
@@ -264,14 +355,23 @@ static int check_append(const mixattn_layout* L, const Cache& c, int layer) {
   return MIXATTN_OK;
 }
 
+static int reserve_for_append(mixattn_layout* L, Cache& c, hipStream_t s) {
+  if (!c.paged) return MIXATTN_OK;
+  std::vector<int64_t> want(L->batch);
+  for (int b = 0; b < L->batch; ++b) want[b] = c.len[b] + 1;
+  return reserve_pages(L, c, want, s);
+}
+
 int mixattn_append_kv(mixattn_layout* L, int layer, const void* k, const void* v, void* stream) {
   if (!L || !k || !v) return MIXATTN_ERR_NULL;
   if (layer < 0 || layer >= L->n_layers) return MIXATTN_ERR_LAYER;
   Cache& c = L->caches[L->layer_cache[layer]];
-  const int st = check_append(L, c, layer);
+  int st = check_append(L, c, layer);
   if (st != MIXATTN_OK) return st;
+  if ((st = reserve_for_append(L, c, (hipStream_t)stream)) != MIXATTN_OK) return st;
   AppendLaunch a;
   a.K = c.K; a.V = c.V; a.d_base = c.d_base; a.d_slots = c.d_slots; a.d_lens = c.lens();
+  a.pages = c.page_table();
   a.window = c.window; a.k = k; a.v = v;
   a.batch = L->batch; a.Hkv = L->Hkv; a.D = L->D; a.elem = L->elem;
   HIP_TRY(L->tiled ? launch_append_tiled(a, (hipStream_t)stream) : launch_append_rowmajor(a, (hipStream_t)stream));
@@ -375,6 +475,7 @@ static int launch_decode(mixattn_layout* L, Cache& c, int attn_window, const voi
   }
   DecodeLaunch a;
   a.K = c.K; a.V = c.V; a.d_base = c.d_base; a.d_slots = c.d_slots; a.d_lens = c.lens();
+  a.pages = c.page_table();
   a.window = c.window; a.attn_window = attn_window; a.q = q; a.out = out;
   a.batch = L->batch; a.Hq = L->Hq; a.Hkv = L->Hkv; a.G = L->G; a.D = L->D;
   a.kv_dtype = L->kv_dtype; a.out_dtype = L->out_dtype; a.scale = L->scale;
@@ -420,6 +521,7 @@ int mixattn_append_decode(mixattn_layout* L, int layer, const void* k, const voi
     st = mixattn_append_kv(L, layer, k, v, stream);
     return st != MIXATTN_OK ? st : mixattn_decode(L, layer, q, out, stream);
   }
+  if ((st = reserve_for_append(L, c, (hipStream_t)stream)) != MIXATTN_OK) return st;
   st = launch_decode(L, c, 0, q, out, k, v, (hipStream_t)stream);
   if (st != MIXATTN_OK) return st;
   c.cur ^= 1;  // the launch wrote n + 1 into the other length array
@@ -528,12 +630,20 @@ static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void*
 
   // commit of the chunk into this layer's cache (writer): reads lens(), writes n_old + seq_len to lens_other()
   auto commit = [&]() -> int {
+    if (c.paged) {
+      std::vector<int64_t> want(L->batch);
+      for (int b = 0; b < L->batch; ++b) want[b] = c.len[b] + len_of(b);
+      const int e = reserve_pages(L, c, want, s);
+      if (e != MIXATTN_OK) return e;
+    }
     StoreLaunch st;
     st.K = c.K; st.V = c.V; st.d_base = c.d_base; st.d_slots = c.d_slots; st.window = c.window;
+    st.pages = c.page_table();
     set_source(st);
     st.d_n_old = c.lens(); st.old_sub = 0;
     if (L->tiled) {
       st.Kold = c.K; st.Vold = c.V; st.old_base = c.d_base; st.old_slots = c.d_slots; st.old_window = c.window;
+      st.old_pages = c.page_table();
       st.old_is_dest = 1;
     }
     st.d_lens_out = c.lens_other();
@@ -584,6 +694,7 @@ static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void*
       if (chunked) {
         st.d_n_old = c.lens(); st.old_sub = 1;  // lengths already include the chunk
         st.Vold = c.V; st.old_base = c.d_base; st.old_slots = c.d_slots; st.old_window = 0;
+        st.old_pages = c.page_table();
       }
       st.batch = L->batch; st.Hkv = L->Hkv; st.D = L->D; st.elem = L->elem;
       st.max_slots = (int)max_new;
@@ -591,6 +702,7 @@ static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void*
       remember_stage();
     }
     p.Kt = c.K; p.k_base = c.d_base; p.k_slots = c.d_slots;
+    p.k_pages = c.page_table();
     p.Vt = L->stageV; p.v_base = L->d_stage_base; p.v_slots = L->d_stage_slots;
     p.stage_window = 0;
     p.d_lens = chunked ? c.lens() : nullptr; p.old_sub = 1;
@@ -672,6 +784,11 @@ int mixattn_load_kv(mixattn_layout* L, int layer, const void* k, const void* v, 
     max_len = std::max(max_len, seq_lens[b]);
   }
   hipStream_t s = (hipStream_t)stream;
+  if (c.paged) {
+    std::vector<int64_t> want(seq_lens, seq_lens + L->batch);
+    const int pe = reserve_pages(L, c, want, s);
+    if (pe != MIXATTN_OK) return pe;
+  }
   // the device copies of the per-sequence tables may still be read by an earlier load on this stream
   HIP_TRY(hipStreamSynchronize(s));
   int e = upload(L->d_stage_lens, seq_lens, sizeof(int32_t) * L->batch);
@@ -680,6 +797,7 @@ int mixattn_load_kv(mixattn_layout* L, int layer, const void* k, const void* v, 
   if (e != MIXATTN_OK) return e;
   StoreLaunch st;
   st.K = c.K; st.V = c.V; st.d_base = c.d_base; st.d_slots = c.d_slots; st.window = c.window;
+  st.pages = c.page_table();
   st.k_src = k; st.v_src = v; st.d_src_first = L->d_stage_src; st.d_src_len = L->d_stage_lens; st.uniform_len = 0;
   st.d_lens_out = c.lens();
   st.batch = L->batch; st.Hkv = L->Hkv; st.D = L->D; st.elem = L->elem;
@@ -724,8 +842,17 @@ int mixattn_read_cache(mixattn_layout* L, int cache_index, int b, int kv_head, i
   const int64_t limit = c.kind == MIXATTN_SLIDING ? c.window : L->capacity[b];
   if (slot < 0 || slot >= limit) return MIXATTN_ERR_LAYER;
   HIP_TRY(hipDeviceSynchronize());
-  HIP_TRY(launch_gather_row(c.K, c.V, c.base[b], c.slots[b], kv_head, slot, L->D, L->elem, L->tiled, L->d_readback,
-                            nullptr));
+  if (c.paged) {
+    // the page that holds the slot, addressed as a one-page cache of its own
+    const int64_t page_tokens = (int64_t)kBlockKeys << c.page_shift;
+    if (slot / page_tokens >= (int64_t)c.seq_pages[b].size()) return MIXATTN_ERR_LAYER;
+    const int64_t pg = c.seq_pages[b][slot / page_tokens];
+    HIP_TRY(launch_gather_row(c.K, c.V, (pg * L->Hkv) << c.page_shift, (int32_t)page_tokens, kv_head,
+                              slot % page_tokens, L->D, L->elem, true, L->d_readback, nullptr));
+  } else {
+    HIP_TRY(launch_gather_row(c.K, c.V, c.base[b], c.slots[b], kv_head, slot, L->D, L->elem, L->tiled, L->d_readback,
+                              nullptr));
+  }
   HIP_TRY(hipDeviceSynchronize());
   const size_t row = (size_t)L->D * L->elem;
   if (k_row) HIP_TRY(hipMemcpy(k_row, L->d_readback, row, hipMemcpyDeviceToHost));

@@ -35,6 +35,23 @@ __host__ __device__ inline int v_tile_offset(int key, int dim) {
   return (dim >> 4) * 512 + ((((key & 15) >> 2) << 4) + (dim & 15)) * 8 + 4 * (key >> 4) + (key & 3);
 }
 
+// Paged full caches: the blocks of (sequence b, kv head h) sit in pages of (1 << shift) blocks x n_kv_heads; the
+// page of block blk is ids[b * max_pages + (blk >> shift)].  ids == nullptr: contiguous storage.
+struct PageTable {
+  const int32_t* ids = nullptr;
+  int max_pages = 0;
+  int shift = 0;
+};
+// Index (in blocks of kBlockElems elements) of block blk of (sequence b, kv head h) in a tile-format cache.
+__device__ inline int64_t tiled_block_index(const int64_t* d_base, const int32_t* d_slots, const PageTable& pt,
+                                            int Hkv, int b, int h, int blk) {
+  if (pt.ids) {
+    const int64_t pg = pt.ids[(int64_t)b * pt.max_pages + (blk >> pt.shift)];
+    return ((pg * Hkv + h) << pt.shift) + (blk & ((1 << pt.shift) - 1));
+  }
+  return d_base[b] + (int64_t)h * (d_slots[b] >> 5) + blk;
+}
+
 struct Cache {
   int kind = 0;
   int window = 0;      // SLIDING only
@@ -54,6 +71,18 @@ struct Cache {
   int32_t* lens() const { return d_lens2[cur]; }
   int32_t* lens_other() const { return d_lens2[cur ^ 1]; }
   std::vector<int64_t> len;    // host mirror
+  // paged storage (full caches of a paged layout): a pool of pages, handed to sequences as they grow
+  bool paged = false;
+  int page_shift = 0;                 // log2(blocks per page)
+  int max_pages = 0;                  // table width: pages a sequence can hold at most
+  std::vector<int32_t> free_pages;    // stack of free page ids
+  std::vector<std::vector<int32_t>> seq_pages;  // [batch] pages of each sequence, in order
+  int32_t* d_pages = nullptr;         // device [batch][max_pages]
+  PageTable page_table() const {
+    PageTable t;
+    if (paged) { t.ids = d_pages; t.max_pages = max_pages; t.shift = page_shift; }
+    return t;
+  }
   // memo of the last split-K plan (it only changes when a sequence crosses a block boundary)
   int64_t plan_key = -1;
   int plan_max_blocks = -1;
@@ -110,6 +139,7 @@ namespace mixattn {
 struct DecodeLaunch {
   const void* K; const void* V;
   const int64_t* d_base; const int32_t* d_slots; const int32_t* d_lens;
+  PageTable pages;     // tiled path, full caches only
   int window;          // ring size of the cache, 0 = full cache
   int attn_window;     // > 0: sliding layer reading a full cache (attends the last attn_window positions)
   const void* q; void* out;
@@ -133,6 +163,7 @@ struct StoreLaunch {
   void* K = nullptr; void* V = nullptr;  // destination; tiled path: either may be nullptr (that tensor is skipped)
   int v_as_f16 = 0;            // tiled path: store V converted to fp16 (prefill staging), saturating at +-65504
   const int64_t* d_base = nullptr; const int32_t* d_slots = nullptr;  // destination geometry
+  PageTable pages;             // destination is a paged cache (tiled path)
   int window = 0;              // 0 = linear destination; > 0 = ring of that many slots
   int stage_window = 0;        // linear only: > 0 = destination index 0 is position max(0, n_old - (stage_window-1))
   const void* k_src = nullptr; const void* v_src = nullptr;  // new tokens, [tokens, Hkv, D]
@@ -144,6 +175,7 @@ struct StoreLaunch {
   // tokens before n_old (tiled path): read from this tile-format cache; nullptr => none are needed
   const void* Kold = nullptr; const void* Vold = nullptr;
   const int64_t* old_base = nullptr; const int32_t* old_slots = nullptr;
+  PageTable old_pages;         // the old cache is paged
   int old_window = 0;          // ring size of the old cache (0 = full cache)
   int old_is_dest = 0;         // the old cache is the destination itself: blocks without new tokens are skipped
   int32_t* d_lens_out = nullptr;  // device lengths to set to n_old + add (nullptr: leave)
@@ -156,6 +188,7 @@ hipError_t launch_store_rowmajor(const StoreLaunch& a, hipStream_t s);
 struct AppendLaunch {
   void* K; void* V;
   const int64_t* d_base; const int32_t* d_slots; int32_t* d_lens;
+  PageTable pages;
   int window;
   const void* k; const void* v;
   int batch, Hkv, D, elem;
@@ -164,6 +197,8 @@ hipError_t launch_append_tiled(const AppendLaunch& a, hipStream_t s);
 hipError_t launch_append_rowmajor(const AppendLaunch& a, hipStream_t s);
 
 hipError_t launch_fill_i32(int32_t* p, int32_t value, int64_t n, hipStream_t s);
+// table[index[i]] = value[i] for i < n (host arrays; the values travel in the kernel arguments)
+hipError_t launch_scatter_i32(int32_t* table, const int64_t* index, const int32_t* value, int n, hipStream_t s);
 // d_first[i] = first[i], d_len[i] = len[i] for i < n (host arrays; the values travel in the kernel arguments)
 hipError_t launch_set_seq_tables(int64_t* d_first, int32_t* d_len, const int64_t* first, const int32_t* len, int n,
                                  hipStream_t s);
@@ -174,6 +209,7 @@ struct PrefillLaunch {
   const void* q = nullptr; void* out = nullptr;
   // tiled path: K in tile format (the full cache itself or the staging area), V in tile format as fp16 (staging)
   const void* Kt = nullptr; const int64_t* k_base = nullptr; const int32_t* k_slots = nullptr;
+  PageTable k_pages;     // K comes from a paged full cache
   const void* Vt = nullptr; const int64_t* v_base = nullptr; const int32_t* v_slots = nullptr;
   int stage_window = 0;  // > 0: key index 0 of Kt/Vt is position max(0, n_old - (stage_window - 1))
   // row-major path: the caller's chunk tensors, and the row-major cache for positions before the chunk

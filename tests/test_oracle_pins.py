@@ -405,3 +405,29 @@ def test_ragged_prefill_equals_token_by_token_decode_and_brute_force():
     assert [ragged.seq_len(0, b) for b in range(B)] == [9, 9, 3]
     with pytest.raises(ValueError):
         ragged.prefill_ragged(0, np.zeros((3, Hq, d)), np.zeros((3, Hkv, d)), np.zeros((3, Hkv, d)), [1, 1])
+
+
+def test_released_sequence_behaves_like_a_fresh_one():
+    Hq, Hkv, d, W = 4, 2, 8, 3
+    layers = [(FULL, 0, 0), (SLIDING, W, 1)]
+    rng = np.random.default_rng(31)
+    a = _stack(layers, 2, Hq, Hkv, d)
+    k = rng.standard_normal((9, Hkv, d)); v = rng.standard_normal((9, Hkv, d))
+    for li in (0, 1):
+        a.load(li, k, v, [5, 4])
+    a.release_sequence(0)
+    assert [a.seq_len(li, 0) for li in (0, 1)] == [0, 0] and [a.seq_len(li, 1) for li in (0, 1)] == [4, 4]
+    # sequence 0 takes a new request of 2 tokens; sequence 1 sits the call out
+    k2 = rng.standard_normal((2, Hkv, d)); v2 = rng.standard_normal((2, Hkv, d))
+    q2 = rng.standard_normal((2, Hq, d))
+    fresh = _stack(layers, 1, Hq, Hkv, d)
+    for li in (0, 1):
+        got = a.prefill_ragged(li, q2, k2, v2, [2, 0])
+        ref = fresh.prefill_ragged(li, q2, k2, v2, [2])
+        np.testing.assert_array_equal(got, ref)
+    # sequence 1 kept its history
+    q = rng.standard_normal((2, Hq, d))
+    solo = _stack(layers, 1, Hq, Hkv, d)
+    for li in (0, 1):
+        solo.load(li, k[5:], v[5:], [4])
+        np.testing.assert_array_equal(a.decode(li, q, rows=[(1, j) for j in range(Hq)])[1], solo.decode(li, q[1:2])[0])
