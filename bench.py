@@ -50,6 +50,9 @@ def parse():
     ap.add_argument("--gen-new", type=int, default=1000)
     ap.add_argument("--page-tokens", type=int, default=0,
                     help="hold full-attention caches as pools of pages of this many tokens (0: contiguous)")
+    ap.add_argument("--group-decode", action="store_true",
+                    help="decode workloads: serve every sliding-window sharing group with one launch (all its queries "
+                         "at once; an upper bound a model cannot reach, reported beside the per-layer figure)")
     ap.add_argument("--two-call-append", action="store_true",
                     help="writer layers call append_kv and decode separately instead of append_decode")
     ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
@@ -130,8 +133,22 @@ def run_decode(args, mx, wl, torch, w, layers=None, label=None):
     full_layers = [li for li, t in enumerate(layers) if t[0] == wl.FULL]
     kinds = {"": None, "full": wl.FULL, "sliding": wl.SLIDING}[args.only]
 
+    # sliding-window sharing groups for --group-decode: writer layer -> all layers on its ring, queries stacked
+    groups = {}
+    if args.group_decode:
+        for li, (kind, W, cid) in enumerate(layers):
+            if kind == wl.SLIDING and layers[lay.writer_of(li)][0] == wl.SLIDING:
+                groups.setdefault(lay.writer_of(li), []).append(li)
+        group_q = {wr: torch.stack([qs[li] for li in ls]).contiguous() for wr, ls in groups.items()}
+        group_out = {wr: torch.empty((len(ls), B, Hq, d), dtype=lay.out_torch, device=dev) for wr, ls in groups.items()}
+    grouped = {li for ls in groups.values() for li in ls}
+
     def step(events=None):
         for li in range(len(layers)):
+            if li in grouped:
+                if li in groups and kinds in (None, wl.SLIDING):
+                    lay.decode_group(groups[li], group_q[li], ks[li], vs[li], group_out[li])
+                continue
             skip = kinds is not None and layers[li][0] != kinds
             fused = ks[li] is not None and not args.two_call_append and not skip
             if ks[li] is not None and not fused:
@@ -169,6 +186,8 @@ def run_decode(args, mx, wl, torch, w, layers=None, label=None):
     kv_full_launch = 0
     for li, (kind, W, _) in enumerate(layers):
         tok = sum(n if kind == wl.FULL else min(n, W) for n in ctx_lens)
+        if li in grouped and li not in groups:
+            continue   # a group launch reads the ring once for all its layers
         if kinds is None or kind == kinds:
             kv_step += tok * per_tok
         if kind == wl.FULL:
@@ -399,7 +418,8 @@ def main():
             "config": {"workload": w.name, "batch": w.batch, "context": w.context, "window": 1024,
                        "layers": "24: 0,12 full; 22 sliding in groups {1-4,5-8,9-11},{13-16,17-20,21-23}",
                        "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
-                       "out_dtype": args.out_dtype, "only": args.only or "all", "page_tokens": args.page_tokens},
+                       "out_dtype": args.out_dtype, "only": args.only or "all", "page_tokens": args.page_tokens,
+                       "group_decode": bool(args.group_decode)},
             "kv_bytes_read_per_step": r["kv_bytes_per_step"],
             "kv_bytes_resident": r["kv_bytes_resident"],
             "decode_attn_logical_GBps": r["logical_gbs"],

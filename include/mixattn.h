@@ -141,6 +141,20 @@ int mixattn_decode(mixattn_layout* L, int layer, const void* q, void* out, void*
 int mixattn_append_decode(mixattn_layout* L, int layer, const void* k, const void* v, const void* q, void* out,
                           void* stream);
 
+/* Benchmark-side upper bound for a sharing group of sliding-window layers (Section 3, KV cache reuse): the decode
+   step of `n_layers` layers that read one ring cache, served by ONE pass over the ring.  A model cannot call this
+   (layer i + 1's query depends on layer i's output); it measures what sharing could save at most when the ring is
+   read once per group instead of once per layer.
+   layers: host array of n_layers distinct layer indices, all reading the same SLIDING cache; n_layers * group
+   size (query heads per KV head) <= 16.  q, out: device [n_layers, batch, n_q_heads, head_dim], layer i of the
+   array at index i; each layer's result is that of mixattn_decode for it.  k, v: both NULL (the step's token is
+   already in the cache) or this step's token [batch, n_kv_heads, head_dim], appended by the same launch as in
+   mixattn_append_decode; layers[0] must then be the cache's writer.  MFMA path only.
+   Errors: NULL, LAYER (index out of range or repeated), LAYOUT (different caches, a full cache, too many layers,
+   not the MFMA path), NOT_WRITER, ORDER (empty sequence and no token given). */
+int mixattn_decode_group(mixattn_layout* L, const int32_t* layers, int n_layers, const void* k, const void* v,
+                         const void* q, void* out, void* stream);
+
 /* Prompt attention for seq_len new tokens per sequence (causal; SLIDING layers also mask keys more than window-1
    tokens back).  The tokens follow the n_b tokens the cache already holds, so a prompt may be fed in chunks: query
    row i of sequence b sits at position n_b + i and attends the cache contents and the chunk.

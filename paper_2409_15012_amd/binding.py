@@ -23,7 +23,7 @@ PARAM_CHUNK_KEYS, PARAM_FUSED_COMBINE, PARAM_PREFILL_SIMPLE, PARAM_PREFILL_WAVES
 EXPORTS = [
     "mixattn_validate_config", "mixattn_create_layout", "mixattn_create_layout_paged", "mixattn_destroy_layout",
     "mixattn_reset", "mixattn_release_sequence",
-    "mixattn_append_kv", "mixattn_decode", "mixattn_append_decode", "mixattn_prefill", "mixattn_prefill_varlen",
+    "mixattn_append_kv", "mixattn_decode", "mixattn_append_decode", "mixattn_decode_group", "mixattn_prefill", "mixattn_prefill_varlen",
     "mixattn_load_kv", "mixattn_n_caches",
     "mixattn_cache_of", "mixattn_seq_len", "mixattn_slot_of", "mixattn_slot_for", "mixattn_read_cache",
     "mixattn_read_device_lens", "mixattn_kv_bytes_allocated", "mixattn_kv_bytes_live", "mixattn_step_read_bytes",
@@ -69,6 +69,7 @@ def load():
     lib.mixattn_append_kv.argtypes = [vp, i32, vp, vp, vp]
     lib.mixattn_decode.argtypes = [vp, i32, vp, vp, vp]
     lib.mixattn_append_decode.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+    lib.mixattn_decode_group.argtypes = [vp, C.POINTER(C.c_int32), i32, vp, vp, vp, vp, vp]
     lib.mixattn_prefill.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
     lib.mixattn_prefill_varlen.argtypes = [vp, i32, vp, vp, vp, vp, C.POINTER(C.c_int32), vp]
     lib.mixattn_load_kv.argtypes = [vp, i32, vp, vp, C.POINTER(C.c_int32), vp]
@@ -212,6 +213,22 @@ class Layout:
             self._dtype_check(out, self.out_torch, (self.batch, self.Hq, self.d))
         self._check(self.lib.mixattn_append_decode(self.h, layer, _ptr(k), _ptr(v), _ptr(q), _ptr(out), _stream()),
                     "mixattn_append_decode")
+        return out
+
+    def decode_group(self, layers: Sequence[int], q: torch.Tensor, k: Optional[torch.Tensor] = None,
+                     v: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        n = len(layers)
+        self._dtype_check(q, self.kv_torch, (n, self.batch, self.Hq, self.d))
+        for t in (k, v):
+            if t is not None:
+                self._dtype_check(t, self.kv_torch, (self.batch, self.Hkv, self.d))
+        if out is None:
+            out = torch.empty((n, self.batch, self.Hq, self.d), dtype=self.out_torch, device=q.device)
+        else:
+            self._dtype_check(out, self.out_torch, (n, self.batch, self.Hq, self.d))
+        arr = (C.c_int32 * max(n, 1))(*[int(l) for l in layers])
+        self._check(self.lib.mixattn_decode_group(self.h, arr, n, _ptr(k), _ptr(v), _ptr(q), _ptr(out), _stream()),
+                    "mixattn_decode_group")
         return out
 
     def prefill(self, layer: int, q: torch.Tensor, k: Optional[torch.Tensor], v: Optional[torch.Tensor],

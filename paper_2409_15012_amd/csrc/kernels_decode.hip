@@ -54,6 +54,9 @@ struct TiledDecodeParams {
   float* p_acc; float* p_ml; uint32_t* counters;
   // fused append (writer layers): this step's token, writable cache pointers, length array to receive n + 1
   const uint16_t* k_new; const uint16_t* v_new; uint16_t* Kw; uint16_t* Vw; int32_t* d_lens_out;
+  // group launch (GROUP): n_group layers of one sharing group in one pass over the ring; layer i's q and out
+  // start layer_rows * i rows after the first layer's (a row = one query head of one sequence)
+  int n_group; int64_t layer_rows;
 };
 
 // device-scope coherent accesses (relaxed atomics): they go past the XCD-private L2
@@ -86,9 +89,14 @@ __device__ inline void merge_partials(const float* p_acc, const float* p_ml, int
 // (the old one is still being read by other workgroups of this launch).
 // WINDOWED (full caches only): the layer is a sliding-window layer that shares a standard layer's cache; it reads
 // the blocks holding positions n - attn_window .. n - 1 and masks the keys before that range.
-template <typename OutT, bool RING, bool FUSED, bool WINDOWED = false>
+// GROUP (rings only): the 16 head columns carry the G query heads of up to 16 / G layers that read this ring, so one
+// pass over the ring serves the whole sharing group.  No column is left for the remainders: they go through a
+// second set of P x V products instead, which keeps the arithmetic of a column the same as in a one-layer launch.
+template <typename OutT, bool RING, bool FUSED, bool WINDOWED = false, bool GROUP = false>
 __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(TiledDecodeParams a) {
   static_assert(!(WINDOWED && (RING || FUSED)), "a windowed reader of a full cache never writes it");
+  static_assert(!GROUP || RING, "group launches serve ring caches");
+  constexpr int kCols = GROUP ? 16 : kMaxGroup;  // head columns that carry results
   constexpr int NW = kDecodeWaves;
   const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int n_old = a.d_lens[b];
@@ -111,13 +119,16 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the block loop on scalar branches
   const int col = lane & 15, g = lane >> 4;
   const int G = a.G;
-  const bool is_hi = col < G, is_lo = (col >= G) && (col < 2 * G);
-  const int head = is_hi ? col : col - G;  // meaningful when is_hi || is_lo
+  const int ncols = GROUP ? a.n_group * G : G;
+  const bool is_hi = col < ncols, is_lo = !GROUP && (col >= G) && (col < 2 * G);
+  const int col_layer = GROUP ? col / G : 0;
+  const int head = GROUP ? col - col_layer * G : (is_hi ? col : col - G);  // meaningful when is_hi || is_lo
 
   // Q^T fragments: lane (col, g) holds dims kk*32 + g*8 .. +7 of its head, zeros in padding columns
   bf16x8_t qf[4];
   {
-    const uint16_t* qp = a.q + ((int64_t)b * a.Hq + (int64_t)h * G + head) * kTiledDim + g * 8;
+    const uint16_t* qp =
+        a.q + (col_layer * a.layer_rows + (int64_t)b * a.Hq + (int64_t)h * G + head) * kTiledDim + g * 8;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       u32x4_t raw = {0u, 0u, 0u, 0u};
@@ -217,12 +228,13 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
       psum += p[j];
     }
     lsum = lsum * alpha + psum;
-    uint32_t pb[8];
+    uint32_t pb[8], pr[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const uint32_t hi = bf16_bits_rn(p[j]);
       const float rem = p[j] - __uint_as_float(hi << 16);
-      pb[j] = is_lo ? bf16_bits_rn(rem) : hi;
+      pr[j] = bf16_bits_rn(rem);
+      pb[j] = is_lo ? pr[j] : hi;
     }
     u32x4_t pw = {pb[0] | (pb[1] << 16), pb[2] | (pb[3] << 16), pb[4] | (pb[5] << 16), pb[6] | (pb[7] << 16)};
     const bf16x8_t pf = __builtin_bit_cast(bf16x8_t, pw);
@@ -230,6 +242,13 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
     for (int nn = 0; nn < 8; ++nn) {
       o[nn] *= alpha;
       o[nn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vd[nn]), pf, o[nn], 0, 0, 0);
+    }
+    if constexpr (GROUP) {
+      u32x4_t rw = {pr[0] | (pr[1] << 16), pr[2] | (pr[3] << 16), pr[4] | (pr[5] << 16), pr[6] | (pr[7] << 16)};
+      const bf16x8_t rf = __builtin_bit_cast(bf16x8_t, rw);
+#pragma unroll
+      for (int nn = 0; nn < 8; ++nn)
+        o[nn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vd[nn]), rf, o[nn], 0, 0, 0);
     }
   };
   using no_tail = std::integral_constant<bool, false>;
@@ -315,14 +334,16 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
   // ---- wave epilogue: total sum over the 4 lane groups, remainder columns folded into their head's column
   lsum += __shfl_xor(lsum, 16);
   lsum += __shfl_xor(lsum, 32);
+  if constexpr (!GROUP) {
 #pragma unroll
-  for (int nn = 0; nn < 8; ++nn)
+    for (int nn = 0; nn < 8; ++nn)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) o[nn][i] += __shfl_down(o[nn][i], G);  // lane col+G of the same 16-lane row
+      for (int i = 0; i < 4; ++i) o[nn][i] += __shfl_down(o[nn][i], G);  // lane col+G of the same 16-lane row
+  }
 
-  __shared__ float s_o[NW][kMaxGroup][kTiledDim];
-  __shared__ float s_m[NW][kMaxGroup];
-  __shared__ float s_l[NW][kMaxGroup];
+  __shared__ float s_o[NW][kCols][kTiledDim];
+  __shared__ float s_m[NW][kCols];
+  __shared__ float s_l[NW][kCols];
   __shared__ int s_last;
   if (is_hi) {
 #pragma unroll
@@ -338,7 +359,12 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
 
   const bool direct = (a.n_chunks == 1);
   const bool fused = !direct && a.fused_combine;
-  for (int idx = tid; idx < G * kTiledDim; idx += NW * 64) {
+  // result row of head column hd: the layer's block of rows, then (sequence, query head)
+  auto row_of = [&](int hd) -> int64_t {
+    const int gl = GROUP ? hd / G : 0;
+    return gl * a.layer_rows + (int64_t)b * a.Hq + (int64_t)h * G + (hd - gl * G);
+  };
+  for (int idx = tid; idx < ncols * kTiledDim; idx += NW * 64) {
     const int hd = idx >> 7, d = idx & 127;
     float M = s_m[0][hd];
 #pragma unroll
@@ -350,7 +376,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
       L += s_l[w][hd] * wgt;
       acc += s_o[w][hd][d] * wgt;
     }
-    const int64_t row = (int64_t)b * a.Hq + (int64_t)h * G + hd;
+    const int64_t row = row_of(hd);
     if (direct) {
       store_out<OutT>((OutT*)a.out + row * kTiledDim + d, acc / L);
     } else {
@@ -387,9 +413,9 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
   }
   __syncthreads();
   if (!s_last) return;
-  for (int idx = tid; idx < G * kTiledDim; idx += NW * 64) {
+  for (int idx = tid; idx < ncols * kTiledDim; idx += NW * 64) {
     const int hd = idx >> 7, d = idx & 127;
-    const int64_t row = (int64_t)b * a.Hq + (int64_t)h * G + hd;
+    const int64_t row = row_of(hd);
     const float* p_acc = a.p_acc + row * kMaxChunks * kTiledDim;
     const float* p_ml = a.p_ml + row * kMaxChunks * 2;
     float M = -INFINITY;
@@ -413,7 +439,7 @@ __global__ __launch_bounds__(kTiledDim) void combine_kernel(TiledDecodeParams a)
   const int lo = (a.attn_window > 0 && n > a.attn_window) ? n - a.attn_window : 0;
   const int nb_read = nb_total - lo / kBlockKeys;
   const int n_chunks_b = (nb_read + a.chunk_blocks - 1) / a.chunk_blocks;
-  const int64_t row = (int64_t)b * a.Hq + hq;
+  const int64_t row = blockIdx.z * a.layer_rows + (int64_t)b * a.Hq + hq;  // z: layer of a group launch
   merge_partials<OutT>(a.p_acc + row * kMaxChunks * kTiledDim, a.p_ml + row * kMaxChunks * 2, n_chunks_b,
                        threadIdx.x, (OutT*)a.out + row * kTiledDim);
 }
@@ -432,11 +458,21 @@ hipError_t launch_decode_tiled(const DecodeLaunch& L, hipStream_t s) {
   p.p_acc = L.scratch.acc; p.p_ml = L.scratch.ml; p.counters = L.scratch.counters;
   p.k_new = (const uint16_t*)L.k_new; p.v_new = (const uint16_t*)L.v_new;
   p.Kw = (uint16_t*)L.K; p.Vw = (uint16_t*)L.V; p.d_lens_out = L.d_lens_out;
+  p.n_group = L.n_group; p.layer_rows = (int64_t)L.batch * L.Hq;
   const dim3 grid(L.n_chunks, L.Hkv, L.batch);
   const bool f32 = L.out_dtype == MIXATTN_F32, ring = L.window > 0, fused = L.k_new != nullptr;
 #define MIXATTN_LAUNCH_DECODE(OUT, RING, FUSED) \
   hipLaunchKernelGGL((decode_tiled_kernel<OUT, RING, FUSED>), grid, dim3(kDecodeWaves * 64), 0, s, p)
-  if (L.attn_window > 0) {
+  if (L.n_group > 0) {  // several layers of one ring's sharing group in one launch
+#define MIXATTN_LAUNCH_GROUP(OUT, FUSED) \
+  hipLaunchKernelGGL((decode_tiled_kernel<OUT, true, FUSED, false, true>), grid, dim3(kDecodeWaves * 64), 0, s, p)
+    if (!ring || L.n_group * L.G > 16) return hipErrorInvalidValue;
+    if (f32 && fused) MIXATTN_LAUNCH_GROUP(float, true);
+    else if (f32) MIXATTN_LAUNCH_GROUP(float, false);
+    else if (fused) MIXATTN_LAUNCH_GROUP(uint16_t, true);
+    else MIXATTN_LAUNCH_GROUP(uint16_t, false);
+#undef MIXATTN_LAUNCH_GROUP
+  } else if (L.attn_window > 0) {
     if (f32) hipLaunchKernelGGL((decode_tiled_kernel<float, false, false, true>), grid, dim3(kDecodeWaves * 64), 0, s, p);
     else hipLaunchKernelGGL((decode_tiled_kernel<uint16_t, false, false, true>), grid, dim3(kDecodeWaves * 64), 0, s, p);
   } else if (fused) {
@@ -454,7 +490,7 @@ hipError_t launch_decode_tiled(const DecodeLaunch& L, hipStream_t s) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (L.n_chunks > 1 && !L.fused_combine) {
-    const dim3 cgrid(L.Hq, L.batch), cblock(kTiledDim);
+    const dim3 cgrid(L.Hq, L.batch, std::max(L.n_group, 1)), cblock(kTiledDim);
     if (L.out_dtype == MIXATTN_F32)
       hipLaunchKernelGGL(combine_kernel<float>, cgrid, cblock, 0, s, p);
     else

@@ -244,7 +244,16 @@ static int create_layout_impl(const mixattn_config* cfg, int page_tokens, int64_
     if ((st = upload(c.d_slots, c.slots.data(), sizeof(int32_t) * B)) != MIXATTN_OK) break;
   }
   if (st == MIXATTN_OK && L->tiled) {
-    const size_t rows = (size_t)B * L->Hq * kMaxChunks;
+    // a group launch serves up to 16 / G layers of one ring at once and keeps partial results for all of them
+    int group_layers = 1;
+    for (size_t ci = 0; ci < L->caches.size(); ++ci) {
+      if (L->caches[ci].kind != MIXATTN_SLIDING) continue;
+      int users = 0;
+      for (int l = 0; l < L->n_layers; ++l) users += L->layer_cache[l] == (int)ci;
+      group_layers = std::max(group_layers, std::min(users, 16 / L->G));
+    }
+    L->group_layers = group_layers;
+    const size_t rows = (size_t)group_layers * B * L->Hq * kMaxChunks;
     st = dev_alloc((void**)&L->scratch.acc, rows * L->D * sizeof(float));
     if (st == MIXATTN_OK) st = dev_alloc((void**)&L->scratch.ml, rows * 2 * sizeof(float));
     if (st == MIXATTN_OK) st = dev_alloc((void**)&L->scratch.counters, sizeof(uint32_t) * (size_t)B * L->Hkv);
@@ -461,7 +470,7 @@ static int plan_chunk_blocks(const mixattn_layout* L, Cache& c, int max_blocks, 
 // Decode launch shared by mixattn_decode and mixattn_append_decode.  `extra` = 1 when a fused launch appends this
 // step's token itself (lengths on host and device still hold the old value while planning).
 static int launch_decode(mixattn_layout* L, Cache& c, int attn_window, const void* q, void* out, const void* k_new,
-                         const void* v_new, hipStream_t stream) {
+                         const void* v_new, hipStream_t stream, int n_group = 0) {
   const int extra = k_new ? 1 : 0;
   int max_blocks = 0;  // most blocks one sequence reads
   for (int b = 0; b < L->batch; ++b) {
@@ -482,6 +491,7 @@ static int launch_decode(mixattn_layout* L, Cache& c, int attn_window, const voi
   a.scratch = L->scratch;
   a.fused_combine = (int)L->fused_combine;
   a.k_new = k_new; a.v_new = v_new; a.d_lens_out = k_new ? c.lens_other() : nullptr;
+  a.n_group = n_group;
   if (!L->tiled) {
     a.max_blocks = a.chunk_blocks = a.n_chunks = 0;
     HIP_TRY(launch_decode_rowmajor(a, stream));
@@ -526,6 +536,36 @@ int mixattn_append_decode(mixattn_layout* L, int layer, const void* k, const voi
   if (st != MIXATTN_OK) return st;
   c.cur ^= 1;  // the launch wrote n + 1 into the other length array
   for (int b = 0; b < L->batch; ++b) c.len[b] += 1;
+  return MIXATTN_OK;
+}
+
+int mixattn_decode_group(mixattn_layout* L, const int32_t* layers, int n_layers, const void* k, const void* v,
+                         const void* q, void* out, void* stream) {
+  if (!L || !layers || !q || !out || (k == nullptr) != (v == nullptr)) return MIXATTN_ERR_NULL;
+  if (n_layers < 1) return MIXATTN_ERR_LAYER;
+  for (int i = 0; i < n_layers; ++i) {
+    if (layers[i] < 0 || layers[i] >= L->n_layers) return MIXATTN_ERR_LAYER;
+    for (int j = 0; j < i; ++j)
+      if (layers[j] == layers[i]) return MIXATTN_ERR_LAYER;
+  }
+  const int ci = L->layer_cache[layers[0]];
+  Cache& c = L->caches[ci];
+  for (int i = 1; i < n_layers; ++i)
+    if (L->layer_cache[layers[i]] != ci) return MIXATTN_ERR_LAYOUT;
+  if (!L->tiled || c.kind != MIXATTN_SLIDING || n_layers > L->group_layers) return MIXATTN_ERR_LAYOUT;
+  if (k) {
+    const int st = check_append(L, c, layers[0]);
+    if (st != MIXATTN_OK) return st;
+  } else {
+    for (int b = 0; b < L->batch; ++b)
+      if (c.len[b] < 1) return MIXATTN_ERR_ORDER;
+  }
+  const int st = launch_decode(L, c, 0, q, out, k, v, (hipStream_t)stream, n_layers);
+  if (st != MIXATTN_OK) return st;
+  if (k) {
+    c.cur ^= 1;  // the launch wrote n + 1 into the other length array
+    for (int b = 0; b < L->batch; ++b) c.len[b] += 1;
+  }
   return MIXATTN_OK;
 }
 

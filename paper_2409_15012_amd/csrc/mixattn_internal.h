@@ -90,8 +90,9 @@ struct Cache {
 };
 
 struct DecodeScratch {
-  float* acc = nullptr;  // [batch][n_q_heads][kMaxChunks][head_dim]
-  float* ml = nullptr;   // [batch][n_q_heads][kMaxChunks][2]  (max in log2 units, sum)
+  // `layers` = most layers one group launch serves (1 when no ring has a reader)
+  float* acc = nullptr;  // [layers][batch][n_q_heads][kMaxChunks][head_dim]
+  float* ml = nullptr;   // [layers][batch][n_q_heads][kMaxChunks][2]  (max in log2 units, sum)
   uint32_t* counters = nullptr;  // [batch][n_kv_heads] arrival counters for the fused combine
 };
 
@@ -129,6 +130,7 @@ struct mixattn_layout {
   int64_t prefill_simple = 0;
   int64_t prefill_waves = 0; // 0 = automatic
   int64_t prefill_heads = 0; // 0 = automatic
+  int group_layers = 1;      // most layers one group launch may serve (sizes the split-K scratch)
   int device = 0;
   int n_cus = 256;
 };
@@ -153,6 +155,8 @@ struct DecodeLaunch {
   DecodeScratch scratch;
   // fused append (tiled path): this step's k, v [batch, Hkv, D] and the length array that receives n + 1; nullptr = none
   const void* k_new = nullptr; const void* v_new = nullptr; int32_t* d_lens_out = nullptr;
+  // > 0 (tiled path, rings only): q and out hold n_group layers, [n_group][batch][Hq][D]; scratch rows likewise
+  int n_group = 0;
 };
 hipError_t launch_decode_tiled(const DecodeLaunch& a, hipStream_t s);
 hipError_t launch_decode_rowmajor(const DecodeLaunch& a, hipStream_t s);
