@@ -163,11 +163,13 @@ int mixattn_decode_group(mixattn_layout* L, const int32_t* layers, int n_layers,
    every n_b grows by seq_len.  Reader layer: runs after its writer's call for the same chunk (its cache then holds
    n_b >= seq_len tokens, the last seq_len being the chunk); pass the writer's k, v again (attended over, not
    stored).  On the MFMA path (bf16, head_dim 128) a reader may instead pass k = v = NULL to reuse the tile-format
-   copy that the most recent mixattn_prefill call on this layout staged, provided that call was for the same cache
-   and seq_len (ORDER otherwise): the cheap way to run the readers of a sharing group right after their writer, and
-   the only way for readers of a SLIDING cache past the first chunk (the writer's commit has overwritten ring slots
-   their first rows need; ORDER if k, v are passed there, and on the scalar path).  On the MFMA path V is staged as
-   fp16 (values beyond +-65504 saturate).  Errors: ORDER, CAPACITY, NULL. */
+   copy of the chunk that a prefill call for the same cache and seq_len staged (ORDER when there is none).  A
+   SLIDING cache that has readers keeps that copy to itself until its next chunk, append, load or release, so its
+   readers may come at any later point of the layer loop; all other caches share one staging area, which holds the
+   chunk of whichever of them ran prefill last.  Passing NULL is the cheap way to run the readers of a sharing
+   group, and the only way for readers of a SLIDING cache past the first chunk (the writer's commit has
+   overwritten ring slots their first rows need; ORDER if k, v are passed there, and on the scalar path).  On the
+   MFMA path V is staged as fp16 (values beyond +-65504 saturate).  Errors: ORDER, CAPACITY, NULL. */
 int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, const void* v, void* out,
                     int seq_len, void* stream);
 

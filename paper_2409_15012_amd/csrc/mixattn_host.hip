@@ -47,6 +47,13 @@ int upload(void* dst, const void* src, size_t bytes) {
   return MIXATTN_OK;
 }
 
+void free_stage(Stage& st) {
+  void* ptrs[] = {st.K, st.V, st.d_base, st.d_slots};
+  for (void* p : ptrs)
+    if (p) (void)hipFree(p);
+  st = Stage();
+}
+
 void free_layout(mixattn_layout* L) {
   if (!L) return;
   for (auto& c : L->caches) {
@@ -55,10 +62,11 @@ void free_layout(mixattn_layout* L) {
     if (c.d_base) (void)hipFree(c.d_base);
     if (c.d_slots) (void)hipFree(c.d_slots);
     if (c.d_pages) (void)hipFree(c.d_pages);
+    free_stage(c.own_stage);
   }
-  void* ptrs[] = {L->d_lens_all, L->scratch.acc, L->scratch.ml, L->scratch.counters, L->stageK, L->stageV,
-                  L->d_stage_lens, L->d_stage_src, L->d_readback, L->d_stage_base, L->d_stage_slots,
-                  L->d_q_first, L->d_q_len};
+  free_stage(L->stage);
+  void* ptrs[] = {L->d_lens_all, L->scratch.acc, L->scratch.ml, L->scratch.counters,
+                  L->d_stage_lens, L->d_stage_src, L->d_readback, L->d_q_first, L->d_q_len};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   delete L;
@@ -188,6 +196,7 @@ static int create_layout_impl(const mixattn_config* cfg, int page_tokens, int64_
     } else {
       L->layer_cache[i] = it->second;
     }
+    L->caches[L->layer_cache[i]].n_users += 1;
   }
   const int B = L->batch;
   const int nc = (int)L->caches.size();
@@ -264,8 +273,6 @@ static int create_layout_impl(const mixattn_config* cfg, int page_tokens, int64_
   if (st == MIXATTN_OK) st = dev_alloc((void**)&L->d_stage_src, sizeof(int64_t) * B);
   if (st == MIXATTN_OK) st = dev_alloc((void**)&L->d_q_first, sizeof(int64_t) * B);
   if (st == MIXATTN_OK) st = dev_alloc((void**)&L->d_q_len, sizeof(int32_t) * B);
-  if (st == MIXATTN_OK) st = dev_alloc((void**)&L->d_stage_base, sizeof(int64_t) * B);
-  if (st == MIXATTN_OK) st = dev_alloc((void**)&L->d_stage_slots, sizeof(int32_t) * B);
   if (st == MIXATTN_OK) st = dev_alloc(&L->d_readback, 2 * kMaxHeadDim * sizeof(float));
   if (st == MIXATTN_OK && !hip_ok(hipDeviceSynchronize())) st = MIXATTN_ERR_HIP;
   if (st != MIXATTN_OK) {
@@ -335,8 +342,9 @@ int mixattn_reset(mixattn_layout* L, void* stream) {
   for (auto& c : L->caches) {
     std::fill(c.len.begin(), c.len.end(), 0);
     for (int b = 0; b < L->batch; ++b) release_pages(c, b);
+    c.own_stage.cache = -1;
   }
-  L->stage_cache = -1;
+  L->stage.cache = -1;
   return MIXATTN_OK;
 }
 
@@ -350,9 +358,16 @@ int mixattn_release_sequence(mixattn_layout* L, int b, void* stream) {
     c.len[b] = 0;
     c.plan_key = -1;
     release_pages(c, b);
+    c.own_stage.cache = -1;
   }
-  L->stage_cache = -1;
+  L->stage.cache = -1;
   return MIXATTN_OK;
+}
+
+// A staged prompt chunk describes the cache as its writer's prefill left it: any other change to the cache retires it.
+static void retire_stage(mixattn_layout* L, Cache& c) {
+  c.own_stage.cache = -1;
+  if (L->stage.cache == (int)(&c - L->caches.data())) L->stage.cache = -1;
 }
 
 static int check_append(const mixattn_layout* L, const Cache& c, int layer) {
@@ -378,6 +393,7 @@ int mixattn_append_kv(mixattn_layout* L, int layer, const void* k, const void* v
   int st = check_append(L, c, layer);
   if (st != MIXATTN_OK) return st;
   if ((st = reserve_for_append(L, c, (hipStream_t)stream)) != MIXATTN_OK) return st;
+  retire_stage(L, c);
   AppendLaunch a;
   a.K = c.K; a.V = c.V; a.d_base = c.d_base; a.d_slots = c.d_slots; a.d_lens = c.lens();
   a.pages = c.page_table();
@@ -532,6 +548,7 @@ int mixattn_append_decode(mixattn_layout* L, int layer, const void* k, const voi
     return st != MIXATTN_OK ? st : mixattn_decode(L, layer, q, out, stream);
   }
   if ((st = reserve_for_append(L, c, (hipStream_t)stream)) != MIXATTN_OK) return st;
+  retire_stage(L, c);
   st = launch_decode(L, c, 0, q, out, k, v, (hipStream_t)stream);
   if (st != MIXATTN_OK) return st;
   c.cur ^= 1;  // the launch wrote n + 1 into the other length array
@@ -556,6 +573,7 @@ int mixattn_decode_group(mixattn_layout* L, const int32_t* layers, int n_layers,
   if (k) {
     const int st = check_append(L, c, layers[0]);
     if (st != MIXATTN_OK) return st;
+    retire_stage(L, c);
   } else {
     for (int b = 0; b < L->batch; ++b)
       if (c.len[b] < 1) return MIXATTN_ERR_ORDER;
@@ -569,26 +587,27 @@ int mixattn_decode_group(mixattn_layout* L, const int32_t* layers, int n_layers,
   return MIXATTN_OK;
 }
 
-static int ensure_stage(mixattn_layout* L, int64_t blocks_per_head) {
-  if (L->stage_blocks >= blocks_per_head) return MIXATTN_OK;
-  // the old staging area may still be in use by work in flight
+static int ensure_stage(mixattn_layout* L, Stage& S, int64_t blocks_per_head) {
+  if (S.blocks >= blocks_per_head) return MIXATTN_OK;
+  // the old area may still be in use by work in flight
   HIP_TRY(hipDeviceSynchronize());
-  if (L->stageK) (void)hipFree(L->stageK);
-  if (L->stageV) (void)hipFree(L->stageV);
-  L->stageK = L->stageV = nullptr;
-  L->stage_blocks = 0;
-  L->stage_cache = -1;
+  if (S.K) (void)hipFree(S.K);
+  if (S.V) (void)hipFree(S.V);
+  S.K = S.V = nullptr;
+  S.blocks = 0;
+  S.cache = -1;
+  int st;
+  if (!S.d_base && (st = dev_alloc((void**)&S.d_base, sizeof(int64_t) * L->batch)) != MIXATTN_OK) return st;
+  if (!S.d_slots && (st = dev_alloc((void**)&S.d_slots, sizeof(int32_t) * L->batch)) != MIXATTN_OK) return st;
   const size_t bytes = (size_t)L->batch * L->Hkv * blocks_per_head * kBlockElems * 2;
-  int st = dev_alloc(&L->stageK, bytes);
-  if (st != MIXATTN_OK) return st;
-  st = dev_alloc(&L->stageV, bytes);
-  if (st != MIXATTN_OK) return st;
+  if ((st = dev_alloc(&S.K, bytes)) != MIXATTN_OK) return st;
+  if ((st = dev_alloc(&S.V, bytes)) != MIXATTN_OK) return st;
   std::vector<int64_t> base(L->batch);
   std::vector<int32_t> slots(L->batch, (int32_t)(blocks_per_head * kBlockKeys));
   for (int b = 0; b < L->batch; ++b) base[b] = (int64_t)b * L->Hkv * blocks_per_head;
-  if ((st = upload(L->d_stage_base, base.data(), sizeof(int64_t) * L->batch)) != MIXATTN_OK) return st;
-  if ((st = upload(L->d_stage_slots, slots.data(), sizeof(int32_t) * L->batch)) != MIXATTN_OK) return st;
-  L->stage_blocks = blocks_per_head;
+  if ((st = upload(S.d_base, base.data(), sizeof(int64_t) * L->batch)) != MIXATTN_OK) return st;
+  if ((st = upload(S.d_slots, slots.data(), sizeof(int32_t) * L->batch)) != MIXATTN_OK) return st;
+  S.blocks = blocks_per_head;
   return MIXATTN_OK;
 }
 
@@ -605,11 +624,13 @@ static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void*
   // a reader may pass k = v = NULL to reuse the prompt copy staged by the latest prefill call, if that call was for
   // the same cache and length (tiled path only)
   const bool reuse_stage = !k && !v;
+  // the staging area this call uses: a ring with readers has one of its own, which outlives other layers' calls
+  Stage& S = (sliding_cache && c.n_users > 1) ? c.own_stage : L->stage;
   if (reuse_stage) {
     if (writer || !L->tiled || L->prefill_simple) return MIXATTN_ERR_NULL;
-    if (L->stage_cache != ci || (int)L->stage_lens.size() != L->batch) return MIXATTN_ERR_ORDER;
+    if (S.cache != ci || (int)S.lens.size() != L->batch) return MIXATTN_ERR_ORDER;
     for (int b = 0; b < L->batch; ++b)
-      if (L->stage_lens[b] != len_of(b)) return MIXATTN_ERR_ORDER;
+      if (S.lens[b] != len_of(b)) return MIXATTN_ERR_ORDER;
   } else if (!k || !v) {
     return MIXATTN_ERR_NULL;
   }
@@ -626,7 +647,7 @@ static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void*
     max_old = std::max(max_old, n_old);
   }
   // Readers of a ring come after their writer's commit, which has overwritten keys the chunk's first rows need:
-  // past the first chunk they can only run from the staged copy.
+  // past the first chunk they can only run from the ring's staged copy of that chunk (k = v = NULL).
   if (chunked && sliding_cache && !writer && !reuse_stage) return MIXATTN_ERR_ORDER;
   if (chunked && sliding_cache && !writer && !L->tiled) return MIXATTN_ERR_ORDER;
   const bool simple = !L->tiled || L->prefill_simple != 0;  // scalar kernel on the caller's tensors
@@ -654,9 +675,9 @@ static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void*
     st.d_src_first = d_first; st.d_src_len = d_len;
   };
   auto remember_stage = [&]() {
-    L->stage_cache = ci;
-    L->stage_lens.resize(L->batch);
-    for (int b = 0; b < L->batch; ++b) L->stage_lens[b] = (int32_t)len_of(b);
+    S.cache = ci;
+    S.lens.resize(L->batch);
+    for (int b = 0; b < L->batch; ++b) S.lens[b] = (int32_t)len_of(b);
   };
 
   PrefillLaunch p;
@@ -724,12 +745,12 @@ static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void*
       if (e != MIXATTN_OK) return e;
     }
     if (!reuse_stage) {
-      int e = ensure_stage(L, (max_new + kBlockKeys - 1) / kBlockKeys);
+      int e = ensure_stage(L, S, (max_new + kBlockKeys - 1) / kBlockKeys);
       if (e != MIXATTN_OK) return e;
-      L->stage_cache = -1;
+      S.cache = -1;
       StoreLaunch st;
-      st.K = nullptr; st.V = L->stageV; st.v_as_f16 = 1;
-      st.d_base = L->d_stage_base; st.d_slots = L->d_stage_slots; st.window = 0;
+      st.K = nullptr; st.V = S.V; st.v_as_f16 = 1;
+      st.d_base = S.d_base; st.d_slots = S.d_slots; st.window = 0;
       set_source(st);
       if (chunked) {
         st.d_n_old = c.lens(); st.old_sub = 1;  // lengths already include the chunk
@@ -743,7 +764,7 @@ static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void*
     }
     p.Kt = c.K; p.k_base = c.d_base; p.k_slots = c.d_slots;
     p.k_pages = c.page_table();
-    p.Vt = L->stageV; p.v_base = L->d_stage_base; p.v_slots = L->d_stage_slots;
+    p.Vt = S.V; p.v_base = S.d_base; p.v_slots = S.d_slots;
     p.stage_window = 0;
     p.d_lens = chunked ? c.lens() : nullptr; p.old_sub = 1;
     HIP_TRY(launch_prefill_tiled(p, s));
@@ -755,12 +776,12 @@ static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void*
   const int W = c.window;
   if (!reuse_stage) {
     const int64_t span = std::min<int64_t>(max_old, W - 1) + seq_len;
-    int e = ensure_stage(L, (span + kBlockKeys - 1) / kBlockKeys);
+    int e = ensure_stage(L, S, (span + kBlockKeys - 1) / kBlockKeys);
     if (e != MIXATTN_OK) return e;
-    L->stage_cache = -1;
+    S.cache = -1;
     StoreLaunch st;
-    st.K = L->stageK; st.V = L->stageV; st.v_as_f16 = 1;
-    st.d_base = L->d_stage_base; st.d_slots = L->d_stage_slots; st.window = 0;
+    st.K = S.K; st.V = S.V; st.v_as_f16 = 1;
+    st.d_base = S.d_base; st.d_slots = S.d_slots; st.window = 0;
     st.stage_window = W;
     set_source(st);
     if (chunked) {  // writer (readers past the first chunk always reuse): lengths do not include the chunk yet
@@ -772,8 +793,8 @@ static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void*
     HIP_TRY(launch_store_tiled(st, s));
     remember_stage();
   }
-  p.Kt = L->stageK; p.k_base = L->d_stage_base; p.k_slots = L->d_stage_slots;
-  p.Vt = L->stageV; p.v_base = L->d_stage_base; p.v_slots = L->d_stage_slots;
+  p.Kt = S.K; p.k_base = S.d_base; p.k_slots = S.d_slots;
+  p.Vt = S.V; p.v_base = S.d_base; p.v_slots = S.d_slots;
   p.stage_window = W;
   p.d_lens = chunked ? c.lens() : nullptr;
   p.old_sub = writer ? 0 : 1;
@@ -823,6 +844,7 @@ int mixattn_load_kv(mixattn_layout* L, int layer, const void* k, const void* v, 
     run += seq_lens[b];
     max_len = std::max(max_len, seq_lens[b]);
   }
+  retire_stage(L, c);
   hipStream_t s = (hipStream_t)stream;
   if (c.paged) {
     std::vector<int64_t> want(seq_lens, seq_lens + L->batch);

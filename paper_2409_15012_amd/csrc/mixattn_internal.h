@@ -52,6 +52,18 @@ __device__ inline int64_t tiled_block_index(const int64_t* d_base, const int32_t
   return d_base[b] + (int64_t)h * (d_slots[b] >> 5) + blk;
 }
 
+// Prompt staging for prefill on the tiled path: tile-format copies that the MFMA kernel reads (V as fp16; for sliding
+// layers also K, positions max(0, n_old - (W-1)) .. n_new-1).  Grown on demand.
+struct Stage {
+  void* K = nullptr;
+  void* V = nullptr;
+  int64_t blocks = 0;          // blocks per (b, h) currently allocated
+  int cache = -1;              // cache whose chunk it holds (-1: none)
+  std::vector<int32_t> lens;   // that chunk's length per sequence
+  int64_t* d_base = nullptr;   // [batch] geometry tables of the area
+  int32_t* d_slots = nullptr;  // [batch]
+};
+
 struct Cache {
   int kind = 0;
   int window = 0;      // SLIDING only
@@ -83,6 +95,10 @@ struct Cache {
     if (paged) { t.ids = d_pages; t.max_pages = max_pages; t.shift = page_shift; }
     return t;
   }
+  // A ring with reader layers keeps the staged copy of its latest prompt chunk to itself, so that its readers can run
+  // at any later point of the layer loop (the ring itself no longer holds the keys the chunk's first rows need).
+  int n_users = 0;   // layers reading this cache, the writer included
+  Stage own_stage;
   // memo of the last split-K plan (it only changes when a sequence crosses a block boundary)
   int64_t plan_key = -1;
   int plan_max_blocks = -1;
@@ -111,14 +127,7 @@ struct mixattn_layout {
   std::vector<int32_t> capacity;  // [batch] for FULL caches
   int32_t* d_lens_all = nullptr;  // [n_caches][2][batch]
   mixattn::DecodeScratch scratch;
-  // prompt staging for prefill on the tiled path (grown on demand): V of every layer as fp16, K of sliding layers
-  void* stageK = nullptr;
-  void* stageV = nullptr;
-  int64_t stage_blocks = 0;  // blocks per (b, h) currently allocated
-  int stage_cache = -1;      // cache whose prompt the staging area holds (-1: none)
-  std::vector<int32_t> stage_lens;  // its chunk length per sequence
-  int64_t* d_stage_base = nullptr;   // [batch] geometry tables of the staging area
-  int32_t* d_stage_slots = nullptr;  // [batch]
+  mixattn::Stage stage;  // shared by full caches and by rings without readers
   int32_t* d_stage_lens = nullptr;  // [batch] device copy of seq_lens for load_kv / prefill commits
   int64_t* d_stage_src = nullptr;   // [batch] device: first packed token of each sequence
   int64_t* d_q_first = nullptr;     // [batch] device: first packed row of each sequence in a varlen prefill call

@@ -189,16 +189,18 @@ def test_bf16_prefill_then_decode_against_oracle(mx, S, W, Hq, Hkv, B, simple):
                       wl.randn(seed + 50 + li, (B, S, Hkv, d), torch.bfloat16, DEV))
         q = wl.randn(seed + 100 + li, (B, S, Hq, d), torch.bfloat16, DEV)
         k, v = kv[wr]
-        if wr != li and not simple and li == wr + 1:
-            out = lay.prefill(li, q, None, None)  # reader right after its writer: reuse the staged prompt
+        if wr != li and not simple:
+            # a reader reuses the prompt staged by its writer: the ring (layers 1, 2) keeps a copy of its own, the
+            # full cache's copy (layer 0) is still in the shared area because no layer since has used that
+            out = lay.prefill(li, q, None, None)
         else:
-            if wr != li and not simple:
-                with pytest.raises(mx.MixAttnError) as ei:  # another group's prompt is staged by now
-                    lay.prefill(li, q, None, None)
-                assert ei.value.status == -6
             out = lay.prefill(li, q, k, v)
         ref = ora.prefill(li, to_f64(q), to_f64(k) if wr == li else None, to_f64(v) if wr == li else None)
         assert_matches(out, ref, "bf16", "prefill layer %d" % li)
+    if not simple:
+        with pytest.raises(mx.MixAttnError) as ei:  # layer 4 (a ring without readers) has used the shared area since
+            lay.prefill(3, q, None, None)
+        assert ei.value.status == -6
     for li in (0, 1, 4):
         _check_cache(lay, ora, li, heads=[0])
     for t in range(2):
@@ -609,4 +611,50 @@ def test_peaked_flat_and_scaled_inputs(mx, qscale, vscale):
             out = lay.append_decode(li, k, v, q)
             max_abs, rel_l2 = errors(out, ora.decode(li, to_f64(q)))
             assert rel_l2 <= 1e-3 and max_abs <= 2e-3 * max(1.0, vscale), (t, li, max_abs, rel_l2)
+    lay.close()
+
+
+# --------------------------------------------------------------------------- ring readers far from their writer
+@pytest.mark.parametrize("W", [48, 200])
+def test_chunked_prefill_with_ring_readers_not_next_to_their_writer(mx, W):
+    """Two rings whose reader layers are interleaved with each other and with a full layer: past the first chunk a
+    reader runs from its ring's own staged copy of the chunk (k = v = None), however many other layers ran since."""
+    d, Hq, Hkv, B = 128, 8, 2, 3
+    # ring 1: layers 0 (writer), 2, 5;  ring 2: layers 1 (writer), 4;  full cache 3: layers 3 (writer), 6
+    layers = [(1, W, 1), (1, W, 2), (1, W, 1), (0, 0, 3), (1, W, 2), (1, W, 1), (0, 0, 3)]
+    chunks = [[70, 5, 33], [1, 130, 64], [40, 0, 97]]
+    total = [sum(c[b] for c in chunks) for b in range(B)]
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[n + 2 for n in total], kv_dtype="bf16", out_dtype="f32")
+    ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
+    for ci, lens in enumerate(chunks):
+        T = sum(lens)
+        kv = {}
+        for li in range(len(layers)):
+            wr = lay.writer_of(li)
+            if wr == li:
+                kv[li] = (wl.randn(9000 + 100 * ci + li, (T, Hkv, d), torch.bfloat16, DEV),
+                          wl.randn(9500 + 100 * ci + li, (T, Hkv, d), torch.bfloat16, DEV))
+            q = wl.randn(9900 + 100 * ci + li, (T, Hq, d), torch.bfloat16, DEV)
+            k, v = kv[wr]
+            if wr == li:
+                out = lay.prefill_varlen(li, q, k, v, lens)
+            elif layers[li][0] == wl.SLIDING:
+                out = lay.prefill_varlen(li, q, None, None, lens)     # from the ring's staged chunk
+            else:
+                out = lay.prefill_varlen(li, q, k, v, lens)           # a full cache holds everything itself
+            ref = ora.prefill_ragged(li, to_f64(q), to_f64(k) if wr == li else None, to_f64(v) if wr == li else None, lens)
+            assert_matches(out, ref, "bf16", "chunk %d layer %d" % (ci, li))
+    # a ring reader handed the chunk's tensors past the first chunk is still refused (the ring has lost keys it needs)
+    with pytest.raises(mx.MixAttnError) as ei:
+        lay.prefill_varlen(2, q, kv[0][0], kv[0][1], lens)
+    assert ei.value.status == -6
+    # an append retires the staged chunk: the reader's prefill without tensors has nothing to run from
+    k1 = wl.randn(1, (B, Hkv, d), torch.bfloat16, DEV)
+    lay.append_kv(0, k1, k1)
+    with pytest.raises(mx.MixAttnError) as ei:
+        lay.prefill_varlen(2, q, None, None, lens)
+    assert ei.value.status == -6
+    ora.append(0, to_f64(k1), to_f64(k1))
+    for li in (0, 1, 3):
+        _check_cache(lay, ora, li, heads=[0, Hkv - 1])
     lay.close()
