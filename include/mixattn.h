@@ -221,8 +221,13 @@ typedef enum {
                                       0 (default): separate combine launch, which measures faster */
   MIXATTN_PARAM_PREFILL_SIMPLE = 2, /* 1: force the scalar prefill kernel (testing) */
   MIXATTN_PARAM_PREFILL_WAVES = 3,  /* wavefronts per MFMA prefill workgroup: 4, 8, or 0 = by layer kind (8 full, 4 sliding) */
-  MIXATTN_PARAM_PREFILL_HEADS = 4   /* query heads of one KV head served by one MFMA prefill workgroup: 1, 2, 4, or
+  MIXATTN_PARAM_PREFILL_HEADS = 4,  /* query heads of one KV head served by one MFMA prefill workgroup: 1, 2, 4, or
                                        0 = as many as divide the group size */
+  MIXATTN_PARAM_BALANCED = 5        /* decode over full caches: cut the blocks of all (sequence, kv head) streams,
+                                       laid end to end, into equal runs, one per workgroup, instead of cutting
+                                       every sequence by itself.  1 (default): when the longest sequence exceeds
+                                       1.25 x the mean or the sequences have to be cut anyway; 0: never; 2: always.
+                                       Ignored when CHUNK_KEYS is set and for batches above 1024. */
 } mixattn_param;
 int mixattn_set_param(mixattn_layout* L, int param, int64_t value);
 int mixattn_get_param(const mixattn_layout* L, int param, int64_t* value);

@@ -19,6 +19,7 @@ _lib = None
 FULL, SLIDING = 0, 1
 F32, BF16 = 0, 1
 PARAM_CHUNK_KEYS, PARAM_FUSED_COMBINE, PARAM_PREFILL_SIMPLE, PARAM_PREFILL_WAVES, PARAM_PREFILL_HEADS = 0, 1, 2, 3, 4
+PARAM_BALANCED = 5
 
 EXPORTS = [
     "mixattn_validate_config", "mixattn_create_layout", "mixattn_create_layout_paged", "mixattn_destroy_layout",

@@ -57,6 +57,8 @@ struct TiledDecodeParams {
   // group launch (GROUP): n_group layers of one sharing group in one pass over the ring; layer i's q and out
   // start layer_rows * i rows after the first layer's (a row = one query head of one sequence)
   int n_group; int64_t layer_rows;
+  // balanced launch: sequences in the batch, blocks per workgroup
+  int batch; int share;
 };
 
 // device-scope coherent accesses (relaxed atomics): they go past the XCD-private L2
@@ -92,13 +94,16 @@ __device__ inline void merge_partials(const float* p_acc, const float* p_ml, int
 // GROUP (rings only): the 16 head columns carry the G query heads of up to 16 / G layers that read this ring, so one
 // pass over the ring serves the whole sharing group.  No column is left for the remainders: they go through a
 // second set of P x V products instead, which keeps the arithmetic of a column the same as in a one-layer launch.
-template <typename OutT, bool RING, bool FUSED, bool WINDOWED = false, bool GROUP = false>
-__global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(TiledDecodeParams a) {
-  static_assert(!(WINDOWED && (RING || FUSED)), "a windowed reader of a full cache never writes it");
-  static_assert(!GROUP || RING, "group launches serve ring caches");
+//
+// decode_piece is the work of one workgroup on blocks blk0 .. blk1-1 of (sequence b, kv head h): piece c of the
+// n_chunks_b pieces that (b, h) is cut into.  A workgroup may run it several times (balanced launches): the
+// function ends with every wavefront past its last read of the shared arrays.
+template <typename OutT, bool RING, bool FUSED, bool WINDOWED, bool GROUP, bool BALANCED>
+__device__ __attribute__((always_inline)) void decode_piece(const TiledDecodeParams& a, const int b, const int h,
+                                                            const int blk0, const int blk1, const int c,
+                                                            const int n_chunks_b) {
   constexpr int kCols = GROUP ? 16 : kMaxGroup;  // head columns that carry results
   constexpr int NW = kDecodeWaves;
-  const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int n_old = a.d_lens[b];
   int n = FUSED ? n_old + 1 : n_old;
   if (RING && n > a.window) n = a.window;
@@ -106,14 +111,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
   const int new_blk = new_slot >> 5, new_key = new_slot & 31;
   const int nb_total = (n + kBlockKeys - 1) / kBlockKeys;
   const int lo = (WINDOWED && n > a.attn_window) ? n - a.attn_window : 0;  // first position attended
-  const int fb = lo / kBlockKeys;                                           // first block read
-  const int nb_read = nb_total - fb;
-  // this sequence's blocks are cut into n_chunks_b chunks of equal length (+-1 block), so that workgroups of one
-  // sequence finish together and a sequence a little longer than a multiple of the target does not grow a stub
-  const int n_chunks_b = (nb_read + a.chunk_blocks - 1) / a.chunk_blocks;
-  if (c >= n_chunks_b) return;  // uniform for the workgroup
-  const int blk0 = fb + (int)(((int64_t)c * nb_read) / n_chunks_b);
-  const int blk1 = fb + (int)(((int64_t)(c + 1) * nb_read) / n_chunks_b);
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the block loop on scalar branches
@@ -358,7 +355,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
   __syncthreads();
 
   const bool direct = (a.n_chunks == 1);
-  const bool fused = !direct && a.fused_combine;
+  const bool fused = !BALANCED && !direct && a.fused_combine;
   // result row of head column hd: the layer's block of rows, then (sequence, query head)
   auto row_of = [&](int hd) -> int64_t {
     const int gl = GROUP ? hd / G : 0;
@@ -396,6 +393,10 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
       }
     }
   }
+  if constexpr (BALANCED) {
+    __syncthreads();  // the shared arrays are written again by this workgroup's next piece
+    return;
+  }
   if (!fused) return;
 
   // ---- fused combine: the workgroup that arrives last for this (sequence, kv head) merges all chunks.
@@ -430,6 +431,114 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
   }
 }
 
+template <typename OutT, bool RING, bool FUSED, bool WINDOWED = false, bool GROUP = false>
+__global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(TiledDecodeParams a) {
+  static_assert(!(WINDOWED && (RING || FUSED)), "a windowed reader of a full cache never writes it");
+  static_assert(!GROUP || RING, "group launches serve ring caches");
+  const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  int n = a.d_lens[b] + (FUSED ? 1 : 0);
+  if (RING && n > a.window) n = a.window;
+  const int nb_total = (n + kBlockKeys - 1) / kBlockKeys;
+  const int lo = (WINDOWED && n > a.attn_window) ? n - a.attn_window : 0;  // first position attended
+  const int fb = lo / kBlockKeys;                                           // first block read
+  const int nb_read = nb_total - fb;
+  // this sequence's blocks are cut into n_chunks_b chunks of equal length (+-1 block), so that workgroups of one
+  // sequence finish together and a sequence a little longer than a multiple of the target does not grow a stub
+  const int n_chunks_b = (nb_read + a.chunk_blocks - 1) / a.chunk_blocks;
+  if (c >= n_chunks_b) return;  // uniform for the workgroup
+  const int blk0 = fb + (int)(((int64_t)c * nb_read) / n_chunks_b);
+  const int blk1 = fb + (int)(((int64_t)(c + 1) * nb_read) / n_chunks_b);
+  decode_piece<OutT, RING, FUSED, WINDOWED, GROUP, false>(a, b, h, blk0, blk1, c, n_chunks_b);
+}
+
+// Balanced launch for full caches whose sequences differ in length.  The blocks of all (sequence, kv head) streams,
+// laid end to end in (b, h) order, are cut into gridDim.x runs of a.share blocks: every workgroup streams the same
+// number of blocks whatever the lengths are, and a stream is cut only where a run ends.  Piece c of a stream is the
+// part inside the c-th run that touches it; the combine launch that follows merges the pieces.
+//   s_first[b] = blocks of one kv head held by sequences 0 .. b-1 (built by the first wavefront, a scan over the batch)
+constexpr int kMaxBalancedBatch = 1024;
+
+template <bool FUSED>
+__device__ inline void scan_block_counts(const int32_t* d_lens, int batch, int* s_first) {
+  const int lane = threadIdx.x & 63;
+  if (threadIdx.x < 64) {
+    int run = 0;
+    for (int b0 = 0; b0 < batch; b0 += 64) {
+      const int bb = b0 + lane;
+      int inc = bb < batch ? (d_lens[bb] + (FUSED ? 1 : 0) + kBlockKeys - 1) / kBlockKeys : 0;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(inc, o);
+        if (lane >= o) inc += t;
+      }
+      if (bb < batch) s_first[bb + 1] = run + inc;
+      run += __shfl(inc, 63);
+    }
+    if (lane == 0) s_first[0] = 0;
+  }
+  __syncthreads();
+}
+
+// stream (b, h) starts at block s_first[b] * Hkv + h * nb_b of the end-to-end order; pieces of a stream starting at
+// block gs with nb blocks, for runs of `share` blocks
+__device__ inline int balanced_first_run(int64_t gs, int share) { return (int)(gs / share); }
+__device__ inline int balanced_pieces(int64_t gs, int nb, int share) {
+  return (int)((gs + nb - 1) / share) - (int)(gs / share) + 1;
+}
+
+template <typename OutT, bool FUSED>
+__global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_balanced_kernel(TiledDecodeParams a) {
+  __shared__ int s_first[kMaxBalancedBatch + 1];
+  scan_block_counts<FUSED>(a.d_lens, a.batch, s_first);
+  const int64_t total = (int64_t)s_first[a.batch] * a.Hkv;
+  const int64_t g0 = (int64_t)blockIdx.x * a.share;
+  const int64_t g1 = min(total, g0 + a.share);
+  // sequence that holds block g0: the last b with s_first[b] * Hkv <= g0 (uniform binary search)
+  int b = 0;
+  {
+    int hi = a.batch;  // invariant: s_first[b] * Hkv <= g0 < s_first[hi] * Hkv (when g0 < total)
+    while (hi - b > 1) {
+      const int mid = (b + hi) >> 1;
+      if ((int64_t)s_first[mid] * a.Hkv <= g0) b = mid; else hi = mid;
+    }
+  }
+  for (int64_t g = g0; g < g1;) {
+    while ((int64_t)s_first[b + 1] * a.Hkv <= g) ++b;  // g < total, so b stays below the batch size
+    const int nb = s_first[b + 1] - s_first[b];
+    const int off = (int)(g - (int64_t)s_first[b] * a.Hkv);
+    const int h = off / nb;
+    const int blk0 = off - h * nb;
+    const int blk1 = (int)min((int64_t)nb, blk0 + (g1 - g));
+    const int64_t gs = g - blk0;
+    decode_piece<OutT, false, FUSED, false, false, true>(a, b, h, blk0, blk1,
+                                                          blockIdx.x - balanced_first_run(gs, a.share),
+                                                          balanced_pieces(gs, nb, a.share));
+    g += blk1 - blk0;
+  }
+}
+
+template <typename OutT>
+__global__ __launch_bounds__(kTiledDim) void combine_balanced_kernel(TiledDecodeParams a) {
+  const int hq = blockIdx.x, b = blockIdx.y;
+  const int extra = a.k_new ? 1 : 0;  // the fused launch before this one read the old length array
+  // blocks of one kv head held by the sequences before b
+  __shared__ int s_part[kTiledDim / 64];
+  int before = 0;
+  for (int bb = threadIdx.x; bb < b; bb += kTiledDim) before += (a.d_lens[bb] + extra + kBlockKeys - 1) / kBlockKeys;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) before += __shfl_xor(before, o);
+  if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = before;
+  __syncthreads();
+  before = 0;
+#pragma unroll
+  for (int w = 0; w < kTiledDim / 64; ++w) before += s_part[w];
+  const int nb = (a.d_lens[b] + extra + kBlockKeys - 1) / kBlockKeys;
+  const int64_t gs = (int64_t)before * a.Hkv + (int64_t)(hq / a.G) * nb;
+  const int64_t row = (int64_t)b * a.Hq + hq;
+  merge_partials<OutT>(a.p_acc + row * kMaxChunks * kTiledDim, a.p_ml + row * kMaxChunks * 2,
+                       balanced_pieces(gs, nb, a.share), threadIdx.x, (OutT*)a.out + row * kTiledDim);
+}
+
 template <typename OutT>
 __global__ __launch_bounds__(kTiledDim) void combine_kernel(TiledDecodeParams a) {
   const int hq = blockIdx.x, b = blockIdx.y;
@@ -459,8 +568,25 @@ hipError_t launch_decode_tiled(const DecodeLaunch& L, hipStream_t s) {
   p.k_new = (const uint16_t*)L.k_new; p.v_new = (const uint16_t*)L.v_new;
   p.Kw = (uint16_t*)L.K; p.Vw = (uint16_t*)L.V; p.d_lens_out = L.d_lens_out;
   p.n_group = L.n_group; p.layer_rows = (int64_t)L.batch * L.Hq;
-  const dim3 grid(L.n_chunks, L.Hkv, L.batch);
+  p.batch = L.batch; p.share = L.balanced_share;
   const bool f32 = L.out_dtype == MIXATTN_F32, ring = L.window > 0, fused = L.k_new != nullptr;
+  if (L.balanced_share > 0) {
+    if (ring || L.attn_window > 0 || L.n_group > 0 || L.batch > kMaxBalancedBatch || L.balanced_runs < 1)
+      return hipErrorInvalidValue;
+    p.n_chunks = 2;  // pieces always go through the combine launch
+    const dim3 bgrid(L.balanced_runs), bblock(kDecodeWaves * 64);
+    if (f32 && fused) hipLaunchKernelGGL((decode_balanced_kernel<float, true>), bgrid, bblock, 0, s, p);
+    else if (f32) hipLaunchKernelGGL((decode_balanced_kernel<float, false>), bgrid, bblock, 0, s, p);
+    else if (fused) hipLaunchKernelGGL((decode_balanced_kernel<uint16_t, true>), bgrid, bblock, 0, s, p);
+    else hipLaunchKernelGGL((decode_balanced_kernel<uint16_t, false>), bgrid, bblock, 0, s, p);
+    hipError_t be = hipGetLastError();
+    if (be != hipSuccess) return be;
+    const dim3 cgrid(L.Hq, L.batch), cblock(kTiledDim);
+    if (f32) hipLaunchKernelGGL(combine_balanced_kernel<float>, cgrid, cblock, 0, s, p);
+    else hipLaunchKernelGGL(combine_balanced_kernel<uint16_t>, cgrid, cblock, 0, s, p);
+    return hipGetLastError();
+  }
+  const dim3 grid(L.n_chunks, L.Hkv, L.batch);
 #define MIXATTN_LAUNCH_DECODE(OUT, RING, FUSED) \
   hipLaunchKernelGGL((decode_tiled_kernel<OUT, RING, FUSED>), grid, dim3(kDecodeWaves * 64), 0, s, p)
   if (L.n_group > 0) {  // several layers of one ring's sharing group in one launch

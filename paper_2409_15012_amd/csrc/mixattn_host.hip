@@ -523,6 +523,32 @@ static int launch_decode(mixattn_layout* L, Cache& c, int attn_window, const voi
   a.max_blocks = max_blocks;
   a.chunk_blocks = chunk_blocks;
   a.n_chunks = (max_blocks + chunk_blocks - 1) / chunk_blocks;
+  // Full caches: when the sequences differ in length, or have to be cut anyway, the blocks of all (sequence, kv
+  // head) streams are cut into equal runs, one per workgroup, instead of cutting every sequence by itself (with one
+  // workgroup per sequence and head the long sequences finish alone, at the pace of a few workgroups; per-sequence
+  // chunks of one target length come in sizes up to 2:1 and in numbers that do not fill the last round).
+  // Measured: ragged batch of 64, 5.68 -> 6.63 TB/s; one sequence of 131072, 4.68 -> 5.23 TB/s; a uniform batch
+  // that needs no cut stays on the unsplit launch (6.72 against 6.64 TB/s).
+  if (c.kind == MIXATTN_FULL && attn_window == 0 && n_group == 0 && L->chunk_keys == 0 && L->balanced != 0 &&
+      L->batch <= 1024) {
+    int64_t sum_nb = 0;
+    int max_nb = 0;
+    for (int b = 0; b < L->batch; ++b) {
+      const int nb = (int)((c.len[b] + extra + kBlockKeys - 1) / kBlockKeys);
+      sum_nb += nb;
+      max_nb = std::max(max_nb, nb);
+    }
+    const bool ragged = (int64_t)max_nb * L->batch * 4 > sum_nb * 5;  // longest sequence > 1.25 x the mean
+    if (ragged || a.n_chunks > 1 || L->balanced == 2) {
+      const int64_t total = sum_nb * L->Hkv;
+      const int64_t slots = 2 * (int64_t)L->n_cus;
+      int64_t share = (total + slots - 1) / slots;
+      share = std::max<int64_t>(share, (max_nb + (kMaxChunks - 2) - 1) / (kMaxChunks - 2));  // pieces per stream <= kMaxChunks
+      share = std::max<int64_t>(share, kDecodeMinChunkBlocks);
+      a.balanced_share = (int)share;
+      a.balanced_runs = (int)((total + share - 1) / share);
+    }
+  }
   HIP_TRY(launch_decode_tiled(a, stream));
   return MIXATTN_OK;
 }
@@ -978,6 +1004,10 @@ int mixattn_set_param(mixattn_layout* L, int param, int64_t value) {
       if (value != 0 && value != 1 && value != 2 && value != 4) return MIXATTN_ERR_PARAM;
       L->prefill_heads = value;
       return MIXATTN_OK;
+    case MIXATTN_PARAM_BALANCED:
+      if (value < 0 || value > 2) return MIXATTN_ERR_PARAM;
+      L->balanced = value;
+      return MIXATTN_OK;
     default: return MIXATTN_ERR_PARAM;
   }
 }
@@ -990,6 +1020,7 @@ int mixattn_get_param(const mixattn_layout* L, int param, int64_t* value) {
     case MIXATTN_PARAM_PREFILL_SIMPLE: *value = L->prefill_simple; return MIXATTN_OK;
     case MIXATTN_PARAM_PREFILL_WAVES: *value = L->prefill_waves; return MIXATTN_OK;
     case MIXATTN_PARAM_PREFILL_HEADS: *value = L->prefill_heads; return MIXATTN_OK;
+    case MIXATTN_PARAM_BALANCED: *value = L->balanced; return MIXATTN_OK;
     default: return MIXATTN_ERR_PARAM;
   }
 }

@@ -139,6 +139,7 @@ struct mixattn_layout {
   int64_t prefill_simple = 0;
   int64_t prefill_waves = 0; // 0 = automatic
   int64_t prefill_heads = 0; // 0 = automatic
+  int64_t balanced = 1;      // 0 never, 1 when the batch is ragged, 2 always
   int group_layers = 1;      // most layers one group launch may serve (sizes the split-K scratch)
   int device = 0;
   int n_cus = 256;
@@ -166,6 +167,8 @@ struct DecodeLaunch {
   const void* k_new = nullptr; const void* v_new = nullptr; int32_t* d_lens_out = nullptr;
   // > 0 (tiled path, rings only): q and out hold n_group layers, [n_group][batch][Hq][D]; scratch rows likewise
   int n_group = 0;
+  // > 0 (tiled path, full caches): balanced launch, `balanced_runs` workgroups of `balanced_share` blocks each
+  int balanced_share = 0, balanced_runs = 0;
 };
 hipError_t launch_decode_tiled(const DecodeLaunch& a, hipStream_t s);
 hipError_t launch_decode_rowmajor(const DecodeLaunch& a, hipStream_t s);

@@ -658,3 +658,51 @@ def test_chunked_prefill_with_ring_readers_not_next_to_their_writer(mx, W):
     for li in (0, 1, 3):
         _check_cache(lay, ora, li, heads=[0, Hkv - 1])
     lay.close()
+
+
+# --------------------------------------------------------------------------- balanced launches over ragged batches
+@pytest.mark.parametrize("B,Hq,Hkv,max_len,paged", [
+    (7, 8, 2, 1000, 0),
+    (70, 4, 1, 600, 0),        # more sequences than one wavefront scans at a time
+    (5, 8, 2, 9000, 256),      # paged full cache, long and short sequences together
+    (1, 8, 2, 5000, 0),        # one sequence: every stream cut into many pieces
+    (3, 8, 8, 64, 0),          # fewer blocks than workgroups
+])
+@pytest.mark.parametrize("balanced", [0, 1, 2])
+def test_balanced_decode_over_ragged_batches(mx, B, Hq, Hkv, max_len, paged, balanced):
+    """Full-cache decode with the blocks of all sequences cut into equal runs (balanced = 2: always, 1: when the
+    batch is ragged, 0: per-sequence chunks only): same results against the oracle, fused append included."""
+    d = 128
+    rng = np.random.default_rng(B * 1000 + max_len)
+    lens = [int(x) for x in rng.integers(1, max_len + 1, size=B)]
+    lens[0] = max_len
+    layers = [(0, 0, 0), (0, 0, 0), (1, 64, 0)]   # writer, full reader, windowed reader of the full cache
+    steps = 3
+    cap = [n + steps for n in lens]
+    kw = {}
+    if paged:
+        kw = dict(page_tokens=paged, pool_tokens=sum((c + paged - 1) // paged for c in cap) * paged)
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=cap, kv_dtype="bf16", out_dtype="f32", **kw)
+    lay.set_param(mx.PARAM_BALANCED, balanced)
+    ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
+    k = wl.randn(4100, (sum(lens), Hkv, d), torch.bfloat16, DEV)
+    v = wl.randn(4101, (sum(lens), Hkv, d), torch.bfloat16, DEV)
+    lay.load_kv(0, k, v, lens)
+    ora.load(0, to_f64(k), to_f64(v), lens)
+    for t in range(steps):
+        k = wl.randn(4200 + t, (B, Hkv, d), torch.bfloat16, DEV)
+        v = wl.randn(4300 + t, (B, Hkv, d), torch.bfloat16, DEV)
+        ora.append(0, to_f64(k), to_f64(v))
+        for li in range(len(layers)):
+            q = wl.randn(4400 + 10 * t + li, (B, Hq, d), torch.bfloat16, DEV)
+            if li == 0 and t != 1:
+                out = lay.append_decode(0, k, v, q)
+            else:
+                if li == 0:
+                    lay.append_kv(0, k, v)
+                out = lay.decode(li, q)
+            assert_matches(out, ora.decode(li, to_f64(q)), "bf16", "step %d layer %d" % (t, li))
+            if li == 1:
+                assert torch.equal(out, lay.decode(li, q))  # same launch again: bit-identical
+    _check_cache(lay, ora, 0, bs=[0, B - 1], heads=[Hkv - 1])
+    lay.close()
