@@ -16,7 +16,8 @@
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every
  *    call that takes a stream only enqueues work on it; calls on one layout must
  *    be issued on one stream (or be ordered by the caller), in layer order.
- *  - One layout is used by one host thread at a time.
+ *  - One layout is used by one host thread at a time, with the device that was current when it was created
+ *    still current.
  *  - The layout owns its caches and scratch; they are allocated in
  *    mixattn_create_layout and freed in mixattn_destroy_layout.
  *  - Sequence lengths live on the device and are mirrored on the host without any
@@ -58,7 +59,7 @@ typedef enum {
   MIXATTN_ERR_NULL = -1,       /* a required pointer is NULL */
   MIXATTN_ERR_LAYOUT = -2,     /* invalid descriptor: bad kind, window < 1, a reader that is neither like its
                                   writer nor a sliding reader of a full cache, heads not divisible, unsupported
-                                  head_dim or dtype, batch < 1 */
+                                  head_dim or dtype, batch < 1, batch or n_q_heads above 65535 */
   MIXATTN_ERR_LAYER = -3,      /* layer / cache / sequence / head / slot index out of range */
   MIXATTN_ERR_NOT_WRITER = -4, /* append, load or k/v commit on a layer that only reads a shared cache */
   MIXATTN_ERR_CAPACITY = -5,   /* a full cache would exceed capacity[b] */

@@ -111,6 +111,7 @@ int mixattn_validate_config(const mixattn_config* cfg) {
   if (!cfg || !cfg->layers) return MIXATTN_ERR_NULL;
   if (cfg->n_layers < 1 || cfg->batch < 1 || cfg->n_q_heads < 1 || cfg->n_kv_heads < 1) return MIXATTN_ERR_LAYOUT;
   if (cfg->n_q_heads % cfg->n_kv_heads != 0) return MIXATTN_ERR_LAYOUT;
+  if (cfg->batch > 65535 || cfg->n_q_heads > 65535) return MIXATTN_ERR_LAYOUT;  // sequences and heads index grid dimensions
   if (cfg->kv_dtype != MIXATTN_F32 && cfg->kv_dtype != MIXATTN_BF16) return MIXATTN_ERR_LAYOUT;
   if (cfg->out_dtype != MIXATTN_F32 && cfg->out_dtype != MIXATTN_BF16) return MIXATTN_ERR_LAYOUT;
   if (cfg->head_dim < 1 || cfg->head_dim > kMaxHeadDim) return MIXATTN_ERR_LAYOUT;
@@ -404,12 +405,6 @@ int mixattn_append_kv(mixattn_layout* L, int layer, const void* k, const void* v
   return MIXATTN_OK;
 }
 
-// Split-K plan for the tiled decode kernel: the target chunk length in blocks.  A sequence of nb blocks is cut
-// into ceil(nb / target) equal chunks, one workgroup each.  Two effects bound a launch (figures measured on
-// MI355X with this kernel): the HBM stream, about 7.0 TB/s once a few hundred workgroups are resident, and the
-// rate of one workgroup, whose four wavefronts keep 128 KiB in flight and so advance by one 16 KiB block in
-// about 0.6 us under load.  Cutting sequences shortens the second bound but costs a combine launch (about 5 us);
-// with two workgroups resident per CU, chunks run in rounds of 2 * CUs.
 // tokens a decode streams for a sequence of `len` tokens: all of a full cache, the ring's content, or the window
 static inline int64_t tokens_read(const Cache& c, int64_t len, int attn_window) {
   if (c.window > 0) return std::min<int64_t>(len, c.window);
@@ -424,6 +419,12 @@ static inline int layer_attn_window(const mixattn_layout* L, int layer) {
   return (c.kind == MIXATTN_FULL && L->layers[layer].kind == MIXATTN_SLIDING) ? L->layers[layer].window : 0;
 }
 
+// Split-K plan for the tiled decode kernel: the target chunk length in blocks.  A sequence of nb blocks is cut
+// into ceil(nb / target) equal chunks, one workgroup each.  Two effects bound a launch (figures measured on
+// MI355X with this kernel): the HBM stream, about 7.0 TB/s once a few hundred workgroups are resident, and the
+// rate of one workgroup, whose four wavefronts keep 128 KiB in flight and advance by one 16 KiB block in about
+// 0.25 us.  Cutting sequences shortens the second bound but costs a combine launch (about 5 us); with two
+// workgroups resident per CU, chunks run in rounds of 2 * CUs.
 static int plan_chunk_blocks(const mixattn_layout* L, Cache& c, int max_blocks, int extra, int attn_window) {
   const double slots = 2.0 * L->n_cus;
   const double us_per_block_bw = 2.0 * kBlockElems * 2 / 7.0e6;  // 16 KiB at 7.0 TB/s

@@ -54,6 +54,8 @@ def test_validate_config_accepts_the_workloads():
     ([(0, 0, 0)], {"capacity": None}, -1),             # full layer needs capacities
     ([(0, 0, 0)], {"capacity": [0, 5]}, -2),
     ([(0, 0, 0)], {"batch": 0, "capacity": []}, -2),
+    ([(1, 8, 0)], {"batch": 65536, "capacity": None}, -2),                    # a sequence indexes a grid dimension
+    ([(1, 8, 0)], {"n_q_heads": 65536, "n_kv_heads": 65536, "capacity": None}, -2),
     ([], {}, -2),
 ])
 def test_validate_config_rejects(layers, kw, status):
