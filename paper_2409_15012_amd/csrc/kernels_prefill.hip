@@ -162,10 +162,31 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
     for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
   float m = -INFINITY, lsum = 0.f;  // m in raw score units
 
+  // Where block kb of this (sequence, kv head) sits in the K buffer.  Contiguous: one base, read once.  Paged: the
+  // page ids of a tile's two blocks are looked up one tile ahead of their use (struct TilePages), because a wait
+  // for such a lookup also waits for every direct load issued before it.
+  const bool k_paged = a.k_pages.ids != nullptr;
+  const int64_t k_first = k_paged ? 0 : a.k_base[b] + (int64_t)h * (a.k_slots[b] >> 5);
+  const int32_t* k_ids = k_paged ? a.k_pages.ids + (int64_t)b * a.k_pages.max_pages : nullptr;
+  const int k_shift = a.k_pages.shift, k_mask = (1 << a.k_pages.shift) - 1;
+  struct TilePages { int pg[2]; };
+  auto pages_of = [&](int jt) {
+    TilePages t;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int kb = jt * 2 + j;
+      t.pg[j] = (k_paged && kb < nblk_valid) ? k_ids[kb >> k_shift] : 0;
+    }
+    return t;
+  };
+  auto k_block = [&](int kb, int pg) -> int64_t {
+    return k_paged ? ((((int64_t)pg * a.Hkv + h) << k_shift) + (kb & k_mask)) : k_first + kb;
+  };
+
   // Tile jt -> stage buf.  A tile is 1024 16-byte pieces of K and of V (512 per block); piece p = T*i + tid, with
   // T threads, lands at LDS byte 16*p, which is what a direct load does when the wave-uniform LDS base is that of
   // the wave's first lane.
-  auto issue = [&](int jt, int buf) {
+  auto issue = [&](int jt, int buf, const TilePages& tp) {
     constexpr int T = NW * 64;
 #pragma unroll
     for (int i = 0; i < 1024 / T; ++i) {
@@ -174,7 +195,7 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
       uint16_t* lk = sK(buf) + (T * i + wave * 64) * 8;
       uint16_t* lv = sV(buf) + (T * i + wave * 64) * 8;
       if (kb < nblk_valid) {
-        const int64_t k_at = tiled_block_index(a.k_base, a.k_slots, a.k_pages, a.Hkv, b, h, kb);
+        const int64_t k_at = k_block(kb, tp.pg[(T * i) / 512]);
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Kt + k_at * 512 + in_block),
                                          (__attribute__((address_space(3))) void*)lk, 16, 0, 0);
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Vg + (int64_t)kb * 512 + in_block),
@@ -187,7 +208,8 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
   };
 
   const int key_row = pf_key_of_row(col);  // key (within a block) this lane feeds as MFMA row `col`
-  issue(jt_lo, 0);
+  issue(jt_lo, 0, pages_of(jt_lo));
+  TilePages next_pages = pages_of(jt_lo + 1);
   if constexpr (kStageQ) {
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the query rows (and the first tile) of this wavefront landed
     const uint16_t* slice = smem + 4 * kBlockElems + wave * (32 * kTiledDim) + col * kTiledDim + hh * 8;
@@ -199,7 +221,10 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
     const int buf = (jt - jt_lo) & 1;
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's direct loads of tile jt have landed
     __syncthreads();                     // ... and everybody's; everybody is also done reading the other stage
-    if (jt < jt_hi) issue(jt + 1, buf ^ 1);
+    if (jt < jt_hi) {
+      issue(jt + 1, buf ^ 1, next_pages);
+      next_pages = pages_of(jt + 2);  // arrives during this tile's arithmetic
+    }
 
     const int k0 = jt * kPfKeys;
     // whole tile masked for every row of this wavefront?
