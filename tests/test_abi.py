@@ -100,3 +100,15 @@ def test_workload_layouts_have_the_stated_shape():
     specs = [mo.LayerSpec(*t) for t in w2.layers]
     assert mo.step_read_tokens(specs, w2.seq_lens) * mo.kv_bytes_per_token(8, 128, 2) == 11542724608
     assert mo.resident_kv_tokens(specs, w2.seq_lens) * 4096 == int(8.75 * 2 ** 30)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2
+    assert "one GPU only" in r.stderr
+    assert r.stdout.strip() == ""
