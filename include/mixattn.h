@@ -120,8 +120,12 @@ int mixattn_destroy_layout(mixattn_layout* L);
 /* Empties every cache (lengths to zero; cache bytes are left as they are and never read again before being
    overwritten).  Enqueued on `stream`. */
 int mixattn_reset(mixattn_layout* L, void* stream);
-/* Empties sequence b in every cache (its slot of the batch can take a new request; a paged layout returns its pages
-   to the pools).  Enqueued on `stream`.  Errors: LAYER (b out of range). */
+/* Sequence b gives up its slot of the batch: every cache forgets it (a paged layout takes its pages back) and the
+   slot is idle until a new request starts in it with a prompt chunk (mixattn_prefill, mixattn_prefill_varlen with
+   seq_lens[b] > 0) or a bulk load.  While idle, mixattn_append_kv / mixattn_append_decode ignore its row of k, v
+   and store nothing for it, every decode call writes zeros to its output rows, mixattn_seq_len reports 0, and the
+   other sequences are unaffected.  (A sequence that has simply never been given a token is empty, not idle:
+   appends start it, decode on it is ORDER.)  Enqueued on `stream`.  Errors: LAYER (b out of range). */
 int mixattn_release_sequence(mixattn_layout* L, int b, void* stream);
 
 /* Appends one token per sequence to the cache `layer` writes (Section 3: a sliding cache keeps the past

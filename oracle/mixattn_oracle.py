@@ -149,6 +149,8 @@ class OracleStack:
         for key in keys:
             self._K[key] = [np.zeros((0, self.Hkv, self.d)) for _ in range(batch)]
             self._V[key] = [np.zeros((0, self.Hkv, self.d)) for _ in range(batch)]
+        # (store key, b) pairs of released sequences: idle until a prompt chunk or a bulk load gives them tokens
+        self._idle = set()
 
     # ---------------------------------------------------------------- helpers
     def _store_key(self, layer: int):
@@ -159,6 +161,10 @@ class OracleStack:
 
     def seq_len(self, layer: int, b: int) -> int:
         return self._K[self._store_key(layer)][b].shape[0]
+
+    def is_idle(self, layer: int, b: int) -> bool:
+        """Released and not yet given a new prompt, in the cache `layer` reads."""
+        return (self._store_key(layer), b) in self._idle
 
     def history(self, layer: int, b: int) -> Tuple[np.ndarray, np.ndarray]:
         """(K, V) [n_b, Hkv, d] in absolute-position order for the cache `layer` reads."""
@@ -185,6 +191,8 @@ class OracleStack:
         v = np.asarray(v, dtype=np.float64).reshape(self.B, 1, self.Hkv, self.d)
         key = self._store_key(layer)
         for b in range(self.B):
+            if (key, b) in self._idle:
+                continue  # an idle slot of the batch takes no decode-step token: its row of k, v is ignored
             self._K[key][b] = np.concatenate([self._K[key][b], k[b]], axis=0)
             self._V[key][b] = np.concatenate([self._V[key][b], v[b]], axis=0)
 
@@ -199,17 +207,21 @@ class OracleStack:
         off = 0
         for b in range(self.B):
             n = int(seq_lens[b])
+            if n > 0:
+                self._idle.discard((key, b))
             self._K[key][b] = np.concatenate([self._K[key][b], k_packed[off:off + n]], axis=0)
             self._V[key][b] = np.concatenate([self._V[key][b], v_packed[off:off + n]], axis=0)
             off += n
 
     def release_sequence(self, b: int):
-        """Sequence b starts over in every cache (its slot of the batch takes a new request)."""
+        """Sequence b gives up its slot of the batch: every cache forgets it and it is idle (appends pass over it,
+        decode returns zeros for it) until a prompt chunk or a bulk load starts a new request in the slot."""
         if not 0 <= b < self.B:
             raise ValueError("no such sequence")
         for key in self._K:
             self._K[key][b] = np.zeros((0, self.Hkv, self.d))
             self._V[key][b] = np.zeros((0, self.Hkv, self.d))
+            self._idle.add((key, b))
 
     def decode(self, layer: int, q: np.ndarray, rows: Optional[Sequence[Tuple[int, int]]] = None) -> np.ndarray:
         """q [B, Hq, d] -> out [B, Hq, d]; the query of sequence b sits at position n_b - 1
@@ -221,6 +233,9 @@ class OracleStack:
         out = np.full((self.B, self.Hq, self.d), np.nan)
         todo = rows if rows is not None else [(b, j) for b in range(self.B) for j in range(self.Hq)]
         for (b, j) in todo:
+            if self.is_idle(layer, b):
+                out[b, j] = 0.0
+                continue
             K, V = self.history(layer, b)
             n = K.shape[0]
             if n < 1:
@@ -253,6 +268,7 @@ class OracleStack:
             v = np.asarray(v, dtype=np.float64).reshape(B, S, self.Hkv, self.d)
             key = self._store_key(layer)
             for b in range(B):
+                self._idle.discard((key, b))
                 self._K[key][b] = np.concatenate([self._K[key][b], k[b]], axis=0)
                 self._V[key][b] = np.concatenate([self._V[key][b], v[b]], axis=0)
         else:
@@ -286,6 +302,8 @@ class OracleStack:
             start = [self.seq_len(layer, b) for b in range(self.B)]
             key = self._store_key(layer)
             for b in range(self.B):
+                if lens[b] > 0:
+                    self._idle.discard((key, b))
                 self._K[key][b] = np.concatenate([self._K[key][b], k[first[b]:first[b + 1]]], axis=0)
                 self._V[key][b] = np.concatenate([self._V[key][b], v[first[b]:first[b + 1]]], axis=0)
         else:

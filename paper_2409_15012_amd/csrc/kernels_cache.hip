@@ -80,6 +80,7 @@ hipError_t launch_scatter_i32(int32_t* table, const int64_t* index, const int32_
 __global__ __launch_bounds__(256) void append_tiled_kernel(AppendLaunch a) {
   const int b = blockIdx.x;
   const int n = a.d_lens[b];
+  if (n < 0) return;  // idle sequence (released, no new prompt yet): its row of k, v is ignored
   const int slot = a.window > 0 ? n % a.window : n;
   if (slot >= a.d_slots[b]) return;  // host checks capacity first; never taken for a consistent layout
   const int blk = slot >> 5, key = slot & 31;
@@ -108,6 +109,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void append_rowmajor_kernel(AppendLaunch a) {
   const int b = blockIdx.x;
   const int n = a.d_lens[b];
+  if (n < 0) return;  // idle sequence
   const int slot = a.window > 0 ? n % a.window : n;
   const int slots = a.d_slots[b];
   if (slot >= slots) return;
@@ -183,8 +185,14 @@ __device__ inline SlotSource slot_source(const StoreLaunch& a, int s, int n_old,
 
 __device__ inline void store_lengths(const StoreLaunch& a, int b, int& n_old, int& n_new, int& off) {
   const int add = a.d_src_len ? a.d_src_len[b] : a.uniform_len;
-  n_old = a.d_n_old ? a.d_n_old[b] - (a.old_sub ? add : 0) : 0;
-  n_new = n_old + add;
+  const int held = a.d_n_old ? a.d_n_old[b] : 0;
+  if (held < 0) {  // idle sequence (length -1): new tokens start it at position 0, none leave it idle
+    n_old = add > 0 ? 0 : -1;
+    n_new = add > 0 ? add : -1;
+  } else {
+    n_old = held - (a.old_sub ? add : 0);
+    n_new = n_old + add;
+  }
   off = (a.stage_window > 0 && n_old > a.stage_window - 1) ? n_old - (a.stage_window - 1) : 0;
 }
 

@@ -431,11 +431,28 @@ __device__ __attribute__((always_inline)) void decode_piece(const TiledDecodePar
   }
 }
 
+// output rows of an idle sequence (released, no new prompt yet): zeros for the G query heads of kv head h, in
+// each of the `layers` layers of a group launch
+template <typename OutT>
+__device__ inline void zero_rows(const TiledDecodeParams& a, int b, int h, int layers) {
+  for (int idx = threadIdx.x; idx < layers * a.G * kTiledDim; idx += blockDim.x) {
+    const int hd = idx >> 7, d = idx & 127;
+    const int gl = hd / a.G;
+    const int64_t row = gl * a.layer_rows + (int64_t)b * a.Hq + (int64_t)h * a.G + (hd - gl * a.G);
+    store_out<OutT>((OutT*)a.out + row * kTiledDim + d, 0.f);
+  }
+}
+
 template <typename OutT, bool RING, bool FUSED, bool WINDOWED = false, bool GROUP = false>
 __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(TiledDecodeParams a) {
   static_assert(!(WINDOWED && (RING || FUSED)), "a windowed reader of a full cache never writes it");
   static_assert(!GROUP || RING, "group launches serve ring caches");
   const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if (a.d_lens[b] < 0) {  // idle sequence: zero rows, stays idle
+    if (c == 0) zero_rows<OutT>(a, b, h, GROUP ? a.n_group : 1);
+    if (FUSED && c == 0 && h == 0 && threadIdx.x == 0) a.d_lens_out[b] = -1;
+    return;
+  }
   int n = a.d_lens[b] + (FUSED ? 1 : 0);
   if (RING && n > a.window) n = a.window;
   const int nb_total = (n + kBlockKeys - 1) / kBlockKeys;
@@ -465,7 +482,8 @@ __device__ inline void scan_block_counts(const int32_t* d_lens, int batch, int* 
     int run = 0;
     for (int b0 = 0; b0 < batch; b0 += 64) {
       const int bb = b0 + lane;
-      int inc = bb < batch ? (d_lens[bb] + (FUSED ? 1 : 0) + kBlockKeys - 1) / kBlockKeys : 0;
+      int inc = 0;  // an idle sequence (length -1) has no blocks
+      if (bb < batch && d_lens[bb] >= 0) inc = (d_lens[bb] + (FUSED ? 1 : 0) + kBlockKeys - 1) / kBlockKeys;
 #pragma unroll
       for (int o = 1; o < 64; o <<= 1) {
         const int t = __shfl_up(inc, o);
@@ -524,7 +542,8 @@ __global__ __launch_bounds__(kTiledDim) void combine_balanced_kernel(TiledDecode
   // blocks of one kv head held by the sequences before b
   __shared__ int s_part[kTiledDim / 64];
   int before = 0;
-  for (int bb = threadIdx.x; bb < b; bb += kTiledDim) before += (a.d_lens[bb] + extra + kBlockKeys - 1) / kBlockKeys;
+  for (int bb = threadIdx.x; bb < b; bb += kTiledDim)
+    if (a.d_lens[bb] >= 0) before += (a.d_lens[bb] + extra + kBlockKeys - 1) / kBlockKeys;
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) before += __shfl_xor(before, o);
   if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = before;
@@ -532,6 +551,12 @@ __global__ __launch_bounds__(kTiledDim) void combine_balanced_kernel(TiledDecode
   before = 0;
 #pragma unroll
   for (int w = 0; w < kTiledDim / 64; ++w) before += s_part[w];
+  const int64_t row0 = (int64_t)b * a.Hq + hq;
+  if (a.d_lens[b] < 0) {  // idle sequence: no workgroup of the balanced launch touched it
+    store_out<OutT>((OutT*)a.out + row0 * kTiledDim + threadIdx.x, 0.f);
+    if (a.k_new && hq == 0 && threadIdx.x == 0) a.d_lens_out[b] = -1;
+    return;
+  }
   const int nb = (a.d_lens[b] + extra + kBlockKeys - 1) / kBlockKeys;
   const int64_t gs = (int64_t)before * a.Hkv + (int64_t)(hq / a.G) * nb;
   const int64_t row = (int64_t)b * a.Hq + hq;
@@ -542,6 +567,7 @@ __global__ __launch_bounds__(kTiledDim) void combine_balanced_kernel(TiledDecode
 template <typename OutT>
 __global__ __launch_bounds__(kTiledDim) void combine_kernel(TiledDecodeParams a) {
   const int hq = blockIdx.x, b = blockIdx.y;
+  if (a.d_lens[b] < 0) return;  // idle sequence: the decode launch wrote its zero rows
   int n = a.d_lens[b] + (a.k_new ? 1 : 0);  // the fused launch before this one read the old length array
   if (a.window > 0 && n > a.window) n = a.window;
   const int nb_total = (n + kBlockKeys - 1) / kBlockKeys;
@@ -658,10 +684,14 @@ __global__ __launch_bounds__(256) void decode_rowmajor_kernel(RowDecodeParams a)
   const int h = hq / a.G;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   int n = a.d_lens[b];
+  const int D = a.D;
+  if (n < 0) {  // idle sequence: zero row
+    for (int d = tid; d < D; d += 256) store_out<OutT>((OutT*)a.out + ((int64_t)b * a.Hq + hq) * D + d, 0.f);
+    return;
+  }
   if (a.window > 0 && n > a.window) n = a.window;
   const int lo = (a.attn_window > 0 && n > a.attn_window) ? n - a.attn_window : 0;  // sliding reader of a full cache
   const int slots = a.d_slots[b];
-  const int D = a.D;
   const T* Kp = (const T*)a.K + (a.d_base[b] + (int64_t)h * slots) * D;
   const T* Vp = (const T*)a.V + (a.d_base[b] + (int64_t)h * slots) * D;
   const T* qp = (const T*)a.q + ((int64_t)b * a.Hq + hq) * D;

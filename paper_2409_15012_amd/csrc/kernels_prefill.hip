@@ -118,7 +118,8 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
   const int64_t qrow0 = a.q_first ? a.q_first[b] : (int64_t)b * a.S;  // first row of the sequence in q / out
   const float c2 = a.scale_log2;
   // query row i sits at key index i + qoff of the K/V buffers
-  const int n_old = a.d_lens ? a.d_lens[b] - (a.old_sub ? S : 0) : 0;
+  // (an idle sequence holds length -1 until its first chunk is committed: it starts at position 0)
+  const int n_old = a.d_lens ? max(a.d_lens[b], 0) - (a.old_sub ? S : 0) : 0;
   const int qoff = (a.stage_window > 0 && n_old > a.stage_window - 1) ? a.stage_window - 1 : n_old;
 
   // Q^T fragments: lane (row, hh) holds dims kk*16 + hh*8 .. +7.  With 4 wavefronts each one first copies its 32
@@ -442,7 +443,8 @@ __global__ __launch_bounds__(256) void prefill_rowmajor_kernel(RowPrefillParams 
     qv[t] = d < D ? pf_load<T>(qp + d) : 0.f;
     acc[t] = 0.f;
   }
-  const int n_old = a.d_lens ? a.d_lens[b] - (a.old_sub ? S : 0) : 0;
+  // (an idle sequence holds length -1 until its first chunk is committed: it starts at position 0)
+  const int n_old = a.d_lens ? max(a.d_lens[b], 0) - (a.old_sub ? S : 0) : 0;
   const int pos = n_old + i;  // absolute position of this query row
   const int lo = a.window > 0 ? max(0, pos - a.window + 1) : 0;
   const int slots = a.d_lens ? a.d_slots[b] : 0;

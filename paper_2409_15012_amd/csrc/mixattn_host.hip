@@ -354,9 +354,9 @@ int mixattn_release_sequence(mixattn_layout* L, int b, void* stream) {
   if (b < 0 || b >= L->batch) return MIXATTN_ERR_LAYER;
   for (auto& c : L->caches) {
     // both length arrays: a fused append may have left the current one either way round
-    HIP_TRY(launch_fill_i32(c.d_lens2[0] + b, 0, 1, (hipStream_t)stream));
-    HIP_TRY(launch_fill_i32(c.d_lens2[1] + b, 0, 1, (hipStream_t)stream));
-    c.len[b] = 0;
+    HIP_TRY(launch_fill_i32(c.d_lens2[0] + b, kIdle, 1, (hipStream_t)stream));
+    HIP_TRY(launch_fill_i32(c.d_lens2[1] + b, kIdle, 1, (hipStream_t)stream));
+    c.len[b] = kIdle;
     c.plan_key = -1;
     release_pages(c, b);
     c.own_stage.cache = -1;
@@ -364,6 +364,10 @@ int mixattn_release_sequence(mixattn_layout* L, int b, void* stream) {
   L->stage.cache = -1;
   return MIXATTN_OK;
 }
+
+// Tokens sequence b holds in cache c (an idle sequence holds none).
+static inline int64_t held(const Cache& c, int b) { return c.len[b] < 0 ? 0 : c.len[b]; }
+static inline bool idle(const Cache& c, int b) { return c.len[b] < 0; }
 
 // A staged prompt chunk describes the cache as its writer's prefill left it: any other change to the cache retires it.
 static void retire_stage(mixattn_layout* L, Cache& c) {
@@ -374,6 +378,7 @@ static void retire_stage(mixattn_layout* L, Cache& c) {
 static int check_append(const mixattn_layout* L, const Cache& c, int layer) {
   if (c.writer != layer) return MIXATTN_ERR_NOT_WRITER;
   for (int b = 0; b < L->batch; ++b) {
+    if (idle(c, b)) continue;  // takes no token
     if (c.kind == MIXATTN_FULL && c.len[b] + 1 > L->capacity[b]) return MIXATTN_ERR_CAPACITY;
     if (c.len[b] + 1 > INT32_MAX) return MIXATTN_ERR_CAPACITY;
   }
@@ -383,7 +388,7 @@ static int check_append(const mixattn_layout* L, const Cache& c, int layer) {
 static int reserve_for_append(mixattn_layout* L, Cache& c, hipStream_t s) {
   if (!c.paged) return MIXATTN_OK;
   std::vector<int64_t> want(L->batch);
-  for (int b = 0; b < L->batch; ++b) want[b] = c.len[b] + 1;
+  for (int b = 0; b < L->batch; ++b) want[b] = idle(c, b) ? 0 : c.len[b] + 1;
   return reserve_pages(L, c, want, s);
 }
 
@@ -401,7 +406,7 @@ int mixattn_append_kv(mixattn_layout* L, int layer, const void* k, const void* v
   a.window = c.window; a.k = k; a.v = v;
   a.batch = L->batch; a.Hkv = L->Hkv; a.D = L->D; a.elem = L->elem;
   HIP_TRY(L->tiled ? launch_append_tiled(a, (hipStream_t)stream) : launch_append_rowmajor(a, (hipStream_t)stream));
-  for (int b = 0; b < L->batch; ++b) c.len[b] += 1;
+  for (int b = 0; b < L->batch; ++b) c.len[b] += idle(c, b) ? 0 : 1;
   return MIXATTN_OK;
 }
 
@@ -432,6 +437,7 @@ static int plan_chunk_blocks(const mixattn_layout* L, Cache& c, int max_blocks, 
   // 0.25 us per block.  (Workgroups of 8 wavefronts were measured as well: no gain, one CU cannot pull much more.)
   const double us_per_block_wg = 0.25, us_wg_fixed = 1.0, us_combine = 5.0;
   auto blocks_of = [&](int b) {
+    if (idle(c, b)) return 0;
     const int64_t n = tokens_read(c, c.len[b] + extra, attn_window);
     return (int)((n + kBlockKeys - 1) / kBlockKeys) + (attn_window > 0 ? 1 : 0);  // a window may straddle a block more
   };
@@ -463,6 +469,7 @@ static int plan_chunk_blocks(const mixattn_layout* L, Cache& c, int max_blocks, 
     } else {
       for (int b = 0; b < L->batch; ++b) {
         const int nb = blocks_of(b);
+        if (nb == 0) continue;  // idle sequence
         const int cb = (nb + t - 1) / t;
         wgs += (double)cb * L->Hkv;
         longest = std::max(longest, (nb + cb - 1) / cb);
@@ -491,6 +498,7 @@ static int launch_decode(mixattn_layout* L, Cache& c, int attn_window, const voi
   const int extra = k_new ? 1 : 0;
   int max_blocks = 0;  // most blocks one sequence reads
   for (int b = 0; b < L->batch; ++b) {
+    if (idle(c, b)) continue;
     const int64_t len = c.len[b] + extra;
     int64_t blocks;
     if (attn_window > 0 && len > attn_window)
@@ -499,6 +507,8 @@ static int launch_decode(mixattn_layout* L, Cache& c, int attn_window, const voi
       blocks = (tokens_read(c, len, attn_window) + kBlockKeys - 1) / kBlockKeys;
     max_blocks = std::max<int>(max_blocks, (int)blocks);
   }
+  const bool nothing_to_read = max_blocks == 0;  // every sequence is idle: the launch only writes zero rows
+  max_blocks = std::max(max_blocks, 1);
   DecodeLaunch a;
   a.K = c.K; a.V = c.V; a.d_base = c.d_base; a.d_slots = c.d_slots; a.d_lens = c.lens();
   a.pages = c.page_table();
@@ -515,7 +525,9 @@ static int launch_decode(mixattn_layout* L, Cache& c, int attn_window, const voi
     return MIXATTN_OK;
   }
   int chunk_blocks;
-  if (L->chunk_keys > 0) {
+  if (nothing_to_read) {
+    chunk_blocks = 1;
+  } else if (L->chunk_keys > 0) {
     chunk_blocks = (int)(L->chunk_keys / kBlockKeys);
   } else {
     chunk_blocks = plan_chunk_blocks(L, c, max_blocks, extra, attn_window);
@@ -531,11 +543,11 @@ static int launch_decode(mixattn_layout* L, Cache& c, int attn_window, const voi
   // Measured: ragged batch of 64, 5.68 -> 6.63 TB/s; one sequence of 131072, 4.68 -> 5.23 TB/s; a uniform batch
   // that needs no cut stays on the unsplit launch (6.72 against 6.64 TB/s).
   if (c.kind == MIXATTN_FULL && attn_window == 0 && n_group == 0 && L->chunk_keys == 0 && L->balanced != 0 &&
-      L->batch <= 1024) {
+      L->batch <= 1024 && !nothing_to_read) {
     int64_t sum_nb = 0;
     int max_nb = 0;
     for (int b = 0; b < L->batch; ++b) {
-      const int nb = (int)((c.len[b] + extra + kBlockKeys - 1) / kBlockKeys);
+      const int nb = idle(c, b) ? 0 : (int)((c.len[b] + extra + kBlockKeys - 1) / kBlockKeys);
       sum_nb += nb;
       max_nb = std::max(max_nb, nb);
     }
@@ -559,7 +571,7 @@ int mixattn_decode(mixattn_layout* L, int layer, const void* q, void* out, void*
   if (layer < 0 || layer >= L->n_layers) return MIXATTN_ERR_LAYER;
   Cache& c = L->caches[L->layer_cache[layer]];
   for (int b = 0; b < L->batch; ++b)
-    if (c.len[b] < 1) return MIXATTN_ERR_ORDER;
+    if (c.len[b] == 0) return MIXATTN_ERR_ORDER;  // empty; an idle sequence (negative) is passed over
   return launch_decode(L, c, layer_attn_window(L, layer), q, out, nullptr, nullptr, (hipStream_t)stream);
 }
 
@@ -579,7 +591,7 @@ int mixattn_append_decode(mixattn_layout* L, int layer, const void* k, const voi
   st = launch_decode(L, c, 0, q, out, k, v, (hipStream_t)stream);
   if (st != MIXATTN_OK) return st;
   c.cur ^= 1;  // the launch wrote n + 1 into the other length array
-  for (int b = 0; b < L->batch; ++b) c.len[b] += 1;
+  for (int b = 0; b < L->batch; ++b) c.len[b] += idle(c, b) ? 0 : 1;
   return MIXATTN_OK;
 }
 
@@ -603,13 +615,13 @@ int mixattn_decode_group(mixattn_layout* L, const int32_t* layers, int n_layers,
     retire_stage(L, c);
   } else {
     for (int b = 0; b < L->batch; ++b)
-      if (c.len[b] < 1) return MIXATTN_ERR_ORDER;
+      if (c.len[b] == 0) return MIXATTN_ERR_ORDER;
   }
   const int st = launch_decode(L, c, 0, q, out, k, v, (hipStream_t)stream, n_layers);
   if (st != MIXATTN_OK) return st;
   if (k) {
     c.cur ^= 1;  // the launch wrote n + 1 into the other length array
-    for (int b = 0; b < L->batch; ++b) c.len[b] += 1;
+    for (int b = 0; b < L->batch; ++b) c.len[b] += idle(c, b) ? 0 : 1;
   }
   return MIXATTN_OK;
 }
@@ -665,7 +677,8 @@ static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void*
   bool chunked = false;
   int64_t max_new = 0, max_old = 0;
   for (int b = 0; b < L->batch; ++b) {
-    const int64_t n_old = writer ? c.len[b] : c.len[b] - len_of(b);
+    if (len_of(b) == 0) continue;  // sits this call out (and stays idle if it is)
+    const int64_t n_old = writer ? held(c, b) : held(c, b) - len_of(b);
     if (n_old < 0) return MIXATTN_ERR_ORDER;  // the writer's prefill of this chunk has not run
     if (c.kind == MIXATTN_FULL && n_old + len_of(b) > L->capacity[b]) return MIXATTN_ERR_CAPACITY;
     if (n_old + len_of(b) > INT32_MAX) return MIXATTN_ERR_CAPACITY;
@@ -720,7 +733,7 @@ static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void*
   auto commit = [&]() -> int {
     if (c.paged) {
       std::vector<int64_t> want(L->batch);
-      for (int b = 0; b < L->batch; ++b) want[b] = c.len[b] + len_of(b);
+      for (int b = 0; b < L->batch; ++b) want[b] = held(c, b) + len_of(b);
       const int e = reserve_pages(L, c, want, s);
       if (e != MIXATTN_OK) return e;
     }
@@ -739,7 +752,8 @@ static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void*
     st.max_slots = (int)(c.window > 0 ? std::min<int64_t>(max_new, c.window) : max_new);
     HIP_TRY(L->tiled ? launch_store_tiled(st, s) : launch_store_rowmajor(st, s));
     c.cur ^= 1;
-    for (int b = 0; b < L->batch; ++b) c.len[b] += len_of(b);
+    for (int b = 0; b < L->batch; ++b)
+      if (len_of(b) > 0) c.len[b] = held(c, b) + len_of(b);  // a chunk also starts an idle sequence
     return MIXATTN_OK;
   };
 
@@ -864,7 +878,7 @@ int mixattn_load_kv(mixattn_layout* L, int layer, const void* k, const void* v, 
   int64_t run = 0;
   int max_len = 0;
   for (int b = 0; b < L->batch; ++b) {
-    if (c.len[b] != 0) return MIXATTN_ERR_ORDER;
+    if (held(c, b) != 0) return MIXATTN_ERR_ORDER;
     if (seq_lens[b] < 0) return MIXATTN_ERR_ORDER;
     if (c.kind == MIXATTN_FULL && seq_lens[b] > L->capacity[b]) return MIXATTN_ERR_CAPACITY;
     first[b] = run;
@@ -888,11 +902,15 @@ int mixattn_load_kv(mixattn_layout* L, int layer, const void* k, const void* v, 
   st.K = c.K; st.V = c.V; st.d_base = c.d_base; st.d_slots = c.d_slots; st.window = c.window;
   st.pages = c.page_table();
   st.k_src = k; st.v_src = v; st.d_src_first = L->d_stage_src; st.d_src_len = L->d_stage_lens; st.uniform_len = 0;
-  st.d_lens_out = c.lens();
+  // lengths: read from the current array (0, or idle), written to the other one, which then becomes current
+  st.d_n_old = c.lens(); st.old_sub = 0;
+  st.d_lens_out = c.lens_other();
   st.batch = L->batch; st.Hkv = L->Hkv; st.D = L->D; st.elem = L->elem;
   st.max_slots = std::max(1, c.window > 0 ? std::min(max_len, c.window) : max_len);
   HIP_TRY(L->tiled ? launch_store_tiled(st, s) : launch_store_rowmajor(st, s));
-  for (int b = 0; b < L->batch; ++b) c.len[b] = seq_lens[b];
+  c.cur ^= 1;
+  for (int b = 0; b < L->batch; ++b)
+    if (seq_lens[b] > 0 || !idle(c, b)) c.len[b] = seq_lens[b];  // an idle sequence given nothing stays idle
   return MIXATTN_OK;
 }
 
@@ -910,7 +928,7 @@ int mixattn_cache_of(const mixattn_layout* L, int layer, int* cache_index, int* 
 int mixattn_seq_len(const mixattn_layout* L, int cache_index, int b, int64_t* n) {
   if (!L || !n) return MIXATTN_ERR_NULL;
   if (cache_index < 0 || cache_index >= (int)L->caches.size() || b < 0 || b >= L->batch) return MIXATTN_ERR_LAYER;
-  *n = L->caches[cache_index].len[b];
+  *n = held(L->caches[cache_index], b);
   return MIXATTN_OK;
 }
 
@@ -968,7 +986,7 @@ int64_t mixattn_kv_bytes_live(const mixattn_layout* L) {
   if (!L) return MIXATTN_ERR_NULL;
   int64_t tok = 0;
   for (const auto& c : L->caches)
-    for (int b = 0; b < L->batch; ++b) tok += c.window > 0 ? std::min<int64_t>(c.len[b], c.window) : c.len[b];
+    for (int b = 0; b < L->batch; ++b) tok += c.window > 0 ? std::min<int64_t>(held(c, b), c.window) : held(c, b);
   return tok * 2 * L->Hkv * L->D * L->elem;
 }
 
@@ -978,7 +996,7 @@ int64_t mixattn_step_read_bytes(const mixattn_layout* L, int layer) {
   const Cache& c = L->caches[L->layer_cache[layer]];
   const int aw = layer_attn_window(L, layer);
   int64_t tok = 0;
-  for (int b = 0; b < L->batch; ++b) tok += tokens_read(c, c.len[b], aw);
+  for (int b = 0; b < L->batch; ++b) tok += tokens_read(c, held(c, b), aw);
   return tok * 2 * L->Hkv * L->D * L->elem;
 }
 

@@ -24,6 +24,7 @@ constexpr int kBlockKeys = 32;
 constexpr int kTiledDim = 128;
 constexpr int kBlockElems = kBlockKeys * kTiledDim;  // 4096 elements = 8 KiB of bf16
 constexpr int kMaxGroup = 8;                         // query heads per KV head on the MFMA decode path
+constexpr int kIdle = -1;                             // length of a released sequence until a prompt chunk or load restarts it
 constexpr int kMaxChunks = 64;                       // split-K chunks per (sequence, kv head)
 constexpr int kMaxHeadDim = 256;
 constexpr int kDecodeMinChunkBlocks = 4;              // a split-K chunk keeps every wavefront of its workgroup busy

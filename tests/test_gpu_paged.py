@@ -179,3 +179,103 @@ def test_paged_layout_rejects_what_it_cannot_hold(mx):
     with pytest.raises(mx.MixAttnError) as ei:   # row-major shapes have no paged form
         mx.Layout(layers, 1, 4, 4, 64, capacity=[100], kv_dtype="f32", page_tokens=64, pool_tokens=640)
     assert ei.value.status == -2
+
+
+@pytest.mark.parametrize("kv_dtype,d,paged,balanced", [("bf16", 128, 0, 1), ("bf16", 128, 64, 2), ("bf16", 128, 0, 0),
+                                                       ("f32", 64, 0, 1)])
+def test_idle_slots_of_the_batch_are_passed_over(mx, kv_dtype, d, paged, balanced):
+    """Requests end at different times: a released sequence is idle (decode-step tokens pass over it, its output
+    rows are zero, its batch mates are unaffected) until a prompt chunk starts a new request in its slot."""
+    Hq, Hkv, W, B = 8, 2, 40, 4
+    tdt = torch.bfloat16 if kv_dtype == "bf16" else torch.float32
+    tol = "bf16" if kv_dtype == "bf16" else "f32"
+    # full writer, ring writer, ring reader, full reader, sliding reader of the full cache
+    layers = [(0, 0, 0), (1, W, 1), (1, W, 1), (0, 0, 0), (1, W, 0)]
+    lens = [300, 77, 5, 130]
+    cap = [n + 400 for n in lens]
+    kw = {}
+    if paged:
+        kw = dict(page_tokens=paged, pool_tokens=sum((c + paged - 1) // paged for c in cap) * paged)
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=cap, kv_dtype=kv_dtype, out_dtype="f32", **kw)
+    lay.set_param(mx.PARAM_BALANCED, balanced)
+    ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
+    for li in (0, 1):
+        k = wl.randn(10 + li, (sum(lens), Hkv, d), tdt, DEV)
+        v = wl.randn(20 + li, (sum(lens), Hkv, d), tdt, DEV)
+        lay.load_kv(li, k, v, lens)
+        ora.load(li, to_f64(k), to_f64(v), lens)
+    seed = [5000]
+
+    def step(fused, group=False):
+        seed[0] += 10
+        outs = {}
+        for li in range(len(layers)):
+            q = wl.randn(seed[0] + li, (B, Hq, d), tdt, DEV)
+            if lay.writer_of(li) == li:
+                k = wl.randn(seed[0] + 100 + li, (B, Hkv, d), tdt, DEV)
+                v = wl.randn(seed[0] + 200 + li, (B, Hkv, d), tdt, DEV)
+                ora.append(li, to_f64(k), to_f64(v))
+                if group and li == 1:
+                    q2 = torch.stack([q, wl.randn(seed[0] + 2, (B, Hq, d), tdt, DEV)]).contiguous()
+                    out2 = lay.decode_group([1, 2], q2, k, v)
+                    outs[1], outs[2] = (out2[0], q2[0]), (out2[1], q2[1])
+                    continue
+                if fused:
+                    out = lay.append_decode(li, k, v, q)
+                else:
+                    lay.append_kv(li, k, v)
+                    out = lay.decode(li, q)
+            elif group and li == 2:
+                continue
+            else:
+                out = lay.decode(li, q)
+            outs[li] = (out, q)
+        for li, (out, q) in outs.items():
+            ref = ora.decode(li, to_f64(q))
+            assert_matches(out, ref, tol, "layer %d" % li)
+            for b in range(B):
+                if ora.is_idle(li, b):
+                    assert torch.count_nonzero(out[b]) == 0, (li, b)
+
+    step(fused=True)
+    for b in (1, 3):
+        lay.release_sequence(b); ora.release_sequence(b)
+    step(fused=True)
+    step(fused=False)
+    if kv_dtype == "bf16":
+        step(fused=True, group=True)
+    ci0, _ = lay.cache_of(0)
+    ci1, _ = lay.cache_of(1)
+    assert [lay.seq_len(ci0, b) for b in range(B)] == [ora.seq_len(0, b) for b in range(B)]
+    assert lay.device_lens(ci0)[1] == -1 and lay.device_lens(ci1)[3] == -1      # idle on the device too
+    # a new request starts in slot 3 (a prompt of 90 tokens, fed in two chunks); slot 1 stays idle
+    for chunk in ([0, 0, 0, 60], [0, 0, 0, 30]):
+        T = sum(chunk)
+        kv = {}
+        for li in range(len(layers)):
+            wr = lay.writer_of(li)
+            seed[0] += 7
+            if wr == li:
+                kv[li] = (wl.randn(seed[0], (T, Hkv, d), tdt, DEV), wl.randn(seed[0] + 1, (T, Hkv, d), tdt, DEV))
+            q = wl.randn(seed[0] + 2, (T, Hq, d), tdt, DEV)
+            k, v = kv[wr]
+            ring_reader = wr != li and layers[li][0] == 1 and layers[wr][0] == 1
+            if ring_reader and kv_dtype == "bf16":
+                out = lay.prefill_varlen(li, q, None, None, chunk)
+            elif ring_reader and chunk[3] == 30:
+                continue    # the scalar path has no staged copy for a ring reader past the first chunk
+            else:
+                out = lay.prefill_varlen(li, q, k, v, chunk)
+            ref = ora.prefill_ragged(li, to_f64(q), to_f64(k) if wr == li else None, to_f64(v) if wr == li else None, chunk)
+            assert_matches(out, ref, tol, "restart chunk %s layer %d" % (chunk, li))
+    step(fused=True)
+    step(fused=False)
+    assert [lay.seq_len(ci0, b) for b in range(B)] == [ora.seq_len(0, b) for b in range(B)]
+    assert lay.device_lens(ci0)[1] == -1 and lay.device_lens(ci0)[3] == ora.seq_len(0, 3)
+    # everybody idle: the calls still run and write zeros
+    for b in (0, 2, 3):
+        lay.release_sequence(b); ora.release_sequence(b)
+    step(fused=True)
+    step(fused=False)
+    assert lay.kv_bytes_live() == 0
+    lay.close()

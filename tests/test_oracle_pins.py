@@ -431,3 +431,46 @@ def test_released_sequence_behaves_like_a_fresh_one():
     for li in (0, 1):
         solo.load(li, k[5:], v[5:], [4])
         np.testing.assert_array_equal(a.decode(li, q, rows=[(1, j) for j in range(Hq)])[1], solo.decode(li, q[1:2])[0])
+
+
+def test_idle_sequences_are_passed_over():
+    """A released sequence is idle: decode-step tokens pass over it, its decode rows are zero, its batch mates see
+    nothing of it, and a new prompt in its slot gives exactly what a fresh stack gives."""
+    Hq, Hkv, d, W = 4, 2, 8, 3
+    layers = [(FULL, 0, 0), (SLIDING, W, 1), (SLIDING, W, 1)]
+    rng = np.random.default_rng(77)
+    a = _stack(layers, 3, Hq, Hkv, d)
+    solo = _stack(layers, 1, Hq, Hkv, d)     # sequence 2 alone
+    k = rng.standard_normal((12, Hkv, d)); v = rng.standard_normal((12, Hkv, d))
+    for li in (0, 1):
+        a.load(li, k, v, [5, 4, 3])
+        solo.load(li, k[9:], v[9:], [3])
+    a.release_sequence(1)
+    assert all(a.is_idle(li, 1) for li in range(3)) and not a.is_idle(0, 0)
+    for step in range(4):
+        k1 = rng.standard_normal((3, Hkv, d)); v1 = rng.standard_normal((3, Hkv, d))
+        q1 = rng.standard_normal((3, Hq, d))
+        for li in (0, 1):
+            a.append(li, k1, v1)
+            solo.append(li, k1[2:], v1[2:])
+        for li in range(3):
+            out = a.decode(li, q1)
+            assert np.all(out[1] == 0.0)
+            np.testing.assert_array_equal(out[2], solo.decode(li, q1[2:])[0])
+        assert [a.seq_len(li, 1) for li in (0, 1)] == [0, 0]
+        assert a.seq_len(0, 0) == 5 + step + 1
+    # a new request in the idle slot: two prompt tokens, the others sit the call out
+    k2 = rng.standard_normal((2, Hkv, d)); v2 = rng.standard_normal((2, Hkv, d)); q2 = rng.standard_normal((2, Hq, d))
+    fresh = _stack(layers, 1, Hq, Hkv, d)
+    for li in range(3):
+        wr = li != 2
+        got = a.prefill_ragged(li, q2, k2 if wr else None, v2 if wr else None, [0, 2, 0])
+        ref = fresh.prefill_ragged(li, q2, k2 if wr else None, v2 if wr else None, [2])
+        np.testing.assert_array_equal(got, ref)
+        assert not a.is_idle(li, 1)
+    k1 = rng.standard_normal((3, Hkv, d)); v1 = rng.standard_normal((3, Hkv, d)); q1 = rng.standard_normal((3, Hq, d))
+    for li in (0, 1):
+        a.append(li, k1, v1)
+        fresh.append(li, k1[1:2], v1[1:2])
+    for li in range(3):
+        np.testing.assert_array_equal(a.decode(li, q1)[1], fresh.decode(li, q1[1:2])[0])
