@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="decode32k", choices=["decode32k", "decode4k", "prefill32k", "ragged64", "variants", "gen31k"])
+    ap.add_argument("--workload", default="decode32k", choices=["decode32k", "decode4k", "prefill32k", "ragged64", "variants", "gen31k", "serve"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-keys", type=int, default=0)
     ap.add_argument("--fused-combine", type=int, default=-1)
@@ -48,6 +48,10 @@ def parse():
     ap.add_argument("--gen-batch", type=int, default=32)
     ap.add_argument("--gen-prompt", type=int, default=31000)
     ap.add_argument("--gen-new", type=int, default=1000)
+    ap.add_argument("--serve-requests", type=int, default=96, help="serve: requests to run through the batch slots")
+    ap.add_argument("--serve-slots", type=int, default=32, help="serve: sequences decoded together")
+    ap.add_argument("--serve-prompt", type=int, nargs=2, default=[8000, 31000], help="serve: prompt length range")
+    ap.add_argument("--serve-new", type=int, nargs=2, default=[100, 1000], help="serve: generated length range")
     ap.add_argument("--page-tokens", type=int, default=0,
                     help="hold full-attention caches as pools of pages of this many tokens (0: contiguous)")
     ap.add_argument("--group-decode", action="store_true",
@@ -390,6 +394,93 @@ def run_generation(args, mx, wl, torch, layers, label):
     return r
 
 
+def run_serving(args, mx, wl, torch, layers, label):
+    """Requests of mixed lengths served through a fixed number of batch slots (Section 4 measures 300 requests
+    through a serving engine): a slot whose request has produced its last token is released and idles until the
+    next request's prompt is prefilled into it (several new prompts go through the stack in one variable-length
+    call), while the other slots keep decoding.  Full caches are paged; values of q/k/v do not change the cost, so
+    one set of tensors serves all layers."""
+    import random
+    dev = "cuda:0"
+    B, R = args.serve_slots, args.serve_requests
+    Hq, Hkv, d = 32, 8, 128
+    rng = random.Random(20240915)
+    reqs = [(rng.randint(*args.serve_prompt), rng.randint(*args.serve_new)) for _ in range(R)]
+    p_max, t_max = args.serve_prompt[1], args.serve_new[1]
+    cap = [p_max + t_max] * B
+    page = args.page_tokens or 256
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=cap, kv_dtype="bf16", out_dtype=args.out_dtype,
+                    **_paging(page, cap))
+    writer_of = [lay.writer_of(li) for li in range(len(layers))]
+    rows = B * p_max
+    q = wl.randn(1, (rows, Hq, d), torch.bfloat16, dev)
+    k = wl.randn(2, (rows, Hkv, d), torch.bfloat16, dev)
+    v = wl.randn(3, (rows, Hkv, d), torch.bfloat16, dev)
+    out = torch.empty((rows, Hq, d), dtype=lay.out_torch, device=dev)
+    q1 = wl.randn(4, (B, Hq, d), torch.bfloat16, dev)
+    k1 = wl.randn(5, (B, Hkv, d), torch.bfloat16, dev)
+    v1 = wl.randn(6, (B, Hkv, d), torch.bfloat16, dev)
+    out1 = torch.empty((B, Hq, d), dtype=lay.out_torch, device=dev)
+
+    def prefill(lens):
+        n = sum(lens)
+        for li in range(len(layers)):
+            if writer_of[li] == li:
+                lay.prefill_varlen(li, q[:n], k[:n], v[:n], lens, out[:n])
+            else:
+                direct = writer_of[li] == li - 1 or (li > 0 and writer_of[li - 1] == writer_of[li])
+                lay.prefill_varlen(li, q[:n], None if direct else k[:n], None if direct else v[:n], lens, out[:n])
+
+    def decode_step():
+        for li in range(len(layers)):
+            if writer_of[li] == li:
+                lay.append_decode(li, k1, v1, q1, out1)
+            else:
+                lay.decode(li, q1, out1)
+
+    def serve(requests):
+        pending = list(requests)
+        for b in range(B):      # every slot starts idle
+            lay.release_sequence(b)
+        left = [0] * B          # tokens the slot's request still has to generate (0: idle)
+        steps = prefills = generated = prompt_tokens = 0
+        while pending or any(left):
+            lens = [0] * B
+            for b in range(B):
+                if left[b] == 0 and pending:
+                    p_len, t_len = pending.pop(0)
+                    lens[b], left[b] = p_len, t_len
+            if any(lens):
+                prefill(lens)
+                prefills += 1
+                prompt_tokens += sum(lens)
+            decode_step()
+            steps += 1
+            for b in range(B):
+                if left[b]:
+                    generated += 1
+                    left[b] -= 1
+                    if left[b] == 0:
+                        lay.release_sequence(b)
+        return steps, prefills, generated, prompt_tokens
+
+    # warm-up: a few short requests through every code path (kernels, staging areas, planner), then start over
+    serve([(args.serve_prompt[1], 3)] * min(B, 2) + [(1000, 2)] * 2)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    steps, prefills, generated, prompt_tokens = serve(reqs)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    r = {"label": label, "slots": B, "requests": R, "prompt_tokens": prompt_tokens, "generated_tokens": generated,
+         "decode_steps": steps, "prefill_calls": prefills, "total_s": t1 - t0,
+         "output_tokens_per_s": generated / (t1 - t0), "requests_per_s": R / (t1 - t0),
+         "kv_bytes_allocated": lay.kv_bytes_allocated(), "page_tokens": page}
+    lay.close()
+    del lay
+    torch.cuda.empty_cache()
+    return r
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -488,6 +579,25 @@ def main():
             line["standard"] = r_std
             line["total_time_ratio_standard_over_mix"] = r_std["total_s"] / r_mix["total_s"]
             line["kv_bytes_ratio_standard_over_mix"] = r_std["kv_bytes_resident"] / r_mix["kv_bytes_resident"]
+    elif args.workload == "serve":
+        r_mix = run_serving(args, mx, wl, torch, wl.layout_mix24(), "mix24")
+        line = dict(base)
+        line.update({
+            "metric": "output tokens/s, %d requests of mixed lengths through %d batch slots, attention stack only "
+                      "(continuous batching: paged full caches, idle slots, variable-length prefill)"
+                      % (args.serve_requests, args.serve_slots),
+            "value": r_mix["output_tokens_per_s"], "unit": "tokens/s", "steps": r_mix["decode_steps"], "warmup": 0,
+            "ms_per_step": r_mix["total_s"] * 1e3 / r_mix["decode_steps"],
+            "config": {"workload": "serve_r%d_b%d" % (args.serve_requests, args.serve_slots),
+                       "prompt_range": args.serve_prompt, "new_token_range": args.serve_new, "window": 1024,
+                       "out_dtype": args.out_dtype},
+            "mix": r_mix,
+        })
+        if args.with_standard:
+            r_std = run_serving(args, mx, wl, torch, wl.layout_full24(), "standard24")
+            line["standard"] = r_std
+            line["total_time_ratio_standard_over_mix"] = r_std["total_s"] / r_mix["total_s"]
+            line["kv_bytes_ratio_standard_over_mix"] = r_std["kv_bytes_allocated"] / r_mix["kv_bytes_allocated"]
     else:  # ragged64
         w = wl.config(4)
         r_mix = run_decode(args, mx, wl, torch, w)
