@@ -474,3 +474,95 @@ def test_idle_sequences_are_passed_over():
         fresh.append(li, k1[1:2], v1[1:2])
     for li in range(3):
         np.testing.assert_array_equal(a.decode(li, q1)[1], fresh.decode(li, q1[1:2])[0])
+
+
+# ----------------------------------------------------- random request traffic against a list-of-tokens model
+def _sdpa_row(q_row, K, V, scale):
+    """One output row through torch's fp64 CPU scaled_dot_product_attention (a library routine, not the oracle's sum)."""
+    qt = torch.from_numpy(np.ascontiguousarray(q_row)).reshape(1, 1, 1, -1)
+    kt = torch.from_numpy(np.ascontiguousarray(K)).reshape(1, 1, K.shape[0], -1)
+    vt = torch.from_numpy(np.ascontiguousarray(V)).reshape(1, 1, V.shape[0], -1)
+    return torch.nn.functional.scaled_dot_product_attention(qt, kt, vt, scale=scale).reshape(-1).numpy()
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_request_traffic_matches_a_list_of_tokens_model(seed):
+    """Random stacks and random sequences of calls (appends, ragged prompt chunks, releases, decodes): every output
+    row equals library attention over the tokens a plain per-(cache, sequence) list says the row can see."""
+    rng = np.random.default_rng(1000 + seed)
+    Hkv = int(rng.integers(1, 3)); G = int(rng.integers(1, 4)); Hq = Hkv * G; d = 4; B = int(rng.integers(1, 4))
+    n_caches = int(rng.integers(1, 4))
+    kinds = [(int(rng.integers(0, 2)), int(rng.integers(1, 6))) for _ in range(n_caches)]   # per cache: kind, window
+    layers, seen = [], set()
+    for _ in range(int(rng.integers(n_caches, n_caches + 4))):
+        c = int(rng.integers(0, n_caches)) if len(seen) == n_caches else len(seen)
+        kind, W = kinds[c]
+        if c in seen and kind == FULL and rng.random() < 0.3:
+            layers.append((SLIDING, int(rng.integers(1, 6)), c))       # sliding reader of a full cache
+        else:
+            layers.append((kind, W if kind == SLIDING else 0, c))
+        seen.add(c)
+    st = _stack(layers, B, Hq, Hkv, d)
+    writer = {}
+    for li, (_, _, c) in enumerate(layers):
+        writer.setdefault(c, li)
+    toks = {c: [[] for _ in range(B)] for c in range(n_caches)}       # the model: (k, v) rows per cache and sequence
+    idle = {c: [False] * B for c in range(n_caches)}
+
+    def expect(li, b, j, q_row, pos):
+        kind, W, c = layers[li]
+        lo = max(0, pos - W + 1) if kind == SLIDING else 0
+        rows = toks[c][b][lo:pos + 1]
+        K = np.stack([r[0][j // G] for r in rows]); V = np.stack([r[1][j // G] for r in rows])
+        return _sdpa_row(q_row, K, V, 1.0 / math.sqrt(d))
+
+    for _ in range(25):
+        op = rng.choice(["append", "chunk", "release", "decode"], p=[0.35, 0.3, 0.1, 0.25])
+        if op == "append":
+            for c, li in writer.items():
+                k = rng.standard_normal((B, Hkv, d)); v = rng.standard_normal((B, Hkv, d))
+                st.append(li, k, v)
+                for b in range(B):
+                    if not idle[c][b]:
+                        toks[c][b].append((k[b], v[b]))
+        elif op == "chunk":
+            lens = [int(x) for x in rng.integers(0, 4, size=B)]
+            if sum(lens) == 0:
+                continue
+            T = sum(lens); first = np.concatenate([[0], np.cumsum(lens)])
+            kv = {c: (rng.standard_normal((T, Hkv, d)), rng.standard_normal((T, Hkv, d))) for c in writer}
+            for li, (_, _, c) in enumerate(layers):
+                q = rng.standard_normal((T, Hq, d))
+                is_w = writer[c] == li
+                if is_w:
+                    for b in range(B):
+                        if lens[b]:
+                            idle[c][b] = False
+                        toks[c][b].extend((kv[c][0][t], kv[c][1][t]) for t in range(first[b], first[b + 1]))
+                out = st.prefill_ragged(li, q, kv[c][0] if is_w else None, kv[c][1] if is_w else None, lens)
+                for b in range(B):
+                    n = len(toks[c][b])
+                    for i in range(lens[b]):
+                        j = int(rng.integers(0, Hq))
+                        np.testing.assert_allclose(out[first[b] + i, j], expect(li, b, j, q[first[b] + i, j], n - lens[b] + i),
+                                                   atol=1e-12)
+        elif op == "release":
+            b = int(rng.integers(0, B))
+            st.release_sequence(b)
+            for c in toks:
+                toks[c][b] = []
+                idle[c][b] = True
+        else:
+            for li, (_, _, c) in enumerate(layers):
+                if any(len(toks[c][b]) == 0 and not idle[c][b] for b in range(B)):
+                    continue   # an empty (not idle) sequence: decode is an error there
+                q = rng.standard_normal((B, Hq, d))
+                out = st.decode(li, q)
+                for b in range(B):
+                    for j in range(Hq):
+                        if idle[c][b]:
+                            assert np.all(out[b, j] == 0.0)
+                        else:
+                            np.testing.assert_allclose(out[b, j], expect(li, b, j, q[b, j], len(toks[c][b]) - 1), atol=1e-12)
+    for c, li in writer.items():
+        assert [st.seq_len(li, b) for b in range(B)] == [len(toks[c][b]) for b in range(B)]
