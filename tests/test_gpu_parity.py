@@ -706,3 +706,95 @@ def test_balanced_decode_over_ragged_batches(mx, B, Hq, Hkv, max_len, paged, bal
                 assert torch.equal(out, lay.decode(li, q))  # same launch again: bit-identical
     _check_cache(lay, ora, 0, bs=[0, B - 1], heads=[Hkv - 1])
     lay.close()
+
+
+# --------------------------------------------------------------------------- random request traffic
+@pytest.mark.parametrize("seed", range(20))
+def test_random_request_traffic_against_oracle(mx, seed):
+    """Random stacks (shared rings, shared full caches, sliding readers of full caches; paged or not) under random
+    sequences of calls: fused and two-call appends, decodes, ragged prompt chunks, releases.  Every output against the
+    oracle; lengths and the cache rows of one head bit-exact at the end."""
+    rng = np.random.default_rng(7000 + seed)
+    Hq, Hkv, d = 8, 2, 128
+    B = int(rng.integers(1, 5))
+    n_caches = int(rng.integers(1, 4))
+    kinds = [(int(rng.integers(0, 2)), int(rng.choice([1, 7, 32, 33, 100]))) for _ in range(n_caches)]
+    layers, seen = [], set()
+    for _ in range(int(rng.integers(n_caches, n_caches + 4))):
+        c = int(rng.integers(0, n_caches)) if len(seen) == n_caches else len(seen)
+        kind, W = kinds[c]
+        if c in seen and kind == 0 and rng.random() < 0.4:
+            layers.append((1, int(rng.choice([1, 5, 40, 64])), c))    # sliding reader of a full cache
+        else:
+            layers.append((kind, W if kind == 1 else 0, c))
+        seen.add(c)
+    paged = int(rng.choice([0, 32, 64]))
+    cap = [2240] * B     # 30 calls of at most 70 tokens; a whole number of pages of either size
+    kw = dict(page_tokens=paged, pool_tokens=B * 2240) if paged else {}
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=cap, kv_dtype="bf16", out_dtype="f32", **kw)
+    lay.set_param(mx.PARAM_BALANCED, int(rng.integers(0, 3)))
+    ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
+    writers = [li for li in range(len(layers)) if lay.writer_of(li) == li]
+    sd = [seed * 100000]
+
+    def rand(shape):
+        sd[0] += 1
+        return wl.randn(sd[0], shape, torch.bfloat16, DEV)
+
+    def can_decode(li):
+        return all(ora.seq_len(li, b) > 0 or ora.is_idle(li, b) for b in range(B))
+
+    for it in range(30):
+        op = rng.choice(["step", "chunk", "release"], p=[0.5, 0.35, 0.15])
+        if op == "step":
+            fused = bool(rng.integers(0, 2))
+            new = {li: (rand((B, Hkv, d)), rand((B, Hkv, d))) for li in writers}
+            for li in range(len(layers)):
+                q = rand((B, Hq, d))
+                if li in new:
+                    k, v = new[li]
+                    ora.append(li, to_f64(k), to_f64(v))
+                    if fused and can_decode(li):
+                        out = lay.append_decode(li, k, v, q)
+                    else:
+                        lay.append_kv(li, k, v)
+                        out = lay.decode(li, q) if can_decode(li) else None
+                else:
+                    out = lay.decode(li, q) if can_decode(li) else None
+                if out is not None:
+                    assert_matches(out, ora.decode(li, to_f64(q)), "bf16", "it %d step layer %d" % (it, li))
+        elif op == "chunk":
+            lens = [int(x) for x in rng.choice([0, 1, 5, 33, 70], size=B)]
+            if sum(lens) == 0:
+                continue
+            T = sum(lens)
+            kv = {li: (rand((T, Hkv, d)), rand((T, Hkv, d))) for li in writers}
+            for li in range(len(layers)):
+                wr = lay.writer_of(li)
+                q = rand((T, Hq, d))
+                k, v = kv[wr]
+                if wr == li:
+                    out = lay.prefill_varlen(li, q, k, v, lens)
+                elif layers[wr][0] == 1:
+                    out = lay.prefill_varlen(li, q, None, None, lens)      # ring reader: from the ring's staged chunk
+                else:
+                    out = lay.prefill_varlen(li, q, k, v, lens)
+                ref = ora.prefill_ragged(li, to_f64(q), to_f64(k) if wr == li else None, to_f64(v) if wr == li else None, lens)
+                assert_matches(out, ref, "bf16", "it %d chunk %s layer %d" % (it, lens, li))
+        else:
+            b = int(rng.integers(0, B))
+            lay.release_sequence(b)
+            ora.release_sequence(b)
+    for li in writers:
+        ci, _ = lay.cache_of(li)
+        assert [lay.seq_len(ci, b) for b in range(B)] == [ora.seq_len(li, b) for b in range(B)]
+        dev_lens = lay.device_lens(ci)
+        assert [max(n, 0) for n in dev_lens] == [ora.seq_len(li, b) for b in range(B)]
+        assert [n < 0 for n in dev_lens] == [ora.is_idle(li, b) for b in range(B)]
+        for b in range(B):
+            K, V = ora.history(li, b)
+            for slot, pos in ora.cache_view(li, b):
+                k_row, v_row = lay.read_cache(ci, b, 1, slot)
+                assert np.array_equal(k_row.double().numpy(), K[pos, 1]), (li, b, slot, pos)
+                assert np.array_equal(v_row.double().numpy(), V[pos, 1]), (li, b, slot, pos)
+    lay.close()
