@@ -798,3 +798,38 @@ def test_random_request_traffic_against_oracle(mx, seed):
                 assert np.array_equal(k_row.double().numpy(), K[pos, 1]), (li, b, slot, pos)
                 assert np.array_equal(v_row.double().numpy(), V[pos, 1]), (li, b, slot, pos)
     lay.close()
+
+
+# --------------------------------------------------------------------------- extreme score ranges
+@pytest.mark.parametrize("gain", [8.0, 1.0 / 64])
+def test_peaked_and_flat_softmax(mx, gain):
+    """Scores 64 times larger than for unit-variance inputs (softmax close to one-hot: differences of hundreds in
+    the exponent, rescales at almost every block) and 4096 times smaller (uniform weights): decode and prefill,
+    full and sliding, against the oracle."""
+    d, Hq, Hkv, B, W, S = 128, 8, 2, 2, 70, 300
+    layers = _mixed_layers(W)
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[S + 4] * B, kv_dtype="bf16", out_dtype="f32")
+    ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
+    kv = {}
+    for li in range(len(layers)):
+        wr = lay.writer_of(li)
+        if wr == li:
+            kv[li] = ((wl.randn(8100 + li, (B, S, Hkv, d), torch.float32, DEV) * gain).to(torch.bfloat16),
+                      wl.randn(8150 + li, (B, S, Hkv, d), torch.bfloat16, DEV))
+        q = (wl.randn(8200 + li, (B, S, Hq, d), torch.float32, DEV) * gain).to(torch.bfloat16)
+        k, v = kv[wr]
+        out = lay.prefill(li, q, k, v)
+        ref = ora.prefill(li, to_f64(q), to_f64(k) if wr == li else None, to_f64(v) if wr == li else None)
+        assert_matches(out, ref, "bf16", "prefill layer %d gain %g" % (li, gain))
+    for t in range(3):
+        for li in range(len(layers)):
+            q = (wl.randn(8300 + 10 * t + li, (B, Hq, d), torch.float32, DEV) * gain).to(torch.bfloat16)
+            if lay.writer_of(li) == li:
+                k = (wl.randn(8400 + 10 * t + li, (B, Hkv, d), torch.float32, DEV) * gain).to(torch.bfloat16)
+                v = wl.randn(8500 + 10 * t + li, (B, Hkv, d), torch.bfloat16, DEV)
+                ora.append(li, to_f64(k), to_f64(v))
+                out = lay.append_decode(li, k, v, q)
+            else:
+                out = lay.decode(li, q)
+            assert_matches(out, ora.decode(li, to_f64(q)), "bf16", "decode %d layer %d gain %g" % (t, li, gain))
+    lay.close()
