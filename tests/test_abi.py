@@ -112,3 +112,16 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.returncode == 2
     assert "one GPU only" in r.stderr
     assert r.stdout.strip() == ""
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/mixattn.h compiles as C99 on its own and declares every exported entry point."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "use_header.c"
+    refs = "\n".join("  (void)&%s;" % n for n in mx.EXPORTS)
+    src.write_text('#include "mixattn.h"\nint main(void) {\n%s\n  return 0;\n}\n' % refs)
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
+                        "-I", os.path.join(root, "include"), str(src)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stderr
