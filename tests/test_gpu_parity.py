@@ -833,3 +833,23 @@ def test_peaked_and_flat_softmax(mx, gain):
                 out = lay.decode(li, q)
             assert_matches(out, ora.decode(li, to_f64(q)), "bf16", "decode %d layer %d gain %g" % (t, li, gain))
     lay.close()
+
+
+# --------------------------------------------------------------------------- the boundary from plain C
+def test_c_program_through_the_abi(tmp_path):
+    """tests/c/abi_smoke.c (built by __graft_entry__.build()): creates a layout, appends and decodes through the
+    C ABI with HIP runtime memory, and checks a closed form (equal keys -> mean of the attended values)."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pkg = os.path.join(root, "paper_2409_15012_amd")
+    exe = os.path.join(pkg, "abi_smoke")
+    if not os.path.exists(exe):  # the library is there (the fixture loaded it): link the small host program against it
+        exe = str(tmp_path / "abi_smoke")
+        subprocess.check_call(["gcc", "-std=c99", "-O1", "-I", os.path.join(root, "include"), "-I", "/opt/rocm/include",
+                               os.path.join(root, "tests", "c", "abi_smoke.c"), "-o", exe, "-L", pkg, "-lmixattn",
+                               "-L", "/opt/rocm/lib", "-lamdhip64", "-lm", "-Wl,-rpath," + pkg,
+                               "-Wl,-rpath,/opt/rocm/lib"])
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "abi smoke ok" in r.stdout
