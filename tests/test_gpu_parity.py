@@ -844,7 +844,7 @@ def test_c_program_through_the_abi(tmp_path):
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     pkg = os.path.join(root, "paper_2409_15012_amd")
     exe = os.path.join(pkg, "abi_smoke")
-    if not os.path.exists(exe):  # the library is there (the fixture loaded it): link the small host program against it
+    if not os.path.exists(exe):  # only the library came along: link the small host program against it here
         exe = str(tmp_path / "abi_smoke")
         subprocess.check_call(["gcc", "-std=c99", "-O1", "-I", os.path.join(root, "include"), "-I", "/opt/rocm/include",
                                os.path.join(root, "tests", "c", "abi_smoke.c"), "-o", exe, "-L", pkg, "-lmixattn",
