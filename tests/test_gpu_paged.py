@@ -41,8 +41,9 @@ def _check_full_cache(lay, ora, layer, heads):
     assert lay.device_lens(ci) == [ora.seq_len(layer, b) for b in range(lay.batch)]
 
 
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("page_tokens", [32, 64, 256, 1024])
-def test_paged_decode_and_prefill_equal_contiguous_and_oracle(mx, page_tokens):
+def test_paged_decode_and_prefill_equal_contiguous_and_oracle(mx, page_tokens, out_dtype):
     Hq, Hkv, W, B = 8, 2, 48, 3
     layers = _layers(W)
     lens = [5, 700, 257]
@@ -50,8 +51,8 @@ def test_paged_decode_and_prefill_equal_contiguous_and_oracle(mx, page_tokens):
     steps = 3
     cap = [lens[b] + chunk[b] + steps for b in range(B)]
     pool = sum((c + page_tokens - 1) // page_tokens for c in cap) * page_tokens
-    lays = [mx.Layout(layers, B, Hq, Hkv, D, capacity=cap, kv_dtype="bf16", out_dtype="f32"),
-            mx.Layout(layers, B, Hq, Hkv, D, capacity=cap, kv_dtype="bf16", out_dtype="f32",
+    lays = [mx.Layout(layers, B, Hq, Hkv, D, capacity=cap, kv_dtype="bf16", out_dtype=out_dtype),
+            mx.Layout(layers, B, Hq, Hkv, D, capacity=cap, kv_dtype="bf16", out_dtype=out_dtype,
                       page_tokens=page_tokens, pool_tokens=pool)]
     ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, D)
     for li in (0, 1):

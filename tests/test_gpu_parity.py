@@ -141,13 +141,14 @@ def test_bf16_decode_bf16_output(mx):
 
 
 # --------------------------------------------------------------------------- MFMA prefill, every workgroup shape
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("waves,heads", [(4, 1), (4, 2), (4, 4), (8, 1), (8, 2), (8, 4)])
-def test_bf16_prefill_workgroup_shapes(mx, waves, heads):
+def test_bf16_prefill_workgroup_shapes(mx, waves, heads, out_dtype):
     """The MFMA prefill kernel with 4 or 8 wavefronts serving 1, 2 or 4 query heads of a KV head per workgroup:
     same results for every shape (S spans several query tiles of every shape and ends ragged)."""
     d, S, W, Hq, Hkv, B = 128, 333, 96, 8, 2, 2
     layers = _mixed_layers(W)
-    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[S + 2] * B, kv_dtype="bf16", out_dtype="f32")
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[S + 2] * B, kv_dtype="bf16", out_dtype=out_dtype)
     lay.set_param(mx.PARAM_PREFILL_WAVES, waves)
     lay.set_param(mx.PARAM_PREFILL_HEADS, heads)
     ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
@@ -169,15 +170,16 @@ def test_bf16_prefill_workgroup_shapes(mx, waves, heads):
 
 
 # --------------------------------------------------------------------------- bf16 prefill, small shapes
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("S,W,Hq,Hkv,B", [
     (1, 64, 8, 2, 1), (31, 48, 8, 2, 2), (100, 48, 8, 2, 2), (129, 64, 4, 4, 1), (300, 200, 8, 2, 2),
     (700, 100, 8, 1, 1), (257, 1024, 6, 2, 1), (70, 1, 8, 2, 2), (130, 2, 8, 2, 1), (96, 31, 8, 2, 1),
 ])
 @pytest.mark.parametrize("simple", [0, 1])
-def test_bf16_prefill_then_decode_against_oracle(mx, S, W, Hq, Hkv, B, simple):
+def test_bf16_prefill_then_decode_against_oracle(mx, S, W, Hq, Hkv, B, simple, out_dtype):
     d = 128
     layers = _mixed_layers(W)
-    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[S + 2] * B, kv_dtype="bf16", out_dtype="f32")
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[S + 2] * B, kv_dtype="bf16", out_dtype=out_dtype)
     lay.set_param(mx.PARAM_PREFILL_SIMPLE, simple)
     ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
     seed = 9000 + S * 7 + W
@@ -338,6 +340,7 @@ def test_error_paths_leave_state_untouched(mx):
     lay.close()
 
 
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("Hq,Hkv,W,lens,chunk", [
     (8, 2, 64, [1, 31, 32, 33, 63, 64, 65, 100, 257, 1000], 0),   # tokens landing first/last in a block, ring wrap
     (8, 2, 48, [5, 47, 48, 49, 95, 96, 700], 32),                 # window not a multiple of the block
@@ -346,13 +349,13 @@ def test_error_paths_leave_state_untouched(mx):
     (8, 2, 1, [1, 5, 64], 0),                                      # window of one key
     (8, 2, 2, [1, 2, 31, 32, 33], 0),
 ])
-def test_fused_append_decode_against_oracle(mx, Hq, Hkv, W, lens, chunk):
+def test_fused_append_decode_against_oracle(mx, Hq, Hkv, W, lens, chunk, out_dtype):
     """mixattn_append_decode == append + decode: outputs against the oracle, cache rows and lengths bit-exact,
     and interchangeable with the two-call form from step to step."""
     B, d = len(lens), 128
     layers = _mixed_layers(W)
     steps = 5
-    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[n + steps for n in lens], kv_dtype="bf16", out_dtype="f32")
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[n + steps for n in lens], kv_dtype="bf16", out_dtype=out_dtype)
     lay.set_param(mx.PARAM_CHUNK_KEYS, chunk)
     ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
     seed = 7000 + Hq * 31 + W
@@ -403,14 +406,15 @@ def test_fused_append_decode_row_major_and_capacity(mx):
     lay.close()
 
 
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("kvd,d,Hq,Hkv", [("bf16", 128, 8, 2), ("f32", 64, 4, 2)])
-def test_sliding_layers_reading_a_full_cache(mx, kvd, d, Hq, Hkv):
+def test_sliding_layers_reading_a_full_cache(mx, kvd, d, Hq, Hkv, out_dtype):
     """Mixed-kind sharing group: sliding layers (two different windows) read the cache of a standard layer."""
     tdt = torch.bfloat16 if kvd == "bf16" else torch.float32
     layers = [(0, 0, 0), (1, 100, 0), (1, 33, 0), (1, 64, 1), (0, 0, 0)]
     for S, lens_extra in ((1, 3), (70, 4), (300, 3)):
         B = 2
-        lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[S + lens_extra] * B, kv_dtype=kvd, out_dtype="f32")
+        lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[S + lens_extra] * B, kv_dtype=kvd, out_dtype=out_dtype)
         lay.set_param(mx.PARAM_CHUNK_KEYS, 64 if S > 100 else 0)
         ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
         kv = {}
@@ -440,13 +444,14 @@ def test_sliding_layers_reading_a_full_cache(mx, kvd, d, Hq, Hkv):
         lay.close()
 
 
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("kvd,d,Hq,Hkv,W,chunks", [
     ("bf16", 128, 8, 2, 64, [40, 1, 31, 100, 200]),     # chunk edges inside blocks, chunks longer than the window
     ("bf16", 128, 8, 2, 100, [300, 17, 129]),
     ("bf16", 128, 4, 4, 1024, [700, 500, 90]),          # window longer than the first chunks
     ("f32", 64, 4, 2, 24, [10, 1, 50, 7]),              # scalar path
 ])
-def test_chunked_prefill_against_oracle(mx, kvd, d, Hq, Hkv, W, chunks):
+def test_chunked_prefill_against_oracle(mx, kvd, d, Hq, Hkv, W, chunks, out_dtype):
     """A prompt fed in chunks: every chunk's rows against the oracle, caches bit-exact, then decode steps."""
     tdt = torch.bfloat16 if kvd == "bf16" else torch.float32
     tiled = kvd == "bf16"
@@ -454,7 +459,7 @@ def test_chunked_prefill_against_oracle(mx, kvd, d, Hq, Hkv, W, chunks):
     # full (cache 0), sliding writer (1), its reader, sliding reader of the full cache, full reader
     layers = [(0, 0, 0), (1, W, 1), (1, W, 1), (1, W, 0), (0, 0, 0)]
     total = sum(chunks)
-    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[total + 2] * B, kv_dtype=kvd, out_dtype="f32")
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[total + 2] * B, kv_dtype=kvd, out_dtype=out_dtype)
     ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
     seed = 4000 + W
     for ci_, S in enumerate(chunks):
@@ -501,12 +506,13 @@ def test_chunked_prefill_against_oracle(mx, kvd, d, Hq, Hkv, W, chunks):
     lay.close()
 
 
-def test_chunked_prefill_ragged_history(mx):
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
+def test_chunked_prefill_ragged_history(mx, out_dtype):
     """Sequences that already hold different numbers of tokens (bulk-loaded) receive one more chunk."""
     B, Hq, Hkv, d, W, S = 3, 8, 2, 128, 48, 70
     lens = [5, 130, 47]
     layers = [(0, 0, 0), (1, W, 1), (1, W, 1)]
-    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[n + S for n in lens], kv_dtype="bf16", out_dtype="f32")
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[n + S for n in lens], kv_dtype="bf16", out_dtype=out_dtype)
     ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
     for li in (0, 1):
         k = wl.randn(60 + li, (sum(lens), Hkv, d), torch.bfloat16, DEV)
@@ -528,8 +534,9 @@ def test_chunked_prefill_ragged_history(mx):
     lay.close()
 
 
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("kvd,d,Hq,Hkv,W", [("bf16", 128, 8, 2, 48), ("bf16", 128, 8, 2, 200), ("f32", 64, 4, 4, 40)])
-def test_varlen_prefill_against_oracle(mx, kvd, d, Hq, Hkv, W):
+def test_varlen_prefill_against_oracle(mx, kvd, d, Hq, Hkv, W, out_dtype):
     """Chunks of a different length per sequence (packed tensors), twice in a row so that the second call lands on
     ragged histories; one sequence sits out each call.  MFMA path (bf16, d 128) and scalar path (fp32)."""
     layers = [(0, 0, 0), (1, W, 1), (1, W, 1), (0, 0, 0)]
@@ -537,7 +544,7 @@ def test_varlen_prefill_against_oracle(mx, kvd, d, Hq, Hkv, W):
     B = 4
     cap = [sum(c[b] for c in calls) + 1 for b in range(B)]
     tdt = torch.bfloat16 if kvd == "bf16" else torch.float32
-    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=cap, kv_dtype=kvd, out_dtype="f32")
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=cap, kv_dtype=kvd, out_dtype=out_dtype)
     ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
     for ci, lens in enumerate(calls):
         T = sum(lens)
@@ -615,8 +622,9 @@ def test_peaked_flat_and_scaled_inputs(mx, qscale, vscale):
 
 
 # --------------------------------------------------------------------------- ring readers far from their writer
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("W", [48, 200])
-def test_chunked_prefill_with_ring_readers_not_next_to_their_writer(mx, W):
+def test_chunked_prefill_with_ring_readers_not_next_to_their_writer(mx, W, out_dtype):
     """Two rings whose reader layers are interleaved with each other and with a full layer: past the first chunk a
     reader runs from its ring's own staged copy of the chunk (k = v = None), however many other layers ran since."""
     d, Hq, Hkv, B = 128, 8, 2, 3
@@ -624,7 +632,7 @@ def test_chunked_prefill_with_ring_readers_not_next_to_their_writer(mx, W):
     layers = [(1, W, 1), (1, W, 2), (1, W, 1), (0, 0, 3), (1, W, 2), (1, W, 1), (0, 0, 3)]
     chunks = [[70, 5, 33], [1, 130, 64], [40, 0, 97]]
     total = [sum(c[b] for c in chunks) for b in range(B)]
-    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[n + 2 for n in total], kv_dtype="bf16", out_dtype="f32")
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[n + 2 for n in total], kv_dtype="bf16", out_dtype=out_dtype)
     ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
     for ci, lens in enumerate(chunks):
         T = sum(lens)
@@ -661,6 +669,7 @@ def test_chunked_prefill_with_ring_readers_not_next_to_their_writer(mx, W):
 
 
 # --------------------------------------------------------------------------- balanced launches over ragged batches
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("B,Hq,Hkv,max_len,paged", [
     (7, 8, 2, 1000, 0),
     (70, 4, 1, 600, 0),        # more sequences than one wavefront scans at a time
@@ -669,7 +678,7 @@ def test_chunked_prefill_with_ring_readers_not_next_to_their_writer(mx, W):
     (3, 8, 8, 64, 0),          # fewer blocks than workgroups
 ])
 @pytest.mark.parametrize("balanced", [0, 1, 2])
-def test_balanced_decode_over_ragged_batches(mx, B, Hq, Hkv, max_len, paged, balanced):
+def test_balanced_decode_over_ragged_batches(mx, B, Hq, Hkv, max_len, paged, balanced, out_dtype):
     """Full-cache decode with the blocks of all sequences cut into equal runs (balanced = 2: always, 1: when the
     batch is ragged, 0: per-sequence chunks only): same results against the oracle, fused append included."""
     d = 128
@@ -682,7 +691,7 @@ def test_balanced_decode_over_ragged_batches(mx, B, Hq, Hkv, max_len, paged, bal
     kw = {}
     if paged:
         kw = dict(page_tokens=paged, pool_tokens=sum((c + paged - 1) // paged for c in cap) * paged)
-    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=cap, kv_dtype="bf16", out_dtype="f32", **kw)
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=cap, kv_dtype="bf16", out_dtype=out_dtype, **kw)
     lay.set_param(mx.PARAM_BALANCED, balanced)
     ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
     k = wl.randn(4100, (sum(lens), Hkv, d), torch.bfloat16, DEV)
@@ -731,7 +740,7 @@ def test_random_request_traffic_against_oracle(mx, seed):
     paged = int(rng.choice([0, 32, 64]))
     cap = [2240] * B     # 30 calls of at most 70 tokens; a whole number of pages of either size
     kw = dict(page_tokens=paged, pool_tokens=B * 2240) if paged else {}
-    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=cap, kv_dtype="bf16", out_dtype="f32", **kw)
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=cap, kv_dtype="bf16", out_dtype="bf16" if seed % 2 else "f32", **kw)
     lay.set_param(mx.PARAM_BALANCED, int(rng.integers(0, 3)))
     ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
     writers = [li for li in range(len(layers)) if lay.writer_of(li) == li]

@@ -283,6 +283,44 @@ def test_ring_slots_against_a_simulated_ring():
     assert mo.ring_slot(FULL, 0, 123456789012) == 123456789012
 
 
+def test_cache_view_against_simulated_storage():
+    """cache_view (what the GPU cache-content checks iterate over) against storage simulated token by token: a ring
+    of W slots overwritten at p mod W, a list for a standard cache.  Covers a ring's writer and reader, a standard
+    cache's writer and reader, and a sliding reader of a standard cache, which stores nothing of its own: its view
+    is the writer's (every position, slot = position), however small its window."""
+    W, B = 5, 2
+    layers = [(FULL, 0, 0), (SLIDING, W, 1), (SLIDING, W, 1), (FULL, 0, 0), (SLIDING, 3, 0)]
+    st = _stack(layers, B=B, Hq=2, Hkv=2, d=4)
+    rng = np.random.default_rng(77)
+    ring = [[None] * W for _ in range(B)]
+    full = [[] for _ in range(B)]
+    st.load(0, rng.standard_normal((2, 2, 4)), rng.standard_normal((2, 2, 4)), [2, 0])  # sequence 0 starts ahead
+    st.load(1, rng.standard_normal((2, 2, 4)), rng.standard_normal((2, 2, 4)), [2, 0])
+    for p in range(2):
+        ring[0][p % W] = p
+        full[0].append(p)
+    for step in range(17):
+        for li in (0, 1):
+            st.append(li, rng.standard_normal((B, 2, 4)), rng.standard_normal((B, 2, 4)))
+        for b in range(B):
+            p = len(full[b])
+            ring[b][p % W] = p
+            full[b].append(p)
+            want_ring = [(s, ring[b][s]) for s in range(W) if ring[b][s] is not None]
+            want_full = list(enumerate(full[b]))
+            assert st.cache_view(1, b) == want_ring and st.cache_view(2, b) == want_ring
+            assert st.cache_view(0, b) == want_full and st.cache_view(3, b) == want_full
+            assert st.cache_view(4, b) == want_full      # mixed-kind reader: the writer's storage
+            # every listed position is where the slot arithmetic puts it, and its row is the history's row
+            for li in range(len(layers)):
+                wk = layers[st.writer[layers[li][2]]]
+                for slot, pos in st.cache_view(li, b):
+                    assert mo.ring_slot(wk[0], wk[1], pos) == slot
+                assert len(st.cache_view(li, b)) == (min(st.seq_len(li, b), W) if wk[0] == SLIDING else st.seq_len(li, b))
+    st.release_sequence(1)
+    assert st.cache_view(1, 1) == [] and st.cache_view(4, 1) == []
+
+
 def test_kv_accounting_matches_the_section3_ratios():
     # every l layers sharing one cache => 1/l of the caches; a sliding cache holds min(n, s) tokens
     n = 5000
