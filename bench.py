@@ -39,7 +39,6 @@ def parse():
     ap.add_argument("--workload", default="decode32k", choices=["decode32k", "decode4k", "prefill32k", "ragged64", "variants", "gen31k", "serve"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-keys", type=int, default=0)
-    ap.add_argument("--fused-combine", type=int, default=-1)
     ap.add_argument("--prefill-waves", type=int, default=0)
     ap.add_argument("--prefill-heads", type=int, default=0)
     ap.add_argument("--chunks", type=int, default=1, help="prefill32k: feed the prompt in this many equal chunks")
@@ -60,22 +59,40 @@ def parse():
     ap.add_argument("--two-call-append", action="store_true",
                     help="writer layers call append_kv and decode separately instead of append_decode")
     ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
+    ap.add_argument("--graph", type=int, default=-1,
+                    help="decode workloads: 1 = the timed steps are replays of one decode step captured into a HIP graph "
+                         "(the eager figure is reported beside it), 0 = eager launches only, -1 = workload default")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="decode32k: skip the prefill32k and ragged64 legs that the default run adds to its line")
     ap.add_argument("--only", default="", help="profiling aid: 'full' or 'sliding' runs only that layer kind per step")
     ap.add_argument("--copy-calibration", type=int, default=0,
                     help="profiling aid: also run N plain device copies of 1 GiB (known traffic for counter scaling)")
     return ap.parse_args()
 
 
-def _traffic_from_profiles(kernel_tag):
-    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE), stored as text under profiles/."""
+def _source_digest(name):
+    import hashlib
+    with open(os.path.join(ROOT, "paper_2409_15012_amd", "csrc", name), "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()[:16]
+
+
+def _traffic_from_profiles(kernel_tag, source="kernels_decode.hip"):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE) in runs of their own, recorded as
+    text under profiles/ together with a digest of the kernel source they were taken with.  Returns (bytes, note):
+    bytes is None when there is no record or the kernel source has changed since (a stale figure is not reported)."""
     path = os.path.join(ROOT, "profiles", "traffic_%s.txt" % kernel_tag)
+    value, digest = None, None
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":")[1])
+                value = float(line.split(":")[1])
+            if line.startswith("kernel_source_sha256_16:"):
+                digest = line.split(":")[1].strip()
     except OSError:
-        pass
-    return None
+        return None, "no recorded counter run"
+    if digest != _source_digest(source):
+        return None, "recorded counter run (profiles/traffic_%s.txt) is for an older %s" % (kernel_tag, source)
+    return value, "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs recorded in profiles/traffic_%s.txt" % kernel_tag
 
 
 def _paging(page_tokens, capacity):
@@ -124,15 +141,16 @@ def run_decode(args, mx, wl, torch, w, layers=None, label=None):
     dev = "cuda:0"
     layers = layers or w.layers
     B, Hq, Hkv, d = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim
-    total_steps = args.warmup + args.steps
+    use_graph = args.graph == 1 and not args.group_decode
+    total_steps = (args.warmup + args.steps) * (2 if use_graph else 1) + (2 if use_graph else 0)
     # the first timed step decodes at exactly the workload's context length
-    seq_lens = [max(1, n - 1 - args.warmup) for n in w.seq_lens]
+    # (of the graph replays when those are what is timed: the eager steps then run just below it)
+    graph_shift = (args.warmup + args.steps + 1) if use_graph else 0
+    seq_lens = [max(1, n - 1 - args.warmup - graph_shift) for n in w.seq_lens]
     lay, qs, ks, vs = build_decode_stack(mx, wl, torch, layers, B, Hq, Hkv, d, seq_lens, total_steps + 1,
                                          args.out_dtype, dev, w.seed, args.page_tokens)
     if args.chunk_keys:
         lay.set_param(mx.PARAM_CHUNK_KEYS, args.chunk_keys)
-    if args.fused_combine >= 0:
-        lay.set_param(mx.PARAM_FUSED_COMBINE, args.fused_combine)
     out = torch.empty((B, Hq, d), dtype=lay.out_torch, device=dev)
     full_layers = [li for li, t in enumerate(layers) if t[0] == wl.FULL]
     kinds = {"": None, "full": wl.FULL, "sliding": wl.SLIDING}[args.only]
@@ -181,10 +199,32 @@ def run_decode(args, mx, wl, torch, w, layers=None, label=None):
         step(events)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = eager_ms = (t1 - t0) * 1e3 / args.steps
+    graph_ms = None
+    if use_graph:
+        # the same step captured once and replayed: every replay appends one token per sequence and attends one
+        # position further (lengths live on the device; the host is told with account_replays)
+        lay.reserve_steps(2 * args.warmup + args.steps + 1)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()
+        for _ in range(args.warmup):
+            graph.replay()
+            lay.account_replays(1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+            lay.account_replays(1)
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        ms_per_step = graph_ms
+        del graph
 
     # logical KV bytes of one step, taken at the mid-point length (n grows by one per step)
-    ctx_lens = [n + args.warmup + 1 + args.steps // 2 for n in seq_lens]
+    ctx_lens = [n + args.warmup + 1 + graph_shift + args.steps // 2 for n in seq_lens]
     per_tok = 2 * Hkv * d * 2
     kv_step = 0
     kv_full_launch = 0
@@ -199,6 +239,7 @@ def run_decode(args, mx, wl, torch, w, layers=None, label=None):
     qo_bytes = B * Hq * d * (2 + (2 if args.out_dtype == "bf16" else 4))
     full_ms = [e0.elapsed_time(e1) for (_, e0, e1) in events]
     res = {
+        "eager_ms_per_step": eager_ms, "graph_ms_per_step": graph_ms,
         "ms_per_step": ms_per_step,
         "tokens_per_s": B / (ms_per_step * 1e-3),
         "kv_bytes_per_step": kv_step,
@@ -261,11 +302,12 @@ def cpu_baseline_decode(wl, torch, w, budget_s=15.0):
     n_slide = len(w.layers) - n_full
     step_s = w.batch * w.n_kv_heads * (n_full * t_full + n_slide * t_slide)
     return {
-        "value": w.batch / step_s, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+        "value": w.batch / step_s, "unit": "tokens/s", "cores": threads, "host_cores": os.cpu_count(), "kind": "oracle",
         "sample": "1 sequence x 1 KV head (%d query heads): one full-layer decode at n=%d and one sliding-layer "
                   "decode at W=%d, %d repetitions (%.1f s); scaled linearly to batch %d x %d KV heads x "
-                  "(%d full + %d sliding layers)" % (G, n, W, reps, time.perf_counter() - t_start, w.batch,
-                                                      w.n_kv_heads, n_full, n_slide),
+                  "(%d full + %d sliding layers); cores = threads the oracle's numpy calls kept busy (CPU time / "
+                  "wall time), host_cores = os.cpu_count() of the box"
+                  % (G, n, W, reps, time.perf_counter() - t_start, w.batch, w.n_kv_heads, n_full, n_slide),
     }
 
 
@@ -481,6 +523,46 @@ def run_serving(args, mx, wl, torch, layers, label):
     return r
 
 
+def ragged_comparison(args, mx, wl, torch, warmup, steps, cycle_caches):
+    """Configuration 4: the MixAttention stack next to the standard 24-layer stack on a ragged batch of 64 (context
+    lengths uniform in [1024, 65536]).  cycle_caches = 0: the standard stack is built whole (24 private caches, about
+    209 GB).  cycle_caches = n > 0: it is timed as 24 full-attention layers that cycle over n distinct caches (n of
+    them append, the others only read); every cache is far larger than the 256 MB last-level cache, so the HBM
+    traffic of a step is that of 24 private caches, and its KV bytes are computed from the lengths.  -1: not run."""
+    w = wl.config(4)
+    a = argparse.Namespace(**vars(args))
+    a.warmup, a.steps, a.only, a.group_decode = warmup, steps, "", False
+    if a.graph < 0:
+        a.graph = 1
+    r_mix = run_decode(a, mx, wl, torch, w)
+    per_tok = 2 * w.n_kv_heads * w.head_dim * 2
+    ctx = sum(w.seq_lens)
+    res = {"workload": w.name, "sum_context": int(ctx), "steps": steps, "warmup": warmup,
+           "mix_ms_per_step": r_mix["ms_per_step"], "mix_eager_ms_per_step": r_mix["eager_ms_per_step"],
+           "mix_tokens_per_s": r_mix["tokens_per_s"], "mix_logical_GBps": r_mix["logical_gbs"],
+           "mix_kv_bytes_read_per_step": r_mix["kv_bytes_per_step"], "mix_kv_bytes_resident": r_mix["kv_bytes_resident"],
+           "mix_full_layer_ms": r_mix["full_layer_ms"],
+           "mix_full_layer_GBps": r_mix["full_layer_bytes"] / (r_mix["full_layer_ms"] * 1e-3) / 1e9}
+    if cycle_caches < 0:
+        return res
+    torch.cuda.empty_cache()
+    if cycle_caches == 0:
+        layers, how = wl.layout_full24(), "24 private caches, built whole"
+    else:
+        layers = [(wl.FULL, 0, i % cycle_caches) for i in range(24)]
+        how = ("24 full-attention launches per step cycling over %d distinct caches of %.1f GB each (each far larger "
+               "than the last-level cache, so HBM traffic equals that of 24 private caches); KV bytes computed from "
+               "the lengths" % (cycle_caches, ctx * per_tok / 1e9))
+    r_std = run_decode(a, mx, wl, torch, w, layers=layers)
+    res.update({"standard_ms_per_step": r_std["ms_per_step"], "standard_eager_ms_per_step": r_std["eager_ms_per_step"],
+                "standard_logical_GBps": r_std["logical_gbs"], "standard_how": how,
+                "standard_kv_bytes_read_per_step": r_std["kv_bytes_per_step"],
+                "standard_kv_bytes_resident": 24 * ctx * per_tok,
+                "step_time_ratio_standard_over_mix": r_std["ms_per_step"] / r_mix["ms_per_step"],
+                "kv_bytes_ratio_standard_over_mix": 24 * ctx * per_tok / r_mix["kv_bytes_resident"]})
+    return res
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -500,6 +582,8 @@ def main():
             "vs_baseline": None, "dtype": "bf16", "data": "synthetic"}
     if args.workload in ("decode32k", "decode4k"):
         w = wl.config(2 if args.workload == "decode32k" else 1)
+        if args.graph < 0:
+            args.graph = 1
         r = run_decode(args, mx, wl, torch, w)
         line = dict(base)
         line.update({
@@ -510,7 +594,10 @@ def main():
                        "layers": "24: 0,12 full; 22 sliding in groups {1-4,5-8,9-11},{13-16,17-20,21-23}",
                        "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
                        "out_dtype": args.out_dtype, "only": args.only or "all", "page_tokens": args.page_tokens,
-                       "group_decode": bool(args.group_decode)},
+                       "group_decode": bool(args.group_decode),
+                       "step": ("one HIP-graph replay of the captured step (8 fused append+decode launches, 16 decode "
+                                "launches)" if r["graph_ms_per_step"] else "eager launches")},
+            "eager_ms_per_step": r["eager_ms_per_step"], "graph_ms_per_step": r["graph_ms_per_step"],
             "kv_bytes_read_per_step": r["kv_bytes_per_step"],
             "kv_bytes_resident": r["kv_bytes_resident"],
             "decode_attn_logical_GBps": r["logical_gbs"],
@@ -518,11 +605,34 @@ def main():
         })
         if r["full_layer_ms"]:
             ach = r["full_layer_bytes"] / (r["full_layer_ms"] * 1e-3) / 1e9
+            traffic, traffic_note = _traffic_from_profiles("decode_full_%s" % w.name)
             line["roofline"] = {"kernel": "decode_tiled_kernel<out, full, fused append> (one full-attention layer; plus its combine launch when split)",
                                 "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                 "frac": ach / HBM_PEAK_GBS, "launch_ms": r["full_layer_ms"],
                                 "bytes_per_launch": r["full_layer_bytes"],
-                                "traffic": _traffic_from_profiles("decode_full_%s" % w.name)}
+                                "traffic": traffic, "traffic_source": traffic_note}
+        if args.workload == "decode32k" and not args.headline_only and not args.only and not args.group_decode:
+            # the other two measurements the metric names, each on its own configuration, in the same run
+            try:
+                pa = argparse.Namespace(**vars(args))
+                pa.warmup, pa.steps, pa.chunks = 1, 3, 1
+                wp = wl.config(3)
+                rp = run_prefill(pa, mx, wl, torch, wp)
+                line["prefill"] = {
+                    "workload": wp.name, "ms": rp["ms_per_step"], "tflops": rp["tflops"], "useful_flops": rp["flops"],
+                    "full_layer_ms": rp["full_layer_ms"],
+                    "full_layer_tflops": rp["full_layer_flops"] / (rp["full_layer_ms"] * 1e-3) / 1e12,
+                    "full_layer_frac_of_2.5PF": rp["full_layer_flops"] / (rp["full_layer_ms"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                    "frac_of_2.5PF": rp["tflops"] / MFMA_BF16_PEAK_TFLOPS, "steps": pa.steps, "warmup": pa.warmup,
+                    "note": "24-layer stack, batch 1, 32768-token prompt, unmasked pairs only; full_layer = layer 0 incl. cache commit"}
+            except Exception as e:  # reported, never hidden
+                line["prefill"] = {"error": repr(e)}
+            torch.cuda.empty_cache()
+            try:
+                line["ragged64"] = ragged_comparison(args, mx, wl, torch, warmup=2, steps=10, cycle_caches=3)
+            except Exception as e:
+                line["ragged64"] = {"error": repr(e)}
+            torch.cuda.empty_cache()
         if not args.no_cpu_baseline:
             line["cpu_baseline"] = cpu_baseline_decode(wl, torch, w)
     elif args.workload == "prefill32k":
@@ -599,18 +709,16 @@ def main():
             line["total_time_ratio_standard_over_mix"] = r_std["total_s"] / r_mix["total_s"]
             line["kv_bytes_ratio_standard_over_mix"] = r_std["kv_bytes_allocated"] / r_mix["kv_bytes_allocated"]
     else:  # ragged64
+        r = ragged_comparison(args, mx, wl, torch, warmup=args.warmup, steps=args.steps,
+                              cycle_caches=0 if not args.skip_standard else -1)
         w = wl.config(4)
-        r_mix = run_decode(args, mx, wl, torch, w)
-        r_full = r_mix if args.skip_standard else run_decode(args, mx, wl, torch, w, layers=wl.layout_full24())
         line = dict(base)
         line.update({
             "metric": "decode tokens/s, ragged batch 64, MixAttention stack (standard 24-layer stack alongside)",
-            "value": r_mix["tokens_per_s"], "unit": "tokens/s", "ms_per_step": r_mix["ms_per_step"],
+            "value": r["mix_tokens_per_s"], "unit": "tokens/s", "ms_per_step": r["mix_ms_per_step"],
             "config": {"workload": w.name, "batch": w.batch, "context": "uniform[1024,65536] seeded",
                        "sum_context": int(sum(w.seq_lens)), "window": 1024, "out_dtype": args.out_dtype},
-            "mix": r_mix, "standard": r_full,
-            "step_time_ratio_standard_over_mix": r_full["ms_per_step"] / r_mix["ms_per_step"],
-            "kv_bytes_ratio_standard_over_mix": r_full["kv_bytes_resident"] / r_mix["kv_bytes_resident"],
+            "ragged64": r,
         })
     print(json.dumps(line))
 

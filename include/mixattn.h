@@ -19,9 +19,15 @@
  *  - One layout is used by one host thread at a time, with the device that was current when it was created
  *    still current.
  *  - The layout owns its caches and scratch; they are allocated in
- *    mixattn_create_layout and freed in mixattn_destroy_layout.
- *  - Sequence lengths live on the device and are mirrored on the host without any
- *    device-to-host copy: every append advances every sequence by exactly one.
+ *    mixattn_create_layout and freed in mixattn_destroy_layout.  The one exception is
+ *    the staging area of prompt chunks (MFMA path), which mixattn_reserve_prefill sizes
+ *    once; a mixattn_prefill* call that finds it too small grows it (this synchronises
+ *    the device and allocates) before it changes anything else.  No other hot call
+ *    allocates or synchronises.
+ *  - Sequence lengths live on the device, at addresses that never change, and are
+ *    mirrored on the host without any device-to-host copy: every append advances every
+ *    sequence by exactly one.  A decode step can therefore be captured into a HIP graph
+ *    and replayed (mixattn_reserve_steps, mixattn_account_replays).
  *
  * Tensor layouts (row-major, contiguous, element type = config.kv_dtype unless noted)
  *  decode   q   [batch, n_q_heads, head_dim]
@@ -168,13 +174,13 @@ int mixattn_decode_group(mixattn_layout* L, const int32_t* layers, int n_layers,
    every n_b grows by seq_len.  Reader layer: runs after its writer's call for the same chunk (its cache then holds
    n_b >= seq_len tokens, the last seq_len being the chunk); pass the writer's k, v again (attended over, not
    stored).  On the MFMA path (bf16, head_dim 128) a reader may instead pass k = v = NULL to reuse the tile-format
-   copy of the chunk that a prefill call for the same cache and seq_len staged (ORDER when there is none).  A
-   SLIDING cache that has readers keeps that copy to itself until its next chunk, append, load or release, so its
-   readers may come at any later point of the layer loop; all other caches share one staging area, which holds the
-   chunk of whichever of them ran prefill last.  Passing NULL is the cheap way to run the readers of a sharing
+   copy of the chunk that its writer's prefill call staged (ORDER when there is none, or it was for other lengths).
+   Every cache keeps that copy to itself until its next chunk, append, load or release, so its readers may come at
+   any later point of the layer loop.  Passing NULL is the cheap way to run the readers of a sharing
    group, and the only way for readers of a SLIDING cache past the first chunk (the writer's commit has
    overwritten ring slots their first rows need; ORDER if k, v are passed there, and on the scalar path).  On the
-   MFMA path V is staged as fp16 (values beyond +-65504 saturate).  Errors: ORDER, CAPACITY, NULL. */
+   MFMA path V is staged as fp16 (values beyond +-65504 saturate).  Errors: ORDER, CAPACITY, NULL, ALLOC (only when
+   the staging area has to grow, see mixattn_reserve_prefill; lengths and caches are then unchanged). */
 int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, const void* v, void* out,
                     int seq_len, void* stream);
 
@@ -187,6 +193,30 @@ int mixattn_prefill(mixattn_layout* L, int layer, const void* q, const void* k, 
    the same cache and the same seq_lens.  Errors: ORDER (negative or all-zero seq_lens, ...), CAPACITY, NULL. */
 int mixattn_prefill_varlen(mixattn_layout* L, int layer, const void* q, const void* k, const void* v, void* out,
                            const int32_t* seq_lens, void* stream);
+
+/* Sizes the staging areas of prompt chunks for chunks of up to max_chunk_tokens tokens per sequence (MFMA path; a
+   no-op otherwise): per standard cache an fp16 copy of V for capacity[b] tokens, per sliding cache K and V for
+   window - 1 + max_chunk_tokens tokens.  Synchronises the device and allocates; call it once after creating the
+   layout, and no later mixattn_prefill / mixattn_prefill_varlen call with chunks up to that length allocates or
+   synchronises.  Errors: ORDER (max_chunk_tokens < 1), ALLOC (areas sized so far are kept). */
+int mixattn_reserve_prefill(mixattn_layout* L, int max_chunk_tokens);
+
+/* Decode steps captured into a HIP graph (Section 4 measures a serving engine, which replays its decode step this
+   way).  All kernel arguments of a decode step are fixed addresses and the kernels take the sequence lengths from
+   device memory, so a stream capture around one step (every writer layer's mixattn_append_decode or mixattn_append_kv,
+   every layer's decode) can be replayed, each replay appending one token per sequence and attending one position
+   further.  The host side is told about the replays with these two calls:
+   mixattn_reserve_steps: checks that every sequence can take `steps` more tokens (CAPACITY otherwise, nothing changed)
+   and gives paged caches the pages for them now (their table entries are enqueued on `stream`), because a replay
+   cannot reserve.  Call it before the capture with steps = 1 + the number of replays planned.
+   mixattn_account_replays: the captured calls themselves count as one step on the host; after launching the graph
+   r times call this with steps = r - 1 (or once per further launch with 1) so that the host lengths match the
+   device again (CAPACITY if that exceeds a capacity: the replays were not reserved).  No device work.
+   Launch plans (split-K chunking, balanced runs) are frozen at capture; the kernels adapt them to the lengths they
+   find, so results stay correct while the sequences grow, and re-capturing every few thousand tokens restores the
+   best plan.  A sequence at capacity takes no further token on the device either (its length stays). */
+int mixattn_reserve_steps(mixattn_layout* L, int steps, void* stream);
+int mixattn_account_replays(mixattn_layout* L, int steps);
 
 /* Bulk fill of an empty cache without attention (sets up decode workloads and ragged batches).  Writer layers
    only.  k, v: device, packed [sum(seq_lens), n_kv_heads, head_dim]; seq_lens: host [batch], each >= 0.  n_b
@@ -221,18 +251,18 @@ int64_t mixattn_step_read_bytes(const mixattn_layout* L, int layer);
 /* ---- tuning knobs (defaults are chosen per call from the shapes) ---- */
 typedef enum {
   MIXATTN_PARAM_CHUNK_KEYS = 0, /* split-K chunk length in keys for decode (multiple of 32; 0 = automatic) */
-  MIXATTN_PARAM_FUSED_COMBINE = 1, /* 1: the last workgroup of a (sequence, kv head) merges the split-K partials
-                                      itself (partials exchanged with device-coherent accesses, no fence);
-                                      0 (default): separate combine launch, which measures faster */
+  /* 1 is not used */
   MIXATTN_PARAM_PREFILL_SIMPLE = 2, /* 1: force the scalar prefill kernel (testing) */
   MIXATTN_PARAM_PREFILL_WAVES = 3,  /* wavefronts per MFMA prefill workgroup: 4, 8, or 0 = by layer kind (8 full, 4 sliding) */
   MIXATTN_PARAM_PREFILL_HEADS = 4,  /* query heads of one KV head served by one MFMA prefill workgroup: 1, 2, 4, or
                                        0 = as many as divide the group size */
-  MIXATTN_PARAM_BALANCED = 5        /* decode over full caches: cut the blocks of all (sequence, kv head) streams,
+  MIXATTN_PARAM_BALANCED = 5,       /* decode over full caches: cut the blocks of all (sequence, kv head) streams,
                                        laid end to end, into equal runs, one per workgroup, instead of cutting
                                        every sequence by itself.  1 (default): when the longest sequence exceeds
                                        1.25 x the mean or the sequences have to be cut anyway; 0: never; 2: always.
                                        Ignored when CHUNK_KEYS is set and for batches above 1024. */
+  MIXATTN_PARAM_TEST_FAIL_ALLOC = 6 /* testing aid, per calling thread (the layout argument is not used): n > 0 makes
+                                       the n-th device allocation from now on fail with ALLOC; 0 switches it off */
 } mixattn_param;
 int mixattn_set_param(mixattn_layout* L, int param, int64_t value);
 int mixattn_get_param(const mixattn_layout* L, int param, int64_t* value);

@@ -18,13 +18,14 @@ _lib = None
 
 FULL, SLIDING = 0, 1
 F32, BF16 = 0, 1
-PARAM_CHUNK_KEYS, PARAM_FUSED_COMBINE, PARAM_PREFILL_SIMPLE, PARAM_PREFILL_WAVES, PARAM_PREFILL_HEADS = 0, 1, 2, 3, 4
-PARAM_BALANCED = 5
+PARAM_CHUNK_KEYS, PARAM_PREFILL_SIMPLE, PARAM_PREFILL_WAVES, PARAM_PREFILL_HEADS = 0, 2, 3, 4
+PARAM_BALANCED, PARAM_TEST_FAIL_ALLOC = 5, 6
 
 EXPORTS = [
     "mixattn_validate_config", "mixattn_create_layout", "mixattn_create_layout_paged", "mixattn_destroy_layout",
     "mixattn_reset", "mixattn_release_sequence",
-    "mixattn_append_kv", "mixattn_decode", "mixattn_append_decode", "mixattn_decode_group", "mixattn_prefill", "mixattn_prefill_varlen",
+    "mixattn_append_kv", "mixattn_decode", "mixattn_append_decode",
+    "mixattn_reserve_prefill", "mixattn_reserve_steps", "mixattn_account_replays", "mixattn_decode_group", "mixattn_prefill", "mixattn_prefill_varlen",
     "mixattn_load_kv", "mixattn_n_caches",
     "mixattn_cache_of", "mixattn_seq_len", "mixattn_slot_of", "mixattn_slot_for", "mixattn_read_cache",
     "mixattn_read_device_lens", "mixattn_kv_bytes_allocated", "mixattn_kv_bytes_live", "mixattn_step_read_bytes",
@@ -69,6 +70,9 @@ def load():
     lib.mixattn_reset.argtypes = [vp, vp]
     lib.mixattn_append_kv.argtypes = [vp, i32, vp, vp, vp]
     lib.mixattn_decode.argtypes = [vp, i32, vp, vp, vp]
+    lib.mixattn_reserve_prefill.argtypes = [vp, i32]
+    lib.mixattn_reserve_steps.argtypes = [vp, i32, vp]
+    lib.mixattn_account_replays.argtypes = [vp, i32]
     lib.mixattn_append_decode.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     lib.mixattn_decode_group.argtypes = [vp, C.POINTER(C.c_int32), i32, vp, vp, vp, vp, vp]
     lib.mixattn_prefill.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
@@ -202,6 +206,15 @@ class Layout:
             self._dtype_check(out, self.out_torch, (self.batch, self.Hq, self.d))
         self._check(self.lib.mixattn_decode(self.h, layer, _ptr(q), _ptr(out), _stream()), "mixattn_decode")
         return out
+
+    def reserve_prefill(self, max_chunk_tokens: int):
+        self._check(self.lib.mixattn_reserve_prefill(self.h, int(max_chunk_tokens)), "mixattn_reserve_prefill")
+
+    def reserve_steps(self, steps: int):
+        self._check(self.lib.mixattn_reserve_steps(self.h, int(steps), _stream()), "mixattn_reserve_steps")
+
+    def account_replays(self, steps: int):
+        self._check(self.lib.mixattn_account_replays(self.h, int(steps)), "mixattn_account_replays")
 
     def append_decode(self, layer: int, k: torch.Tensor, v: torch.Tensor, q: torch.Tensor,
                       out: Optional[torch.Tensor] = None) -> torch.Tensor:

@@ -18,6 +18,24 @@ hipError_t launch_fill_i32(int32_t* p, int32_t value, int64_t n, hipStream_t s) 
   return hipGetLastError();
 }
 
+// Lengths after a bulk store (a launch of its own: every workgroup of the store reads the old lengths).
+__global__ void advance_lens_kernel(int32_t* lens, const int32_t* src_len, int uniform_len, int batch) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= batch) return;
+  const int add = src_len ? src_len[b] : uniform_len;
+  const int held = lens[b];
+  if (held < 0) {  // idle sequence: new tokens start it at position 0, none leave it idle
+    if (add > 0) lens[b] = add;
+  } else {
+    lens[b] = held + add;
+  }
+}
+
+hipError_t launch_advance_lens(int32_t* lens, const int32_t* src_len, int uniform_len, int batch, hipStream_t s) {
+  hipLaunchKernelGGL(advance_lens_kernel, dim3((batch + 255) / 256), dim3(256), 0, s, lens, src_len, uniform_len, batch);
+  return hipGetLastError();
+}
+
 // Per-sequence tables (first packed row, row count) written by a kernel that carries the values in its arguments:
 // stream-ordered, no host synchronisation and no pinned staging buffer to recycle.
 struct SeqTableChunk {
@@ -206,7 +224,6 @@ __global__ __launch_bounds__(256) void store_tiled_kernel(StoreLaunch a) {
   store_lengths(a, b, n_old, n_new, off);
   const int add = n_new - n_old;
   const int64_t first = a.d_src_first ? a.d_src_first[b] : (int64_t)b * a.uniform_len;
-  if (a.d_lens_out && blk == 0 && h == 0 && threadIdx.x == 0) a.d_lens_out[b] = n_new;
   // a block no token maps to is left untouched (never read: it lies beyond the length)
   const int live = a.window > 0 ? (n_new < a.window ? n_new : a.window) : n_new - off;
   if (blk * kBlockKeys >= live) return;
@@ -304,7 +321,6 @@ __global__ __launch_bounds__(256) void store_rowmajor_kernel(StoreLaunch a) {
   int n_old, n_new, off;
   store_lengths(a, b, n_old, n_new, off);
   const int64_t first = a.d_src_first ? a.d_src_first[b] : (int64_t)b * a.uniform_len;
-  if (a.d_lens_out && blockIdx.x == 0 && h == 0 && threadIdx.x == 0) a.d_lens_out[b] = n_new;
   if (slot >= slots) return;
   const SlotSource src = slot_source(a, slot, n_old, n_new, off);
   if (src.kind != 1) return;

@@ -11,6 +11,7 @@
 // about 16 significant bits at no extra MFMA cost (the columns would otherwise be padding).  Scores, softmax
 // state and accumulators are fp32.  The online-softmax state of a head lives in the lanes of its column, so
 // rescaling the accumulator is lane-local; the only cross-lane traffic per block is two shuffles for the maximum.
+#include <algorithm>
 #include <type_traits>
 
 #include "mixattn_internal.h"
@@ -50,24 +51,17 @@ struct TiledDecodeParams {
   int Hq, Hkv, G;
   float scale_log2;  // softmax scale times log2(e)
   int chunk_blocks, n_chunks;
-  int fused_combine;
-  float* p_acc; float* p_ml; uint32_t* counters;
-  // fused append (writer layers): this step's token, writable cache pointers, length array to receive n + 1
-  const uint16_t* k_new; const uint16_t* v_new; uint16_t* Kw; uint16_t* Vw; int32_t* d_lens_out;
+  // split-K partials: row r, chunk c at (r * chunk_stride + c)
+  float* p_acc; float* p_ml; int chunk_stride;
+  // fused append (writer layers): this step's token, writable cache pointers, the length array once more (the
+  // workgroup that finishes last advances it in place) and the arrival counter of this cache (zero between launches)
+  const uint16_t* k_new; const uint16_t* v_new; uint16_t* Kw; uint16_t* Vw; int32_t* d_lens_rw; uint32_t* arrive;
   // group launch (GROUP): n_group layers of one sharing group in one pass over the ring; layer i's q and out
   // start layer_rows * i rows after the first layer's (a row = one query head of one sequence)
   int n_group; int64_t layer_rows;
-  // balanced launch: sequences in the batch, blocks per workgroup
-  int batch; int share;
+  // sequences in the batch (balanced launches, fused append)
+  int batch;
 };
-
-// device-scope coherent accesses (relaxed atomics): they go past the XCD-private L2
-__device__ inline void coherent_store(float* p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ inline float coherent_load(const float* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
 // merges the split-K partials of one (sequence, query head): thread d handles one output dim
 template <typename OutT>
@@ -105,7 +99,10 @@ __device__ __attribute__((always_inline)) void decode_piece(const TiledDecodePar
   constexpr int kCols = GROUP ? 16 : kMaxGroup;  // head columns that carry results
   constexpr int NW = kDecodeWaves;
   const int n_old = a.d_lens[b];
-  int n = FUSED ? n_old + 1 : n_old;
+  // a fused launch sees the sequence one token longer; a full cache that is at capacity takes no token (the host
+  // refuses such a call; replays of a captured step beyond the reserved capacity end up here)
+  const bool room = FUSED && (RING || n_old < a.d_slots[b]);
+  int n = room ? n_old + 1 : n_old;
   if (RING && n > a.window) n = a.window;
   const int new_slot = RING ? n_old % a.window : n_old;  // where a fused launch puts its token
   const int new_blk = new_slot >> 5, new_key = new_slot & 31;
@@ -261,7 +258,7 @@ __device__ __attribute__((always_inline)) void decode_piece(const TiledDecodePar
   // A fused launch takes the block that receives the new token out of this sequence (the wavefront that owns it
   // handles it after the pipeline, see below), so the steady-state loop stays free of conditional loads.
   const int first = blk0 + wave;
-  const bool own_new = FUSED && new_blk >= blk0 && new_blk < blk1 && ((new_blk - blk0) & (NW - 1)) == wave;
+  const bool own_new = room && new_blk >= blk0 && new_blk < blk1 && ((new_blk - blk0) & (NW - 1)) == wave;
   const int i_new = own_new ? (new_blk - first) / NW : 0x7fffffff;
   const int cnt = (blk1 - blk0 - wave + NW - 1) / NW - (own_new ? 1 : 0);  // may be <= 0
   auto blk_of = [&](int i) { return first + (i + (i >= i_new ? 1 : 0)) * NW; };
@@ -324,7 +321,6 @@ __device__ __attribute__((always_inline)) void decode_piece(const TiledDecodePar
       if (lane < 16) *(u32x4_t*)(Kd + k_tile_offset(new_key, lane * 8)) = *(const u32x4_t*)(kn + lane * 8);
       Vd[v_tile_offset(new_key, lane)] = vn[lane];
       Vd[v_tile_offset(new_key, lane + 64)] = vn[lane + 64];
-      if (h == 0 && lane == 0) a.d_lens_out[b] = n_old + 1;
     }
   }
 
@@ -341,7 +337,6 @@ __device__ __attribute__((always_inline)) void decode_piece(const TiledDecodePar
   __shared__ float s_o[NW][kCols][kTiledDim];
   __shared__ float s_m[NW][kCols];
   __shared__ float s_l[NW][kCols];
-  __shared__ int s_last;
   if (is_hi) {
 #pragma unroll
     for (int nn = 0; nn < 8; ++nn)
@@ -355,7 +350,6 @@ __device__ __attribute__((always_inline)) void decode_piece(const TiledDecodePar
   __syncthreads();
 
   const bool direct = (a.n_chunks == 1);
-  const bool fused = !BALANCED && !direct && a.fused_combine;
   // result row of head column hd: the layer's block of rows, then (sequence, query head)
   auto row_of = [&](int hd) -> int64_t {
     const int gl = GROUP ? hd / G : 0;
@@ -377,57 +371,38 @@ __device__ __attribute__((always_inline)) void decode_piece(const TiledDecodePar
     if (direct) {
       store_out<OutT>((OutT*)a.out + row * kTiledDim + d, acc / L);
     } else {
-      const int64_t pr = row * kMaxChunks + c;
-      if (fused) {  // read by another workgroup of this launch, maybe on another XCD: device-coherent stores
-        coherent_store(a.p_acc + pr * kTiledDim + d, acc);
-        if (d == 0) {
-          coherent_store(a.p_ml + 2 * pr, M);
-          coherent_store(a.p_ml + 2 * pr + 1, L);
-        }
-      } else {
-        a.p_acc[pr * kTiledDim + d] = acc;
-        if (d == 0) {
-          a.p_ml[2 * pr] = M;
-          a.p_ml[2 * pr + 1] = L;
-        }
+      const int64_t pr = row * a.chunk_stride + c;
+      a.p_acc[pr * kTiledDim + d] = acc;
+      if (d == 0) {
+        a.p_ml[2 * pr] = M;
+        a.p_ml[2 * pr + 1] = L;
       }
     }
   }
-  if constexpr (BALANCED) {
-    __syncthreads();  // the shared arrays are written again by this workgroup's next piece
-    return;
-  }
-  if (!fused) return;
+  if constexpr (BALANCED) __syncthreads();  // the shared arrays are written again by this workgroup's next piece
+}
 
-  // ---- fused combine: the workgroup that arrives last for this (sequence, kv head) merges all chunks.
-  // No fence: a device-scope fence writes back and invalidates the whole L2 of the XCD, which throws away the K/V
-  // stream of every other workgroup on it (5x slower).  Instead the partials are written and read with
-  // device-coherent accesses (they bypass the XCD-private L2), each thread waits until its own stores have been
-  // acknowledged, and the arrival counter is a device-scope atomic.
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-  __syncthreads();
-  if (tid == 0) {
-    uint32_t* cnt = a.counters + b * a.Hkv + h;
-    const uint32_t prev = __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    s_last = (prev == (uint32_t)(n_chunks_b - 1));
-    if (s_last) __hip_atomic_store(cnt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next launch
+// Fused append: the lengths are advanced in place by the workgroup of the launch that finishes last.  Every
+// workgroup has read all the lengths it uses before it arrives (they steer its loads, whose results it has consumed),
+// so the one that finds every other arrival counted can overwrite them: no workgroup of this launch reads a length
+// again, and the next launch on the stream sees the new values.  The counter is a device-scope atomic (workgroups of
+// one launch run on several XCDs); the last arriver puts it back to zero for the next launch.  Called by every
+// workgroup of the grid exactly once, from uniform control flow.
+__device__ inline void arrive_and_advance(const TiledDecodeParams& a, uint32_t total_workgroups) {
+  __shared__ int s_is_last;
+  __syncthreads();  // every wavefront of this workgroup is past its reads of the length array
+  if (threadIdx.x == 0) {
+    const uint32_t prev = __hip_atomic_fetch_add(a.arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int last = prev == total_workgroups - 1;
+    if (last) __hip_atomic_store(a.arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_is_last = last;
   }
   __syncthreads();
-  if (!s_last) return;
-  for (int idx = tid; idx < ncols * kTiledDim; idx += NW * 64) {
-    const int hd = idx >> 7, d = idx & 127;
-    const int64_t row = row_of(hd);
-    const float* p_acc = a.p_acc + row * kMaxChunks * kTiledDim;
-    const float* p_ml = a.p_ml + row * kMaxChunks * 2;
-    float M = -INFINITY;
-    for (int cc = 0; cc < n_chunks_b; ++cc) M = fmaxf(M, coherent_load(p_ml + 2 * cc));
-    float L = 0.f, acc = 0.f;
-    for (int cc = 0; cc < n_chunks_b; ++cc) {
-      const float w = fast_exp2(coherent_load(p_ml + 2 * cc) - M);
-      L += coherent_load(p_ml + 2 * cc + 1) * w;
-      acc += coherent_load(p_acc + (int64_t)cc * kTiledDim + d) * w;
+  if (s_is_last) {
+    for (int bb = threadIdx.x; bb < a.batch; bb += blockDim.x) {
+      const int n = a.d_lens_rw[bb];  // idle sequences (negative) stay idle; a full cache at capacity stays as it is
+      if (n >= 0 && (a.window > 0 || n < a.d_slots[bb])) a.d_lens_rw[bb] = n + 1;
     }
-    store_out<OutT>((OutT*)a.out + row * kTiledDim + d, acc / L);
   }
 }
 
@@ -448,42 +423,65 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
   static_assert(!(WINDOWED && (RING || FUSED)), "a windowed reader of a full cache never writes it");
   static_assert(!GROUP || RING, "group launches serve ring caches");
   const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  if (a.d_lens[b] < 0) {  // idle sequence: zero rows, stays idle
+  const int n_held = a.d_lens[b];
+  if (n_held < 0) {  // idle sequence: zero rows, stays idle
     if (c == 0) zero_rows<OutT>(a, b, h, GROUP ? a.n_group : 1);
-    if (FUSED && c == 0 && h == 0 && threadIdx.x == 0) a.d_lens_out[b] = -1;
-    return;
+  } else {
+    int n = n_held + ((FUSED && (RING || n_held < a.d_slots[b])) ? 1 : 0);
+    if (RING && n > a.window) n = a.window;
+    const int nb_total = (n + kBlockKeys - 1) / kBlockKeys;
+    const int lo = (WINDOWED && n > a.attn_window) ? n - a.attn_window : 0;  // first position attended
+    const int fb = lo / kBlockKeys;                                           // first block read
+    const int nb_read = nb_total - fb;
+    // this sequence's blocks are cut into n_chunks_b chunks of equal length (+-1 block), so that workgroups of one
+    // sequence finish together and a sequence a little longer than a multiple of the target does not grow a stub.
+    // Never more chunks than the grid has workgroups for: a launch planned for shorter sequences (a captured step
+    // replayed later) then simply takes longer chunks.
+    const int n_chunks_b = min((nb_read + a.chunk_blocks - 1) / a.chunk_blocks, (int)gridDim.x);
+    if (c < n_chunks_b) {  // uniform for the workgroup
+      const int blk0 = fb + (int)(((int64_t)c * nb_read) / n_chunks_b);
+      const int blk1 = fb + (int)(((int64_t)(c + 1) * nb_read) / n_chunks_b);
+      decode_piece<OutT, RING, FUSED, WINDOWED, GROUP, false>(a, b, h, blk0, blk1, c, n_chunks_b);
+    }
   }
-  int n = a.d_lens[b] + (FUSED ? 1 : 0);
-  if (RING && n > a.window) n = a.window;
-  const int nb_total = (n + kBlockKeys - 1) / kBlockKeys;
-  const int lo = (WINDOWED && n > a.attn_window) ? n - a.attn_window : 0;  // first position attended
-  const int fb = lo / kBlockKeys;                                           // first block read
-  const int nb_read = nb_total - fb;
-  // this sequence's blocks are cut into n_chunks_b chunks of equal length (+-1 block), so that workgroups of one
-  // sequence finish together and a sequence a little longer than a multiple of the target does not grow a stub
-  const int n_chunks_b = (nb_read + a.chunk_blocks - 1) / a.chunk_blocks;
-  if (c >= n_chunks_b) return;  // uniform for the workgroup
-  const int blk0 = fb + (int)(((int64_t)c * nb_read) / n_chunks_b);
-  const int blk1 = fb + (int)(((int64_t)(c + 1) * nb_read) / n_chunks_b);
-  decode_piece<OutT, RING, FUSED, WINDOWED, GROUP, false>(a, b, h, blk0, blk1, c, n_chunks_b);
+  if constexpr (FUSED) arrive_and_advance(a, gridDim.x * gridDim.y * gridDim.z);
 }
 
 // Balanced launch for full caches whose sequences differ in length.  The blocks of all (sequence, kv head) streams,
-// laid end to end in (b, h) order, are cut into gridDim.x runs of a.share blocks: every workgroup streams the same
+// laid end to end in (b, h) order, are cut into gridDim.x runs of `share` blocks: every workgroup streams the same
 // number of blocks whatever the lengths are, and a stream is cut only where a run ends.  Piece c of a stream is the
-// part inside the c-th run that touches it; the combine launch that follows merges the pieces.
+// part inside the c-th run that touches it; the combine launch that follows merges the pieces.  `share` is derived
+// on the device from the lengths and the grid size (balanced_share), so a launch set up for one set of lengths
+// stays correct when they have grown (a captured step replayed later).
 //   s_first[b] = blocks of one kv head held by sequences 0 .. b-1 (built by the first wavefront, a scan over the batch)
 constexpr int kMaxBalancedBatch = 1024;
 
+// blocks a decode reads for a sequence of length n (idle: none); a fused launch counts the token it appends
 template <bool FUSED>
-__device__ inline void scan_block_counts(const int32_t* d_lens, int batch, int* s_first) {
+__device__ inline int blocks_of_length(int n, int slots) {
+  if (n < 0) return 0;
+  return (n + ((FUSED && n < slots) ? 1 : 0) + kBlockKeys - 1) / kBlockKeys;
+}
+
+// Blocks per run: the total spread over the runs, but no stream may fall into more than kMaxChunks pieces (a stream
+// of nb blocks touches at most (nb - 1) / share + 2 runs) and a run keeps every wavefront of its workgroup busy.
+__device__ inline int balanced_share(int64_t total, int max_nb, int runs) {
+  int64_t share = (total + runs - 1) / runs;
+  share = max(share, (int64_t)((max_nb + (kMaxChunks - 2) - 1) / (kMaxChunks - 2)));
+  return (int)max(share, (int64_t)kDecodeMinChunkBlocks);
+}
+
+// s_first[0 .. batch] = exclusive scan of the block counts, *s_max = the largest count
+template <bool FUSED>
+__device__ inline void scan_block_counts(const int32_t* d_lens, const int32_t* d_slots, int batch, int* s_first,
+                                         int* s_max) {
   const int lane = threadIdx.x & 63;
   if (threadIdx.x < 64) {
-    int run = 0;
+    int run = 0, mx = 0;
     for (int b0 = 0; b0 < batch; b0 += 64) {
       const int bb = b0 + lane;
-      int inc = 0;  // an idle sequence (length -1) has no blocks
-      if (bb < batch && d_lens[bb] >= 0) inc = (d_lens[bb] + (FUSED ? 1 : 0) + kBlockKeys - 1) / kBlockKeys;
+      int inc = bb < batch ? blocks_of_length<FUSED>(d_lens[bb], d_slots[bb]) : 0;
+      mx = max(mx, inc);
 #pragma unroll
       for (int o = 1; o < 64; o <<= 1) {
         const int t = __shfl_up(inc, o);
@@ -492,7 +490,12 @@ __device__ inline void scan_block_counts(const int32_t* d_lens, int batch, int* 
       if (bb < batch) s_first[bb + 1] = run + inc;
       run += __shfl(inc, 63);
     }
-    if (lane == 0) s_first[0] = 0;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = max(mx, __shfl_xor(mx, o));
+    if (lane == 0) {
+      s_first[0] = 0;
+      *s_max = mx;
+    }
   }
   __syncthreads();
 }
@@ -507,10 +510,12 @@ __device__ inline int balanced_pieces(int64_t gs, int nb, int share) {
 template <typename OutT, bool FUSED>
 __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_balanced_kernel(TiledDecodeParams a) {
   __shared__ int s_first[kMaxBalancedBatch + 1];
-  scan_block_counts<FUSED>(a.d_lens, a.batch, s_first);
+  __shared__ int s_max;
+  scan_block_counts<FUSED>(a.d_lens, a.d_slots, a.batch, s_first, &s_max);
   const int64_t total = (int64_t)s_first[a.batch] * a.Hkv;
-  const int64_t g0 = (int64_t)blockIdx.x * a.share;
-  const int64_t g1 = min(total, g0 + a.share);
+  const int share = balanced_share(total, s_max, (int)gridDim.x);
+  const int64_t g0 = (int64_t)blockIdx.x * share;
+  const int64_t g1 = min(total, g0 + share);
   // sequence that holds block g0: the last b with s_first[b] * Hkv <= g0 (uniform binary search)
   int b = 0;
   {
@@ -529,53 +534,72 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_balanced_kernel(T
     const int blk1 = (int)min((int64_t)nb, blk0 + (g1 - g));
     const int64_t gs = g - blk0;
     decode_piece<OutT, false, FUSED, false, false, true>(a, b, h, blk0, blk1,
-                                                          blockIdx.x - balanced_first_run(gs, a.share),
-                                                          balanced_pieces(gs, nb, a.share));
+                                                          blockIdx.x - balanced_first_run(gs, share),
+                                                          balanced_pieces(gs, nb, share));
     g += blk1 - blk0;
   }
+  if constexpr (FUSED) arrive_and_advance(a, gridDim.x);
 }
 
+// Merges the pieces of a balanced launch: one workgroup per (sequence, query head), thread d one output dim.  It
+// runs after the decode launch, so a fused append has already advanced the lengths: the block counts it derives
+// from them are the ones the decode launch worked with.  a.n_chunks = number of runs of that launch.
 template <typename OutT>
 __global__ __launch_bounds__(kTiledDim) void combine_balanced_kernel(TiledDecodeParams a) {
   const int hq = blockIdx.x, b = blockIdx.y;
-  const int extra = a.k_new ? 1 : 0;  // the fused launch before this one read the old length array
-  // blocks of one kv head held by the sequences before b
-  __shared__ int s_part[kTiledDim / 64];
-  int before = 0;
-  for (int bb = threadIdx.x; bb < b; bb += kTiledDim)
-    if (a.d_lens[bb] >= 0) before += (a.d_lens[bb] + extra + kBlockKeys - 1) / kBlockKeys;
+  // blocks of one kv head held by the sequences before b, by all sequences, and the largest count
+  __shared__ int s_part[3][kTiledDim / 64];
+  int before = 0, all = 0, mx = 0;
+  for (int bb = threadIdx.x; bb < a.batch; bb += kTiledDim) {
+    const int nb_bb = blocks_of_length<false>(a.d_lens[bb], 0);
+    before += bb < b ? nb_bb : 0;
+    all += nb_bb;
+    mx = max(mx, nb_bb);
+  }
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) before += __shfl_xor(before, o);
-  if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = before;
+  for (int o = 32; o > 0; o >>= 1) {
+    before += __shfl_xor(before, o);
+    all += __shfl_xor(all, o);
+    mx = max(mx, __shfl_xor(mx, o));
+  }
+  if ((threadIdx.x & 63) == 0) {
+    s_part[0][threadIdx.x >> 6] = before;
+    s_part[1][threadIdx.x >> 6] = all;
+    s_part[2][threadIdx.x >> 6] = mx;
+  }
   __syncthreads();
-  before = 0;
+  before = all = mx = 0;
 #pragma unroll
-  for (int w = 0; w < kTiledDim / 64; ++w) before += s_part[w];
-  const int64_t row0 = (int64_t)b * a.Hq + hq;
+  for (int w = 0; w < kTiledDim / 64; ++w) {
+    before += s_part[0][w];
+    all += s_part[1][w];
+    mx = max(mx, s_part[2][w]);
+  }
+  const int64_t row = (int64_t)b * a.Hq + hq;
   if (a.d_lens[b] < 0) {  // idle sequence: no workgroup of the balanced launch touched it
-    store_out<OutT>((OutT*)a.out + row0 * kTiledDim + threadIdx.x, 0.f);
-    if (a.k_new && hq == 0 && threadIdx.x == 0) a.d_lens_out[b] = -1;
+    store_out<OutT>((OutT*)a.out + row * kTiledDim + threadIdx.x, 0.f);
     return;
   }
-  const int nb = (a.d_lens[b] + extra + kBlockKeys - 1) / kBlockKeys;
+  const int share = balanced_share((int64_t)all * a.Hkv, mx, a.n_chunks);
+  const int nb = blocks_of_length<false>(a.d_lens[b], 0);
   const int64_t gs = (int64_t)before * a.Hkv + (int64_t)(hq / a.G) * nb;
-  const int64_t row = (int64_t)b * a.Hq + hq;
-  merge_partials<OutT>(a.p_acc + row * kMaxChunks * kTiledDim, a.p_ml + row * kMaxChunks * 2,
-                       balanced_pieces(gs, nb, a.share), threadIdx.x, (OutT*)a.out + row * kTiledDim);
+  merge_partials<OutT>(a.p_acc + row * a.chunk_stride * kTiledDim, a.p_ml + row * a.chunk_stride * 2,
+                       balanced_pieces(gs, nb, share), threadIdx.x, (OutT*)a.out + row * kTiledDim);
 }
 
+// Merges the chunks of a split launch (runs after it: a fused append has already advanced the lengths).
 template <typename OutT>
 __global__ __launch_bounds__(kTiledDim) void combine_kernel(TiledDecodeParams a) {
   const int hq = blockIdx.x, b = blockIdx.y;
   if (a.d_lens[b] < 0) return;  // idle sequence: the decode launch wrote its zero rows
-  int n = a.d_lens[b] + (a.k_new ? 1 : 0);  // the fused launch before this one read the old length array
+  int n = a.d_lens[b];
   if (a.window > 0 && n > a.window) n = a.window;
   const int nb_total = (n + kBlockKeys - 1) / kBlockKeys;
   const int lo = (a.attn_window > 0 && n > a.attn_window) ? n - a.attn_window : 0;
   const int nb_read = nb_total - lo / kBlockKeys;
-  const int n_chunks_b = (nb_read + a.chunk_blocks - 1) / a.chunk_blocks;
+  const int n_chunks_b = min((nb_read + a.chunk_blocks - 1) / a.chunk_blocks, a.n_chunks);
   const int64_t row = blockIdx.z * a.layer_rows + (int64_t)b * a.Hq + hq;  // z: layer of a group launch
-  merge_partials<OutT>(a.p_acc + row * kMaxChunks * kTiledDim, a.p_ml + row * kMaxChunks * 2, n_chunks_b,
+  merge_partials<OutT>(a.p_acc + row * a.chunk_stride * kTiledDim, a.p_ml + row * a.chunk_stride * 2, n_chunks_b,
                        threadIdx.x, (OutT*)a.out + row * kTiledDim);
 }
 
@@ -589,17 +613,19 @@ hipError_t launch_decode_tiled(const DecodeLaunch& L, hipStream_t s) {
   p.Hq = L.Hq; p.Hkv = L.Hkv; p.G = L.G;
   p.scale_log2 = L.scale * kLog2e;
   p.chunk_blocks = L.chunk_blocks; p.n_chunks = L.n_chunks;
-  p.fused_combine = L.fused_combine;
-  p.p_acc = L.scratch.acc; p.p_ml = L.scratch.ml; p.counters = L.scratch.counters;
   p.k_new = (const uint16_t*)L.k_new; p.v_new = (const uint16_t*)L.v_new;
-  p.Kw = (uint16_t*)L.K; p.Vw = (uint16_t*)L.V; p.d_lens_out = L.d_lens_out;
+  p.Kw = (uint16_t*)L.K; p.Vw = (uint16_t*)L.V; p.d_lens_rw = L.d_lens_rw; p.arrive = L.arrive;
   p.n_group = L.n_group; p.layer_rows = (int64_t)L.batch * L.Hq;
-  p.batch = L.batch; p.share = L.balanced_share;
+  p.batch = L.batch;
   const bool f32 = L.out_dtype == MIXATTN_F32, ring = L.window > 0, fused = L.k_new != nullptr;
-  if (L.balanced_share > 0) {
-    if (ring || L.attn_window > 0 || L.n_group > 0 || L.batch > kMaxBalancedBatch || L.balanced_runs < 1)
-      return hipErrorInvalidValue;
-    p.n_chunks = 2;  // pieces always go through the combine launch
+  if (fused && (!L.d_lens_rw || !L.arrive)) return hipErrorInvalidValue;
+  const bool balanced = L.balanced_runs > 0;
+  p.chunk_stride = kMaxChunks;
+  p.p_acc = L.scratch.acc; p.p_ml = L.scratch.ml;
+  if (balanced) {
+    if (ring || L.attn_window > 0 || L.n_group > 0 || L.batch > kMaxBalancedBatch) return hipErrorInvalidValue;
+    p.n_chunks = L.balanced_runs;  // pieces always go through the combine launch (n_chunks != 1)
+    if (p.n_chunks < 2) return hipErrorInvalidValue;
     const dim3 bgrid(L.balanced_runs), bblock(kDecodeWaves * 64);
     if (f32 && fused) hipLaunchKernelGGL((decode_balanced_kernel<float, true>), bgrid, bblock, 0, s, p);
     else if (f32) hipLaunchKernelGGL((decode_balanced_kernel<float, false>), bgrid, bblock, 0, s, p);
@@ -612,6 +638,7 @@ hipError_t launch_decode_tiled(const DecodeLaunch& L, hipStream_t s) {
     else hipLaunchKernelGGL(combine_balanced_kernel<uint16_t>, cgrid, cblock, 0, s, p);
     return hipGetLastError();
   }
+  if (L.n_chunks < 1 || L.n_chunks > kMaxChunks || L.chunk_blocks < 1) return hipErrorInvalidValue;
   const dim3 grid(L.n_chunks, L.Hkv, L.batch);
 #define MIXATTN_LAUNCH_DECODE(OUT, RING, FUSED) \
   hipLaunchKernelGGL((decode_tiled_kernel<OUT, RING, FUSED>), grid, dim3(kDecodeWaves * 64), 0, s, p)
@@ -641,7 +668,7 @@ hipError_t launch_decode_tiled(const DecodeLaunch& L, hipStream_t s) {
 #undef MIXATTN_LAUNCH_DECODE
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (L.n_chunks > 1 && !L.fused_combine) {
+  if (L.n_chunks > 1) {
     const dim3 cgrid(L.Hq, L.batch, std::max(L.n_group, 1)), cblock(kTiledDim);
     if (L.out_dtype == MIXATTN_F32)
       hipLaunchKernelGGL(combine_kernel<float>, cgrid, cblock, 0, s, p);

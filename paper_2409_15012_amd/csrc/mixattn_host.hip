@@ -29,9 +29,13 @@ inline int elem_bytes(int dt) { return dt == MIXATTN_F32 ? 4 : 2; }
 
 inline bool use_tiled(int kv_dtype, int D, int G) { return kv_dtype == MIXATTN_BF16 && D == kTiledDim && G <= kMaxGroup; }
 
+// testing aid (MIXATTN_PARAM_TEST_FAIL_ALLOC): > 0 counts device allocations down, the one that reaches 0 fails
+thread_local int64_t g_fail_alloc_in = 0;
+
 int dev_alloc(void** p, size_t bytes) {
   *p = nullptr;
   if (bytes == 0) bytes = 16;
+  if (g_fail_alloc_in > 0 && --g_fail_alloc_in == 0) return MIXATTN_ERR_ALLOC;
   hipError_t e = hipMalloc(p, bytes);
   if (e == hipErrorOutOfMemory) {
     g_last_hip = (int)e;
@@ -64,8 +68,7 @@ void free_layout(mixattn_layout* L) {
     if (c.d_pages) (void)hipFree(c.d_pages);
     free_stage(c.own_stage);
   }
-  free_stage(L->stage);
-  void* ptrs[] = {L->d_lens_all, L->scratch.acc, L->scratch.ml, L->scratch.counters,
+  void* ptrs[] = {L->d_lens_all, L->d_arrive_all, L->scratch.acc, L->scratch.ml,
                   L->d_stage_lens, L->d_stage_src, L->d_readback, L->d_q_first, L->d_q_len};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
@@ -176,7 +179,6 @@ static int create_layout_impl(const mixattn_config* cfg, int page_tokens, int64_
     if (!hip_ok(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, L->device)) || cus < 1) cus = 256;
     L->n_cus = cus;
   }
-  L->fused_combine = 0;  // device-scope fences write back and invalidate the XCD L2s: measured far slower than a separate launch
   L->layers.assign(cfg->layers, cfg->layers + cfg->n_layers);
   if (cfg->capacity) L->capacity.assign(cfg->capacity, cfg->capacity + cfg->batch);
 
@@ -201,16 +203,17 @@ static int create_layout_impl(const mixattn_config* cfg, int page_tokens, int64_
   }
   const int B = L->batch;
   const int nc = (int)L->caches.size();
-  st = dev_alloc((void**)&L->d_lens_all, sizeof(int32_t) * (size_t)nc * 2 * B);
-  if (st == MIXATTN_OK && !hip_ok(hipMemset(L->d_lens_all, 0, sizeof(int32_t) * (size_t)nc * 2 * B))) st = MIXATTN_ERR_HIP;
+  st = dev_alloc((void**)&L->d_lens_all, sizeof(int32_t) * (size_t)nc * B);
+  if (st == MIXATTN_OK && !hip_ok(hipMemset(L->d_lens_all, 0, sizeof(int32_t) * (size_t)nc * B))) st = MIXATTN_ERR_HIP;
+  if (st == MIXATTN_OK) st = dev_alloc((void**)&L->d_arrive_all, sizeof(uint32_t) * (size_t)nc);
+  if (st == MIXATTN_OK && !hip_ok(hipMemset(L->d_arrive_all, 0, sizeof(uint32_t) * (size_t)nc))) st = MIXATTN_ERR_HIP;
   for (int ci = 0; ci < nc && st == MIXATTN_OK; ++ci) {
     Cache& c = L->caches[ci];
     c.base.resize(B);
     c.slots.resize(B);
     c.len.assign(B, 0);
-    c.d_lens2[0] = L->d_lens_all + (size_t)ci * 2 * B;
-    c.d_lens2[1] = c.d_lens2[0] + B;
-    c.cur = 0;
+    c.d_lens = L->d_lens_all + (size_t)ci * B;
+    c.d_arrive = L->d_arrive_all + ci;
     int64_t run = 0;  // blocks (tiled) or rows (row-major) before sequence b
     int64_t max_cap = 0;
     for (int b = 0; b < B; ++b) {
@@ -266,9 +269,6 @@ static int create_layout_impl(const mixattn_config* cfg, int page_tokens, int64_
     const size_t rows = (size_t)group_layers * B * L->Hq * kMaxChunks;
     st = dev_alloc((void**)&L->scratch.acc, rows * L->D * sizeof(float));
     if (st == MIXATTN_OK) st = dev_alloc((void**)&L->scratch.ml, rows * 2 * sizeof(float));
-    if (st == MIXATTN_OK) st = dev_alloc((void**)&L->scratch.counters, sizeof(uint32_t) * (size_t)B * L->Hkv);
-    if (st == MIXATTN_OK && !hip_ok(hipMemset(L->scratch.counters, 0, sizeof(uint32_t) * (size_t)B * L->Hkv)))
-      st = MIXATTN_ERR_HIP;
   }
   if (st == MIXATTN_OK) st = dev_alloc((void**)&L->d_stage_lens, sizeof(int32_t) * B);
   if (st == MIXATTN_OK) st = dev_alloc((void**)&L->d_stage_src, sizeof(int64_t) * B);
@@ -308,19 +308,22 @@ static int reserve_pages(mixattn_layout* L, Cache& c, const std::vector<int64_t>
   }
   if (need == 0) return MIXATTN_OK;
   if (need > (int64_t)c.free_pages.size()) return MIXATTN_ERR_CAPACITY;  // the pool is exhausted
+  // plan first, enqueue the table entries, and only then take the pages off the free list
   std::vector<int64_t> index;
   std::vector<int32_t> value;
+  std::vector<int> owner;
+  size_t top = c.free_pages.size();
   for (int b = 0; b < L->batch; ++b) {
     const int64_t pages = (want[b] + page_tokens - 1) / page_tokens;
-    while ((int64_t)c.seq_pages[b].size() < pages) {
-      const int32_t pg = c.free_pages.back();
-      c.free_pages.pop_back();
-      index.push_back((int64_t)b * c.max_pages + (int64_t)c.seq_pages[b].size());
-      value.push_back(pg);
-      c.seq_pages[b].push_back(pg);
+    for (int64_t have = (int64_t)c.seq_pages[b].size(); have < pages; ++have) {
+      index.push_back((int64_t)b * c.max_pages + have);
+      value.push_back(c.free_pages[--top]);
+      owner.push_back(b);
     }
   }
   HIP_TRY(launch_scatter_i32(c.d_pages, index.data(), value.data(), (int)index.size(), s));
+  for (size_t i = 0; i < value.size(); ++i) c.seq_pages[owner[i]].push_back(value[i]);
+  c.free_pages.resize(top);
   return MIXATTN_OK;
 }
 
@@ -339,13 +342,13 @@ int mixattn_destroy_layout(mixattn_layout* L) {
 
 int mixattn_reset(mixattn_layout* L, void* stream) {
   if (!L) return MIXATTN_ERR_NULL;
-  HIP_TRY(launch_fill_i32(L->d_lens_all, 0, (int64_t)L->caches.size() * 2 * L->batch, (hipStream_t)stream));
+  HIP_TRY(launch_fill_i32(L->d_lens_all, 0, (int64_t)L->caches.size() * L->batch, (hipStream_t)stream));
   for (auto& c : L->caches) {
     std::fill(c.len.begin(), c.len.end(), 0);
     for (int b = 0; b < L->batch; ++b) release_pages(c, b);
     c.own_stage.cache = -1;
+    c.plan_key = -1;
   }
-  L->stage.cache = -1;
   return MIXATTN_OK;
 }
 
@@ -353,15 +356,12 @@ int mixattn_release_sequence(mixattn_layout* L, int b, void* stream) {
   if (!L) return MIXATTN_ERR_NULL;
   if (b < 0 || b >= L->batch) return MIXATTN_ERR_LAYER;
   for (auto& c : L->caches) {
-    // both length arrays: a fused append may have left the current one either way round
-    HIP_TRY(launch_fill_i32(c.d_lens2[0] + b, kIdle, 1, (hipStream_t)stream));
-    HIP_TRY(launch_fill_i32(c.d_lens2[1] + b, kIdle, 1, (hipStream_t)stream));
+    HIP_TRY(launch_fill_i32(c.d_lens + b, kIdle, 1, (hipStream_t)stream));
     c.len[b] = kIdle;
     c.plan_key = -1;
     release_pages(c, b);
     c.own_stage.cache = -1;
   }
-  L->stage.cache = -1;
   return MIXATTN_OK;
 }
 
@@ -370,10 +370,7 @@ static inline int64_t held(const Cache& c, int b) { return c.len[b] < 0 ? 0 : c.
 static inline bool idle(const Cache& c, int b) { return c.len[b] < 0; }
 
 // A staged prompt chunk describes the cache as its writer's prefill left it: any other change to the cache retires it.
-static void retire_stage(mixattn_layout* L, Cache& c) {
-  c.own_stage.cache = -1;
-  if (L->stage.cache == (int)(&c - L->caches.data())) L->stage.cache = -1;
-}
+static void retire_stage(mixattn_layout*, Cache& c) { c.own_stage.cache = -1; }
 
 static int check_append(const mixattn_layout* L, const Cache& c, int layer) {
   if (c.writer != layer) return MIXATTN_ERR_NOT_WRITER;
@@ -491,8 +488,9 @@ static int plan_chunk_blocks(const mixattn_layout* L, Cache& c, int max_blocks, 
   return c.plan_chunk_blocks;
 }
 
-// Decode launch shared by mixattn_decode and mixattn_append_decode.  `extra` = 1 when a fused launch appends this
-// step's token itself (lengths on host and device still hold the old value while planning).
+// Decode launch shared by mixattn_decode, mixattn_append_decode and mixattn_decode_group.
+// `extra` = 1 when a fused launch appends this step's token itself (lengths on host and device still hold the old
+// value while planning).
 static int launch_decode(mixattn_layout* L, Cache& c, int attn_window, const void* q, void* out, const void* k_new,
                          const void* v_new, hipStream_t stream, int n_group = 0) {
   const int extra = k_new ? 1 : 0;
@@ -516,8 +514,9 @@ static int launch_decode(mixattn_layout* L, Cache& c, int attn_window, const voi
   a.batch = L->batch; a.Hq = L->Hq; a.Hkv = L->Hkv; a.G = L->G; a.D = L->D;
   a.kv_dtype = L->kv_dtype; a.out_dtype = L->out_dtype; a.scale = L->scale;
   a.scratch = L->scratch;
-  a.fused_combine = (int)L->fused_combine;
-  a.k_new = k_new; a.v_new = v_new; a.d_lens_out = k_new ? c.lens_other() : nullptr;
+  a.k_new = k_new; a.v_new = v_new;
+  a.d_lens_rw = k_new ? c.lens() : nullptr;
+  a.arrive = k_new ? c.d_arrive : nullptr;
   a.n_group = n_group;
   if (!L->tiled) {
     a.max_blocks = a.chunk_blocks = a.n_chunks = 0;
@@ -553,25 +552,33 @@ static int launch_decode(mixattn_layout* L, Cache& c, int attn_window, const voi
     }
     const bool ragged = (int64_t)max_nb * L->batch * 4 > sum_nb * 5;  // longest sequence > 1.25 x the mean
     if (ragged || a.n_chunks > 1 || L->balanced == 2) {
+      // the kernels derive the run length from the lengths and the number of runs in the same way
       const int64_t total = sum_nb * L->Hkv;
       const int64_t slots = 2 * (int64_t)L->n_cus;
       int64_t share = (total + slots - 1) / slots;
       share = std::max<int64_t>(share, (max_nb + (kMaxChunks - 2) - 1) / (kMaxChunks - 2));  // pieces per stream <= kMaxChunks
       share = std::max<int64_t>(share, kDecodeMinChunkBlocks);
-      a.balanced_share = (int)share;
-      a.balanced_runs = (int)((total + share - 1) / share);
+      const int64_t runs = (total + share - 1) / share;
+      if (runs >= 2) a.balanced_runs = (int)runs;
     }
   }
   HIP_TRY(launch_decode_tiled(a, stream));
   return MIXATTN_OK;
 }
 
-int mixattn_decode(mixattn_layout* L, int layer, const void* q, void* out, void* stream) {
+static int check_decode(const mixattn_layout* L, int layer, const void* q, const void* out) {
   if (!L || !q || !out) return MIXATTN_ERR_NULL;
   if (layer < 0 || layer >= L->n_layers) return MIXATTN_ERR_LAYER;
-  Cache& c = L->caches[L->layer_cache[layer]];
+  const Cache& c = L->caches[L->layer_cache[layer]];
   for (int b = 0; b < L->batch; ++b)
     if (c.len[b] == 0) return MIXATTN_ERR_ORDER;  // empty; an idle sequence (negative) is passed over
+  return MIXATTN_OK;
+}
+
+int mixattn_decode(mixattn_layout* L, int layer, const void* q, void* out, void* stream) {
+  const int st = check_decode(L, layer, q, out);
+  if (st != MIXATTN_OK) return st;
+  Cache& c = L->caches[L->layer_cache[layer]];
   return launch_decode(L, c, layer_attn_window(L, layer), q, out, nullptr, nullptr, (hipStream_t)stream);
 }
 
@@ -587,11 +594,10 @@ int mixattn_append_decode(mixattn_layout* L, int layer, const void* k, const voi
     return st != MIXATTN_OK ? st : mixattn_decode(L, layer, q, out, stream);
   }
   if ((st = reserve_for_append(L, c, (hipStream_t)stream)) != MIXATTN_OK) return st;
-  retire_stage(L, c);
   st = launch_decode(L, c, 0, q, out, k, v, (hipStream_t)stream);
   if (st != MIXATTN_OK) return st;
-  c.cur ^= 1;  // the launch wrote n + 1 into the other length array
-  for (int b = 0; b < L->batch; ++b) c.len[b] += idle(c, b) ? 0 : 1;
+  retire_stage(L, c);
+  for (int b = 0; b < L->batch; ++b) c.len[b] += idle(c, b) ? 0 : 1;  // the launch advances the device lengths
   return MIXATTN_OK;
 }
 
@@ -612,7 +618,6 @@ int mixattn_decode_group(mixattn_layout* L, const int32_t* layers, int n_layers,
   if (k) {
     const int st = check_append(L, c, layers[0]);
     if (st != MIXATTN_OK) return st;
-    retire_stage(L, c);
   } else {
     for (int b = 0; b < L->batch; ++b)
       if (c.len[b] == 0) return MIXATTN_ERR_ORDER;
@@ -620,33 +625,113 @@ int mixattn_decode_group(mixattn_layout* L, const int32_t* layers, int n_layers,
   const int st = launch_decode(L, c, 0, q, out, k, v, (hipStream_t)stream, n_layers);
   if (st != MIXATTN_OK) return st;
   if (k) {
-    c.cur ^= 1;  // the launch wrote n + 1 into the other length array
-    for (int b = 0; b < L->batch; ++b) c.len[b] += idle(c, b) ? 0 : 1;
+    retire_stage(L, c);
+    for (int b = 0; b < L->batch; ++b) c.len[b] += idle(c, b) ? 0 : 1;  // the launch advances the device lengths
   }
   return MIXATTN_OK;
 }
 
-static int ensure_stage(mixattn_layout* L, Stage& S, int64_t blocks_per_head) {
+// ---- captured decode steps (HIP graphs) ---------------------------------------------------------------------
+int mixattn_reserve_steps(mixattn_layout* L, int steps, void* stream) {
+  if (!L) return MIXATTN_ERR_NULL;
+  if (steps < 0) return MIXATTN_ERR_ORDER;
+  // every check first, for every cache: a refusal leaves every page table as it was
+  for (const Cache& c : L->caches) {
+    if (c.kind != MIXATTN_FULL) continue;
+    int64_t need = 0;
+    const int64_t page_tokens = (int64_t)kBlockKeys << c.page_shift;
+    for (int b = 0; b < L->batch; ++b) {
+      if (idle(c, b)) continue;
+      if (c.len[b] + steps > L->capacity[b]) return MIXATTN_ERR_CAPACITY;
+      if (c.paged) need += std::max<int64_t>(0, (c.len[b] + steps + page_tokens - 1) / page_tokens - (int64_t)c.seq_pages[b].size());
+    }
+    if (c.paged && need > (int64_t)c.free_pages.size()) return MIXATTN_ERR_CAPACITY;
+  }
+  for (Cache& c : L->caches) {
+    if (!c.paged) continue;
+    std::vector<int64_t> want(L->batch);
+    for (int b = 0; b < L->batch; ++b) want[b] = idle(c, b) ? 0 : c.len[b] + steps;
+    const int st = reserve_pages(L, c, want, (hipStream_t)stream);
+    if (st != MIXATTN_OK) return st;
+  }
+  return MIXATTN_OK;
+}
+
+int mixattn_account_replays(mixattn_layout* L, int steps) {
+  if (!L) return MIXATTN_ERR_NULL;
+  if (steps < 0) return MIXATTN_ERR_ORDER;
+  for (const Cache& c : L->caches)
+    for (int b = 0; b < L->batch; ++b)
+      if (!idle(c, b) && c.kind == MIXATTN_FULL && c.len[b] + steps > L->capacity[b]) return MIXATTN_ERR_CAPACITY;
+  for (Cache& c : L->caches) {
+    for (int b = 0; b < L->batch; ++b) c.len[b] += idle(c, b) ? 0 : steps;
+    if (steps > 0) retire_stage(L, c);
+  }
+  return MIXATTN_OK;
+}
+
+// Staging area of cache c for prompt chunks: tile-format copies that the MFMA prefill kernel reads.  A full cache
+// stages V only (as fp16, positions 0 .. n-1; K is read from the cache itself), a ring stages K and V of positions
+// n_old - (W-1) .. n_new-1.  Growing it synchronises the device and allocates, so callers do it before they change
+// any state; mixattn_reserve_prefill sizes every area once, after which no prefill call gets here.
+static int grow_stage(mixattn_layout* L, Cache& c, int64_t blocks_per_head) {
+  Stage& S = c.own_stage;
   if (S.blocks >= blocks_per_head) return MIXATTN_OK;
-  // the old area may still be in use by work in flight
-  HIP_TRY(hipDeviceSynchronize());
-  if (S.K) (void)hipFree(S.K);
-  if (S.V) (void)hipFree(S.V);
-  S.K = S.V = nullptr;
-  S.blocks = 0;
-  S.cache = -1;
+  const bool need_k = c.kind == MIXATTN_SLIDING;
+  const size_t bytes = (size_t)L->batch * L->Hkv * blocks_per_head * kBlockElems * 2;
+  // allocate the new area first: a failure leaves the old one (and whatever it holds) as it was
+  void* nK = nullptr;
+  void* nV = nullptr;
   int st;
   if (!S.d_base && (st = dev_alloc((void**)&S.d_base, sizeof(int64_t) * L->batch)) != MIXATTN_OK) return st;
   if (!S.d_slots && (st = dev_alloc((void**)&S.d_slots, sizeof(int32_t) * L->batch)) != MIXATTN_OK) return st;
-  const size_t bytes = (size_t)L->batch * L->Hkv * blocks_per_head * kBlockElems * 2;
-  if ((st = dev_alloc(&S.K, bytes)) != MIXATTN_OK) return st;
-  if ((st = dev_alloc(&S.V, bytes)) != MIXATTN_OK) return st;
+  if (need_k && (st = dev_alloc(&nK, bytes)) != MIXATTN_OK) return st;
+  if ((st = dev_alloc(&nV, bytes)) != MIXATTN_OK) {
+    if (nK) (void)hipFree(nK);
+    return st;
+  }
+  // the old area and its geometry tables may still be in use by work in flight
+  if (!hip_ok(hipDeviceSynchronize())) {
+    if (nK) (void)hipFree(nK);
+    (void)hipFree(nV);
+    return MIXATTN_ERR_HIP;
+  }
+  if (S.K) (void)hipFree(S.K);
+  if (S.V) (void)hipFree(S.V);
+  S.K = nK;
+  S.V = nV;
+  S.blocks = 0;
+  S.cache = -1;
   std::vector<int64_t> base(L->batch);
   std::vector<int32_t> slots(L->batch, (int32_t)(blocks_per_head * kBlockKeys));
   for (int b = 0; b < L->batch; ++b) base[b] = (int64_t)b * L->Hkv * blocks_per_head;
   if ((st = upload(S.d_base, base.data(), sizeof(int64_t) * L->batch)) != MIXATTN_OK) return st;
   if ((st = upload(S.d_slots, slots.data(), sizeof(int32_t) * L->batch)) != MIXATTN_OK) return st;
   S.blocks = blocks_per_head;
+  return MIXATTN_OK;
+}
+
+// blocks per (sequence, kv head) the staging area of cache c needs for chunks of up to `chunk` tokens
+static int64_t stage_blocks_for(const mixattn_layout* L, const Cache& c, int64_t chunk) {
+  int64_t tokens;
+  if (c.kind == MIXATTN_FULL) {
+    tokens = 0;  // a copy of V for everything the cache can hold
+    for (int b = 0; b < L->batch; ++b) tokens = std::max<int64_t>(tokens, L->capacity[b]);
+  } else {
+    tokens = (int64_t)c.window - 1 + chunk;
+  }
+  return (tokens + kBlockKeys - 1) / kBlockKeys;
+}
+
+int mixattn_reserve_prefill(mixattn_layout* L, int max_chunk_tokens) {
+  if (!L) return MIXATTN_ERR_NULL;
+  if (max_chunk_tokens < 1) return MIXATTN_ERR_ORDER;
+  if (!L->tiled) return MIXATTN_OK;  // the scalar path stages nothing
+  for (Cache& c : L->caches) {
+    const int st = grow_stage(L, c, stage_blocks_for(L, c, max_chunk_tokens));
+    if (st != MIXATTN_OK) return st;
+  }
+  L->reserved_chunk = std::max<int64_t>(L->reserved_chunk, max_chunk_tokens);
   return MIXATTN_OK;
 }
 
@@ -663,8 +748,8 @@ static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void*
   // a reader may pass k = v = NULL to reuse the prompt copy staged by the latest prefill call, if that call was for
   // the same cache and length (tiled path only)
   const bool reuse_stage = !k && !v;
-  // the staging area this call uses: a ring with readers has one of its own, which outlives other layers' calls
-  Stage& S = (sliding_cache && c.n_users > 1) ? c.own_stage : L->stage;
+  // every cache stages its chunks in an area of its own, which outlives the calls of other layers
+  Stage& S = c.own_stage;
   if (reuse_stage) {
     if (writer || !L->tiled || L->prefill_simple) return MIXATTN_ERR_NULL;
     if (S.cache != ci || (int)S.lens.size() != L->batch) return MIXATTN_ERR_ORDER;
@@ -694,6 +779,20 @@ static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void*
   if (simple && L->tiled && chunked) return MIXATTN_ERR_ORDER;  // the cross-check path keeps to whole prompts
   hipStream_t s = (hipStream_t)stream;
   const int attn_window = L->layers[layer].kind == MIXATTN_SLIDING ? L->layers[layer].window : 0;
+  // Everything that can fail is done before the first state change: the staging area is grown if mixattn_reserve_prefill
+  // has not sized it for this chunk (synchronises and allocates), then a paged cache takes the pages the chunk needs.
+  if (L->tiled && !simple && !reuse_stage) {
+    const int64_t need = sliding_cache ? (std::min<int64_t>(max_old, c.window - 1) + seq_len + kBlockKeys - 1) / kBlockKeys
+                                       : (max_new + kBlockKeys - 1) / kBlockKeys;
+    const int e = grow_stage(L, c, need);
+    if (e != MIXATTN_OK) return e;
+  }
+  if (writer && c.paged) {
+    std::vector<int64_t> want(L->batch);
+    for (int b = 0; b < L->batch; ++b) want[b] = held(c, b) + len_of(b);
+    const int e = reserve_pages(L, c, want, s);
+    if (e != MIXATTN_OK) return e;
+  }
   // per-sequence row tables of a varlen call (every kernel of this call reads them after this point of the stream)
   const int64_t* d_first = nullptr;
   const int32_t* d_len = nullptr;
@@ -729,14 +828,8 @@ static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void*
   p.heads = (int)L->prefill_heads;
   p.d_q_first = d_first; p.d_q_len = d_len;
 
-  // commit of the chunk into this layer's cache (writer): reads lens(), writes n_old + seq_len to lens_other()
+  // commit of the chunk into this layer's cache (writer): the store reads the lengths, a small launch then advances them
   auto commit = [&]() -> int {
-    if (c.paged) {
-      std::vector<int64_t> want(L->batch);
-      for (int b = 0; b < L->batch; ++b) want[b] = held(c, b) + len_of(b);
-      const int e = reserve_pages(L, c, want, s);
-      if (e != MIXATTN_OK) return e;
-    }
     StoreLaunch st;
     st.K = c.K; st.V = c.V; st.d_base = c.d_base; st.d_slots = c.d_slots; st.window = c.window;
     st.pages = c.page_table();
@@ -747,11 +840,10 @@ static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void*
       st.old_pages = c.page_table();
       st.old_is_dest = 1;
     }
-    st.d_lens_out = c.lens_other();
     st.batch = L->batch; st.Hkv = L->Hkv; st.D = L->D; st.elem = L->elem;
     st.max_slots = (int)(c.window > 0 ? std::min<int64_t>(max_new, c.window) : max_new);
     HIP_TRY(L->tiled ? launch_store_tiled(st, s) : launch_store_rowmajor(st, s));
-    c.cur ^= 1;
+    HIP_TRY(launch_advance_lens(c.lens(), d_len, varlen ? 0 : seq_len, L->batch, s));
     for (int b = 0; b < L->batch; ++b)
       if (len_of(b) > 0) c.len[b] = held(c, b) + len_of(b);  // a chunk also starts an idle sequence
     return MIXATTN_OK;
@@ -786,8 +878,6 @@ static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void*
       if (e != MIXATTN_OK) return e;
     }
     if (!reuse_stage) {
-      int e = ensure_stage(L, S, (max_new + kBlockKeys - 1) / kBlockKeys);
-      if (e != MIXATTN_OK) return e;
       S.cache = -1;
       StoreLaunch st;
       st.K = nullptr; st.V = S.V; st.v_as_f16 = 1;
@@ -817,8 +907,6 @@ static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void*
   const int W = c.window;
   if (!reuse_stage) {
     const int64_t span = std::min<int64_t>(max_old, W - 1) + seq_len;
-    int e = ensure_stage(L, S, (span + kBlockKeys - 1) / kBlockKeys);
-    if (e != MIXATTN_OK) return e;
     S.cache = -1;
     StoreLaunch st;
     st.K = S.K; st.V = S.V; st.v_as_f16 = 1;
@@ -885,32 +973,27 @@ int mixattn_load_kv(mixattn_layout* L, int layer, const void* k, const void* v, 
     run += seq_lens[b];
     max_len = std::max(max_len, seq_lens[b]);
   }
-  retire_stage(L, c);
   hipStream_t s = (hipStream_t)stream;
   if (c.paged) {
     std::vector<int64_t> want(seq_lens, seq_lens + L->batch);
     const int pe = reserve_pages(L, c, want, s);
     if (pe != MIXATTN_OK) return pe;
   }
-  // the device copies of the per-sequence tables may still be read by an earlier load on this stream
-  HIP_TRY(hipStreamSynchronize(s));
-  int e = upload(L->d_stage_lens, seq_lens, sizeof(int32_t) * L->batch);
-  if (e != MIXATTN_OK) return e;
-  e = upload(L->d_stage_src, first.data(), sizeof(int64_t) * L->batch);
-  if (e != MIXATTN_OK) return e;
+  retire_stage(L, c);
+  // per-sequence tables travel in the arguments of a small kernel: stream-ordered behind any earlier user of them
+  HIP_TRY(launch_set_seq_tables(L->d_stage_src, L->d_stage_lens, first.data(), seq_lens, L->batch, s));
   StoreLaunch st;
   st.K = c.K; st.V = c.V; st.d_base = c.d_base; st.d_slots = c.d_slots; st.window = c.window;
   st.pages = c.page_table();
   st.k_src = k; st.v_src = v; st.d_src_first = L->d_stage_src; st.d_src_len = L->d_stage_lens; st.uniform_len = 0;
-  // lengths: read from the current array (0, or idle), written to the other one, which then becomes current
-  st.d_n_old = c.lens(); st.old_sub = 0;
-  st.d_lens_out = c.lens_other();
+  st.d_n_old = c.lens(); st.old_sub = 0;  // 0, or idle
   st.batch = L->batch; st.Hkv = L->Hkv; st.D = L->D; st.elem = L->elem;
   st.max_slots = std::max(1, c.window > 0 ? std::min(max_len, c.window) : max_len);
   HIP_TRY(L->tiled ? launch_store_tiled(st, s) : launch_store_rowmajor(st, s));
-  c.cur ^= 1;
+  HIP_TRY(launch_advance_lens(c.lens(), L->d_stage_lens, 0, L->batch, s));
   for (int b = 0; b < L->batch; ++b)
     if (seq_lens[b] > 0 || !idle(c, b)) c.len[b] = seq_lens[b];  // an idle sequence given nothing stays idle
+  c.plan_key = -1;
   return MIXATTN_OK;
 }
 
@@ -1007,9 +1090,9 @@ int mixattn_set_param(mixattn_layout* L, int param, int64_t value) {
       if (value < 0 || value % kBlockKeys != 0 || value > (int64_t)1 << 30) return MIXATTN_ERR_PARAM;
       L->chunk_keys = value;
       return MIXATTN_OK;
-    case MIXATTN_PARAM_FUSED_COMBINE:
-      if (value != 0 && value != 1) return MIXATTN_ERR_PARAM;
-      L->fused_combine = value;
+    case MIXATTN_PARAM_TEST_FAIL_ALLOC:
+      if (value < 0) return MIXATTN_ERR_PARAM;
+      g_fail_alloc_in = value;
       return MIXATTN_OK;
     case MIXATTN_PARAM_PREFILL_SIMPLE:
       if (value != 0 && value != 1) return MIXATTN_ERR_PARAM;
@@ -1035,7 +1118,7 @@ int mixattn_get_param(const mixattn_layout* L, int param, int64_t* value) {
   if (!L || !value) return MIXATTN_ERR_NULL;
   switch (param) {
     case MIXATTN_PARAM_CHUNK_KEYS: *value = L->chunk_keys; return MIXATTN_OK;
-    case MIXATTN_PARAM_FUSED_COMBINE: *value = L->fused_combine; return MIXATTN_OK;
+    case MIXATTN_PARAM_TEST_FAIL_ALLOC: *value = g_fail_alloc_in; return MIXATTN_OK;
     case MIXATTN_PARAM_PREFILL_SIMPLE: *value = L->prefill_simple; return MIXATTN_OK;
     case MIXATTN_PARAM_PREFILL_WAVES: *value = L->prefill_waves; return MIXATTN_OK;
     case MIXATTN_PARAM_PREFILL_HEADS: *value = L->prefill_heads; return MIXATTN_OK;

@@ -28,7 +28,6 @@ constexpr int kIdle = -1;                             // length of a released se
 constexpr int kMaxChunks = 64;                       // split-K chunks per (sequence, kv head)
 constexpr int kMaxHeadDim = 256;
 constexpr int kDecodeMinChunkBlocks = 4;              // a split-K chunk keeps every wavefront of its workgroup busy
-
 __host__ __device__ inline int k_tile_offset(int key, int dim) {
   return (key >> 4) * 2048 + (dim >> 3) * 128 + (key & 15) * 8 + (dim & 7);
 }
@@ -77,12 +76,11 @@ struct Cache {
   std::vector<int32_t> slots;  // slots per (b, h): capacity rounded up to 32 (tiled) / capacity (row-major)
   int64_t* d_base = nullptr;
   int32_t* d_slots = nullptr;
-  // device lengths, [batch], two copies in Layout::d_lens_all: kernels read lens(); a fused append+decode launch
-  // writes the other copy and the host then flips `cur`
-  int32_t* d_lens2[2] = {nullptr, nullptr};
-  int cur = 0;
-  int32_t* lens() const { return d_lens2[cur]; }
-  int32_t* lens_other() const { return d_lens2[cur ^ 1]; }
+  // device lengths, [batch], a slice of Layout::d_lens_all.  Always the same address (a captured launch stays valid):
+  // appends advance them in place, a bulk store is followed by a small kernel that sets them.
+  int32_t* d_lens = nullptr;
+  int32_t* lens() const { return d_lens; }
+  uint32_t* d_arrive = nullptr;  // arrival counter of fused append+decode launches on this cache (zero between launches)
   std::vector<int64_t> len;    // host mirror
   // paged storage (full caches of a paged layout): a pool of pages, handed to sequences as they grow
   bool paged = false;
@@ -96,8 +94,8 @@ struct Cache {
     if (paged) { t.ids = d_pages; t.max_pages = max_pages; t.shift = page_shift; }
     return t;
   }
-  // A ring with reader layers keeps the staged copy of its latest prompt chunk to itself, so that its readers can run
-  // at any later point of the layer loop (the ring itself no longer holds the keys the chunk's first rows need).
+  // Every cache keeps the staged copy of its latest prompt chunk to itself, so that its readers can run at any later
+  // point of the layer loop (a ring no longer holds the keys the chunk's first rows need).
   int n_users = 0;   // layers reading this cache, the writer included
   Stage own_stage;
   // memo of the last split-K plan (it only changes when a sequence crosses a block boundary)
@@ -110,7 +108,6 @@ struct DecodeScratch {
   // `layers` = most layers one group launch serves (1 when no ring has a reader)
   float* acc = nullptr;  // [layers][batch][n_q_heads][kMaxChunks][head_dim]
   float* ml = nullptr;   // [layers][batch][n_q_heads][kMaxChunks][2]  (max in log2 units, sum)
-  uint32_t* counters = nullptr;  // [batch][n_kv_heads] arrival counters for the fused combine
 };
 
 }  // namespace mixattn
@@ -126,9 +123,11 @@ struct mixattn_layout {
   std::vector<int> layer_cache;  // layer -> cache index
   std::vector<mixattn::Cache> caches;
   std::vector<int32_t> capacity;  // [batch] for FULL caches
-  int32_t* d_lens_all = nullptr;  // [n_caches][2][batch]
+  int32_t* d_lens_all = nullptr;  // [n_caches][batch]
+  uint32_t* d_arrive_all = nullptr;  // [n_caches]
   mixattn::DecodeScratch scratch;
-  mixattn::Stage stage;  // shared by full caches and by rings without readers
+  int64_t reserved_chunk = 0;     // longest prompt chunk the staging areas were sized for (mixattn_reserve_prefill)
+  int fail_alloc_in = 0;          // testing: > 0 counts down device allocations, the one that reaches 0 fails
   int32_t* d_stage_lens = nullptr;  // [batch] device copy of seq_lens for load_kv / prefill commits
   int64_t* d_stage_src = nullptr;   // [batch] device: first packed token of each sequence
   int64_t* d_q_first = nullptr;     // [batch] device: first packed row of each sequence in a varlen prefill call
@@ -136,7 +135,6 @@ struct mixattn_layout {
   void* d_readback = nullptr;       // 2 * kMaxHeadDim elements for mixattn_read_cache
   // tuning
   int64_t chunk_keys = 0;
-  int64_t fused_combine = 0;
   int64_t prefill_simple = 0;
   int64_t prefill_waves = 0; // 0 = automatic
   int64_t prefill_heads = 0; // 0 = automatic
@@ -162,14 +160,15 @@ struct DecodeLaunch {
   int max_blocks;      // over the batch, ceil(min(n_b, window)/32) (tiled path)
   int chunk_blocks;    // blocks per split-K chunk
   int n_chunks;        // grid.x
-  int fused_combine;
   DecodeScratch scratch;
-  // fused append (tiled path): this step's k, v [batch, Hkv, D] and the length array that receives n + 1; nullptr = none
-  const void* k_new = nullptr; const void* v_new = nullptr; int32_t* d_lens_out = nullptr;
+  // fused append (tiled path): this step's k, v [batch, Hkv, D], the length array (advanced in place by the launch)
+  // and the cache's arrival counter; nullptr = none
+  const void* k_new = nullptr; const void* v_new = nullptr; int32_t* d_lens_rw = nullptr; uint32_t* arrive = nullptr;
   // > 0 (tiled path, rings only): q and out hold n_group layers, [n_group][batch][Hq][D]; scratch rows likewise
   int n_group = 0;
-  // > 0 (tiled path, full caches): balanced launch, `balanced_runs` workgroups of `balanced_share` blocks each
-  int balanced_share = 0, balanced_runs = 0;
+  // > 0 (tiled path, full caches): balanced launch of `balanced_runs` (>= 2) workgroups, each taking an equal run of
+  // the batch's blocks (the run length is derived on the device from the lengths)
+  int balanced_runs = 0;
 };
 hipError_t launch_decode_tiled(const DecodeLaunch& a, hipStream_t s);
 hipError_t launch_decode_rowmajor(const DecodeLaunch& a, hipStream_t s);
@@ -195,7 +194,6 @@ struct StoreLaunch {
   PageTable old_pages;         // the old cache is paged
   int old_window = 0;          // ring size of the old cache (0 = full cache)
   int old_is_dest = 0;         // the old cache is the destination itself: blocks without new tokens are skipped
-  int32_t* d_lens_out = nullptr;  // device lengths to set to n_old + add (nullptr: leave)
   int batch = 0, Hkv = 0, D = 0, elem = 0;
   int max_slots = 0;           // max over b of destination slots that can receive data (grid size)
 };
@@ -213,6 +211,9 @@ struct AppendLaunch {
 hipError_t launch_append_tiled(const AppendLaunch& a, hipStream_t s);
 hipError_t launch_append_rowmajor(const AppendLaunch& a, hipStream_t s);
 
+// after a bulk store: lens[b] = tokens held once sequence b has received its new tokens (src_len[b], or uniform_len
+// for every sequence when src_len is nullptr); an idle sequence (negative) given none stays idle
+hipError_t launch_advance_lens(int32_t* lens, const int32_t* src_len, int uniform_len, int batch, hipStream_t s);
 hipError_t launch_fill_i32(int32_t* p, int32_t value, int64_t n, hipStream_t s);
 // table[index[i]] = value[i] for i < n (host arrays; the values travel in the kernel arguments)
 hipError_t launch_scatter_i32(int32_t* table, const int64_t* index, const int32_t* value, int n, hipStream_t s);

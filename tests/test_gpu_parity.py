@@ -75,24 +75,23 @@ def _mixed_layers(W):
     return [(0, 0, 0), (1, W, 1), (1, W, 1), (0, 0, 0), (1, W, 2)]
 
 
-@pytest.mark.parametrize("Hq,Hkv,W,lens,chunk,fused", [
-    (8, 2, 64, [1, 31, 32, 33, 100, 257, 1000], 0, 1),
-    (8, 2, 48, [5, 47, 48, 49, 96, 700], 32, 1),       # window not a multiple of the block, one block per chunk
-    (8, 2, 256, [300, 2100, 64], 64, 0),               # separate combine launch
-    (4, 4, 100, [129, 4000], 128, 1),                  # G = 1
-    (8, 1, 1024, [1500, 1023, 2048], 0, 1),            # G = 8
-    (6, 2, 33, [77, 3], 0, 1),                         # G = 3
-    (8, 2, 1, [1, 2, 40], 0, 0),                       # window of one key: every sliding layer returns v of its token
-    (8, 2, 2, [1, 2, 3, 65], 0, 0),
-    (8, 2, 31, [30, 31, 32, 1000], 0, 0),              # window just under one block
+@pytest.mark.parametrize("Hq,Hkv,W,lens,chunk", [
+    (8, 2, 64, [1, 31, 32, 33, 100, 257, 1000], 0),
+    (8, 2, 48, [5, 47, 48, 49, 96, 700], 32),       # window not a multiple of the block, one block per chunk
+    (8, 2, 256, [300, 2100, 64], 64),
+    (4, 4, 100, [129, 4000], 128),                  # G = 1
+    (8, 1, 1024, [1500, 1023, 2048], 0),            # G = 8
+    (6, 2, 33, [77, 3], 0),                         # G = 3
+    (8, 2, 1, [1, 2, 40], 0),                       # window of one key: every sliding layer returns v of its token
+    (8, 2, 2, [1, 2, 3, 65], 0),
+    (8, 2, 31, [30, 31, 32, 1000], 0),              # window just under one block
 ])
-def test_bf16_decode_against_oracle(mx, Hq, Hkv, W, lens, chunk, fused):
+def test_bf16_decode_against_oracle(mx, Hq, Hkv, W, lens, chunk):
     B, d = len(lens), 128
     layers = _mixed_layers(W)
     steps = 3
     lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[n + steps for n in lens], kv_dtype="bf16", out_dtype="f32")
     lay.set_param(mx.PARAM_CHUNK_KEYS, chunk)
-    lay.set_param(mx.PARAM_FUSED_COMBINE, fused)
     ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
     seed = 5000 + Hq * 31 + W
     for li in range(len(layers)):
@@ -192,16 +191,16 @@ def test_bf16_prefill_then_decode_against_oracle(mx, S, W, Hq, Hkv, B, simple, o
         q = wl.randn(seed + 100 + li, (B, S, Hq, d), torch.bfloat16, DEV)
         k, v = kv[wr]
         if wr != li and not simple:
-            # a reader reuses the prompt staged by its writer: the ring (layers 1, 2) keeps a copy of its own, the
-            # full cache's copy (layer 0) is still in the shared area because no layer since has used that
+            # a reader reuses the prompt copy its writer staged: every cache keeps its own, so layer 3 finds
+            # layer 0's although two other caches have been through their prefill since
             out = lay.prefill(li, q, None, None)
         else:
             out = lay.prefill(li, q, k, v)
         ref = ora.prefill(li, to_f64(q), to_f64(k) if wr == li else None, to_f64(v) if wr == li else None)
         assert_matches(out, ref, "bf16", "prefill layer %d" % li)
     if not simple:
-        with pytest.raises(mx.MixAttnError) as ei:  # layer 4 (a ring without readers) has used the shared area since
-            lay.prefill(3, q, None, None)
+        with pytest.raises(mx.MixAttnError) as ei:  # a staged copy made for another chunk length is not reused
+            lay.prefill(3, torch.cat([q, q], 1), None, None)
         assert ei.value.status == -6
     for li in (0, 1, 4):
         _check_cache(lay, ora, li, heads=[0])
@@ -306,10 +305,10 @@ def test_split_count_does_not_change_the_result(mx):
     lay.load_kv(0, k, v, [n])
     q = wl.randn(23, (B, Hq, d), torch.bfloat16, DEV)
     outs = []
-    for chunk in (1 << 20, 2048, 256, 64):
-        for fused in (0, 1):
+    for chunk in (1 << 20, 2048, 256, 64, 0):
+        for balanced in (0, 2):
             lay.set_param(mx.PARAM_CHUNK_KEYS, chunk)
-            lay.set_param(mx.PARAM_FUSED_COMBINE, fused)
+            lay.set_param(mx.PARAM_BALANCED, balanced)
             outs.append(lay.decode(0, q))
     for o in outs[1:]:
         assert float((o - outs[0]).abs().max()) <= 2e-5
@@ -337,6 +336,84 @@ def test_error_paths_leave_state_untouched(mx):
     assert e.value.status == -3
     lay.reset()
     assert lay.seq_len(0, 0) == 0 and lay.device_lens(0) == [0]
+    lay.close()
+
+
+def test_failed_prefill_changes_nothing_and_reserved_prefill_never_allocates(mx):
+    """A prompt chunk whose staging area cannot be allocated fails with ALLOC before any state change: lengths (host
+    and device) and cache rows stay as they were, and the same call succeeds afterwards.  Once
+    mixattn_reserve_prefill has sized the areas, prefill calls reach no allocation at all."""
+    B, Hq, Hkv, d, W = 2, 8, 2, 128, 48
+    layers = [(0, 0, 0), (1, W, 1), (1, W, 1)]
+    chunks = [40, 100, 70]
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[sum(chunks)] * B, kv_dtype="bf16", out_dtype="f32")
+    ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
+
+    def inputs(ci):
+        S = chunks[ci]
+        return (wl.randn(100 + ci, (B, S, Hq, d), torch.bfloat16, DEV), wl.randn(200 + ci, (B, S, Hkv, d), torch.bfloat16, DEV),
+                wl.randn(300 + ci, (B, S, Hkv, d), torch.bfloat16, DEV))
+
+    def state():
+        rows = [lay.read_cache(ci, b, 1, slot) for ci in (0, 1) for b in range(B) for slot in (0, 7, 39)]
+        return ([lay.seq_len(ci, b) for ci in (0, 1) for b in range(B)], [lay.device_lens(ci) for ci in (0, 1)],
+                [(k.clone(), v.clone()) for k, v in rows])
+
+    def same(a, b):
+        return a[0] == b[0] and a[1] == b[1] and all(torch.equal(x[0], y[0]) and torch.equal(x[1], y[1])
+                                                     for x, y in zip(a[2], b[2]))
+
+    for ci in range(2):          # chunk 0 needs the areas, chunk 1 needs larger ones
+        q, k, v = inputs(ci)
+        for li in (0, 1):
+            before = state()
+            lay.set_param(mx.PARAM_TEST_FAIL_ALLOC, 1)
+            with pytest.raises(mx.MixAttnError) as ei:
+                lay.prefill(li, q, k, v)
+            assert ei.value.status == -7
+            assert lay.get_param(mx.PARAM_TEST_FAIL_ALLOC) == 0
+            assert same(before, state()), "a failed prefill changed lengths or cache rows (chunk %d layer %d)" % (ci, li)
+            out = lay.prefill(li, q, k, v)
+            assert_matches(out, ora.prefill(li, to_f64(q), to_f64(k), to_f64(v)), "bf16", "chunk %d layer %d" % (ci, li))
+        out = lay.prefill(2, q, None, None)
+        assert_matches(out, ora.prefill(2, to_f64(q), None, None), "bf16", "chunk %d reader" % ci)
+    # reserved: the countdown is still armed after the calls, i.e. no device allocation was attempted
+    with pytest.raises(mx.MixAttnError) as ei:
+        lay.set_param(mx.PARAM_TEST_FAIL_ALLOC, 1)
+        lay.reserve_prefill(chunks[2])
+    assert ei.value.status == -7
+    lay.reserve_prefill(chunks[2])
+    q, k, v = inputs(2)
+    lay.set_param(mx.PARAM_TEST_FAIL_ALLOC, 1)
+    for li in (0, 1):
+        out = lay.prefill(li, q, k, v)
+        assert_matches(out, ora.prefill(li, to_f64(q), to_f64(k), to_f64(v)), "bf16", "reserved, layer %d" % li)
+    assert_matches(lay.prefill(2, q, None, None), ora.prefill(2, to_f64(q), None, None), "bf16", "reserved, reader")
+    assert lay.get_param(mx.PARAM_TEST_FAIL_ALLOC) == 1
+    lay.set_param(mx.PARAM_TEST_FAIL_ALLOC, 0)
+    for li in (0, 1):
+        _check_cache(lay, ora, li, heads=[1])
+    lay.close()
+
+
+def test_bulk_loads_back_to_back_are_stream_ordered(mx):
+    """mixattn_load_kv only enqueues work: loads of several caches with different lengths, issued without any
+    synchronisation in between, each see their own per-sequence tables."""
+    B, Hq, Hkv, d, W = 3, 8, 2, 128, 40
+    layers = [(0, 0, 0), (1, W, 1), (0, 0, 2), (1, W, 3)]
+    all_lens = [[5, 300, 77], [64, 1, 129], [33, 2, 200], [90, 91, 3]]
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[300] * B, kv_dtype="bf16", out_dtype="f32")
+    ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
+    kv = [(wl.randn(10 + li, (sum(all_lens[li]), Hkv, d), torch.bfloat16, DEV),
+           wl.randn(20 + li, (sum(all_lens[li]), Hkv, d), torch.bfloat16, DEV)) for li in range(4)]
+    torch.cuda.synchronize()
+    for li in range(4):
+        lay.load_kv(li, kv[li][0], kv[li][1], all_lens[li])
+    for li in range(4):
+        ora.load(li, to_f64(kv[li][0]), to_f64(kv[li][1]), all_lens[li])
+        q = wl.randn(30 + li, (B, Hq, d), torch.bfloat16, DEV)
+        assert_matches(lay.decode(li, q), ora.decode(li, to_f64(q)), "bf16", "layer %d" % li)
+        _check_cache(lay, ora, li, heads=[0])
     lay.close()
 
 
