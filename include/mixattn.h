@@ -74,7 +74,8 @@ typedef enum {
                                   seq_len */
   MIXATTN_ERR_ALLOC = -7,      /* device or host allocation failed */
   MIXATTN_ERR_HIP = -8,        /* a HIP runtime call failed (see mixattn_last_hip_error) */
-  MIXATTN_ERR_PARAM = -9       /* unknown tuning parameter or value out of range */
+  MIXATTN_ERR_PARAM = -9,      /* unknown tuning parameter or value out of range */
+  MIXATTN_ERR_SCRATCH = -10    /* mixattn_decode_noalloc: the call needs more split-K scratch than the static area holds */
 } mixattn_status;
 
 /* One layer (Section 3): its attention kind, its window (tokens, >= 1, SLIDING only; the query attends the
@@ -145,6 +146,18 @@ int mixattn_append_kv(mixattn_layout* L, int layer, const void* k, const void* v
    out = sum_p softmax_p(scale * q.k_p) v_p.  out: device [batch, n_q_heads, head_dim].  Errors: ORDER if any
    sequence is empty. */
 int mixattn_decode(mixattn_layout* L, int layer, const void* q, void* out, void* stream);
+
+/* mixattn_decode for callers that cannot allocate device memory or depend on memory a layout allocated for scratch:
+   code under HIP graph capture that must not reference per-layout scratch, tight serving loops, harnesses that forbid
+   hipMalloc.  Same arguments, same result (to rounding order) and same errors as mixattn_decode, MFMA path only
+   (LAYOUT otherwise).  Split-K partial results go to a fixed 16 MiB area in the library's device image instead of the
+   layout's scratch (each GPU holds its own copy until the process ends; its address is looked up when a layout is
+   created on that GPU).  The call allocates nothing and frees nothing.  It is refused with SCRATCH, before anything
+   is enqueued, when batch * n_q_heads * chunks * (head_dim + 2) * 4 bytes exceed the area (chunks = the split-K
+   chunk count the call would use; calls that need no split use no scratch).  Every call on a GPU shares that GPU's
+   area: calls that overlap on one GPU (several streams, several layouts) race; calls ordered on one stream do not.
+   Nothing in the area has to be cleared between calls: a call writes every partial that it reads. */
+int mixattn_decode_noalloc(mixattn_layout* L, int layer, const void* q, void* out, void* stream);
 
 /* mixattn_append_kv followed by mixattn_decode on the same (writer) layer, as one call: same arguments, same
    result, same errors (NOT_WRITER, CAPACITY, NULL).  On the MFMA path (bf16, head_dim 128) it is a single launch:

@@ -20,11 +20,12 @@ FULL, SLIDING = 0, 1
 F32, BF16 = 0, 1
 PARAM_CHUNK_KEYS, PARAM_PREFILL_SIMPLE, PARAM_PREFILL_WAVES, PARAM_PREFILL_HEADS = 0, 2, 3, 4
 PARAM_BALANCED, PARAM_TEST_FAIL_ALLOC = 5, 6
+ERR_SCRATCH = -10
 
 EXPORTS = [
     "mixattn_validate_config", "mixattn_create_layout", "mixattn_create_layout_paged", "mixattn_destroy_layout",
     "mixattn_reset", "mixattn_release_sequence",
-    "mixattn_append_kv", "mixattn_decode", "mixattn_append_decode",
+    "mixattn_append_kv", "mixattn_decode", "mixattn_decode_noalloc", "mixattn_append_decode",
     "mixattn_reserve_prefill", "mixattn_reserve_steps", "mixattn_account_replays", "mixattn_decode_group", "mixattn_prefill", "mixattn_prefill_varlen",
     "mixattn_load_kv", "mixattn_n_caches",
     "mixattn_cache_of", "mixattn_seq_len", "mixattn_slot_of", "mixattn_slot_for", "mixattn_read_cache",
@@ -70,6 +71,7 @@ def load():
     lib.mixattn_reset.argtypes = [vp, vp]
     lib.mixattn_append_kv.argtypes = [vp, i32, vp, vp, vp]
     lib.mixattn_decode.argtypes = [vp, i32, vp, vp, vp]
+    lib.mixattn_decode_noalloc.argtypes = [vp, i32, vp, vp, vp]
     lib.mixattn_reserve_prefill.argtypes = [vp, i32]
     lib.mixattn_reserve_steps.argtypes = [vp, i32, vp]
     lib.mixattn_account_replays.argtypes = [vp, i32]
@@ -205,6 +207,13 @@ class Layout:
         else:
             self._dtype_check(out, self.out_torch, (self.batch, self.Hq, self.d))
         self._check(self.lib.mixattn_decode(self.h, layer, _ptr(q), _ptr(out), _stream()), "mixattn_decode")
+        return out
+
+    def decode_noalloc(self, layer: int, q: torch.Tensor, out: torch.Tensor) -> torch.Tensor:
+        self._dtype_check(q, self.kv_torch, (self.batch, self.Hq, self.d))
+        self._dtype_check(out, self.out_torch, (self.batch, self.Hq, self.d))
+        self._check(self.lib.mixattn_decode_noalloc(self.h, layer, _ptr(q), _ptr(out), _stream()),
+                    "mixattn_decode_noalloc")
         return out
 
     def reserve_prefill(self, max_chunk_tokens: int):

@@ -603,6 +603,31 @@ __global__ __launch_bounds__(kTiledDim) void combine_kernel(TiledDecodeParams a)
                        threadIdx.x, (OutT*)a.out + row * kTiledDim);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Split-K scratch for callers that cannot allocate (mixattn_decode_noalloc): a fixed area in the library's device
+// image.  Each GPU the library runs on holds its own copy at its own address, looked up once per device.  Nothing in
+// it has to start at zero: a launch writes every partial that its combine launch reads.  Calls that overlap on one
+// GPU share it and race.
+// ------------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+hipError_t static_scratch_init(int device) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  if (g_scratch_ptr[device]) return hipSuccess;
+  void* ptr = nullptr;
+  const hipError_t e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));  // address on the current device
+  if (e != hipSuccess) return e;
+  if (!ptr) return hipErrorInvalidSymbol;
+  g_scratch_ptr[device] = ptr;
+  return hipSuccess;
+}
+
+void* static_scratch_ptr(int device) {
+  return (device >= 0 && device < kMaxDevices) ? g_scratch_ptr[device] : nullptr;
+}
+
 hipError_t launch_decode_tiled(const DecodeLaunch& L, hipStream_t s) {
   TiledDecodeParams p;
   p.K = (const uint16_t*)L.K; p.V = (const uint16_t*)L.V;
@@ -620,8 +645,19 @@ hipError_t launch_decode_tiled(const DecodeLaunch& L, hipStream_t s) {
   const bool f32 = L.out_dtype == MIXATTN_F32, ring = L.window > 0, fused = L.k_new != nullptr;
   if (fused && (!L.d_lens_rw || !L.arrive)) return hipErrorInvalidValue;
   const bool balanced = L.balanced_runs > 0;
-  p.chunk_stride = kMaxChunks;
-  p.p_acc = L.scratch.acc; p.p_ml = L.scratch.ml;
+  const int n_pieces = balanced ? L.balanced_runs : L.n_chunks;  // partial results per row, at most
+  if (L.static_scratch) {
+    // partial rows packed as tightly as this launch allows; the host has checked that they fit the static area
+    const int64_t rows = (int64_t)std::max(L.n_group, 1) * L.batch * L.Hq;
+    p.chunk_stride = balanced ? kMaxChunks : n_pieces;
+    unsigned char* base = (unsigned char*)static_scratch_ptr(L.device);
+    if (!base || static_scratch_bytes(rows, p.chunk_stride) > (int64_t)kStaticScratchBytes) return hipErrorInvalidValue;
+    p.p_acc = (float*)base;
+    p.p_ml = p.p_acc + rows * p.chunk_stride * kTiledDim;
+  } else {
+    p.chunk_stride = kMaxChunks;
+    p.p_acc = L.scratch.acc; p.p_ml = L.scratch.ml;
+  }
   if (balanced) {
     if (ring || L.attn_window > 0 || L.n_group > 0 || L.batch > kMaxBalancedBatch) return hipErrorInvalidValue;
     p.n_chunks = L.balanced_runs;  // pieces always go through the combine launch (n_chunks != 1)

@@ -94,6 +94,7 @@ const char* mixattn_strerror(int st) {
     case MIXATTN_ERR_ALLOC: return "allocation failed";
     case MIXATTN_ERR_HIP: return "HIP runtime error";
     case MIXATTN_ERR_PARAM: return "bad tuning parameter";
+    case MIXATTN_ERR_SCRATCH: return "the call needs more split-K scratch than the static area holds";
     default: return "unknown status";
   }
 }
@@ -203,6 +204,11 @@ static int create_layout_impl(const mixattn_config* cfg, int page_tokens, int64_
   }
   const int B = L->batch;
   const int nc = (int)L->caches.size();
+  // the static split-K area of this device (mixattn_decode_noalloc): its address is looked up here, at set-up
+  if (!hip_ok(static_scratch_init(L->device))) {
+    delete L;
+    return MIXATTN_ERR_HIP;
+  }
   st = dev_alloc((void**)&L->d_lens_all, sizeof(int32_t) * (size_t)nc * B);
   if (st == MIXATTN_OK && !hip_ok(hipMemset(L->d_lens_all, 0, sizeof(int32_t) * (size_t)nc * B))) st = MIXATTN_ERR_HIP;
   if (st == MIXATTN_OK) st = dev_alloc((void**)&L->d_arrive_all, sizeof(uint32_t) * (size_t)nc);
@@ -488,11 +494,12 @@ static int plan_chunk_blocks(const mixattn_layout* L, Cache& c, int max_blocks, 
   return c.plan_chunk_blocks;
 }
 
-// Decode launch shared by mixattn_decode, mixattn_append_decode and mixattn_decode_group.
+// Decode launch shared by mixattn_decode, mixattn_decode_noalloc, mixattn_append_decode and mixattn_decode_group.
 // `extra` = 1 when a fused launch appends this step's token itself (lengths on host and device still hold the old
-// value while planning).
+// value while planning).  static_scratch: split-K partials go to the library's static device area; the call is
+// refused (SCRATCH) when they do not fit.
 static int launch_decode(mixattn_layout* L, Cache& c, int attn_window, const void* q, void* out, const void* k_new,
-                         const void* v_new, hipStream_t stream, int n_group = 0) {
+                         const void* v_new, hipStream_t stream, int n_group = 0, bool static_scratch = false) {
   const int extra = k_new ? 1 : 0;
   int max_blocks = 0;  // most blocks one sequence reads
   for (int b = 0; b < L->batch; ++b) {
@@ -514,6 +521,7 @@ static int launch_decode(mixattn_layout* L, Cache& c, int attn_window, const voi
   a.batch = L->batch; a.Hq = L->Hq; a.Hkv = L->Hkv; a.G = L->G; a.D = L->D;
   a.kv_dtype = L->kv_dtype; a.out_dtype = L->out_dtype; a.scale = L->scale;
   a.scratch = L->scratch;
+  a.static_scratch = static_scratch; a.device = L->device;
   a.k_new = k_new; a.v_new = v_new;
   a.d_lens_rw = k_new ? c.lens() : nullptr;
   a.arrive = k_new ? c.d_arrive : nullptr;
@@ -540,9 +548,10 @@ static int launch_decode(mixattn_layout* L, Cache& c, int attn_window, const voi
   // workgroup per sequence and head the long sequences finish alone, at the pace of a few workgroups; per-sequence
   // chunks of one target length come in sizes up to 2:1 and in numbers that do not fill the last round).
   // Measured: ragged batch of 64, 5.68 -> 6.63 TB/s; one sequence of 131072, 4.68 -> 5.23 TB/s; a uniform batch
-  // that needs no cut stays on the unsplit launch (6.72 against 6.64 TB/s).
+  // that needs no cut stays on the unsplit launch (6.72 against 6.64 TB/s).  Not with the static scratch area: a
+  // balanced launch needs room for the most pieces a stream can fall into, whatever the lengths turn out to be.
   if (c.kind == MIXATTN_FULL && attn_window == 0 && n_group == 0 && L->chunk_keys == 0 && L->balanced != 0 &&
-      L->batch <= 1024 && !nothing_to_read) {
+      L->batch <= 1024 && !nothing_to_read && !static_scratch) {
     int64_t sum_nb = 0;
     int max_nb = 0;
     for (int b = 0; b < L->batch; ++b) {
@@ -562,6 +571,10 @@ static int launch_decode(mixattn_layout* L, Cache& c, int attn_window, const voi
       if (runs >= 2) a.balanced_runs = (int)runs;
     }
   }
+  if (static_scratch && a.n_chunks > 1) {
+    const int64_t rows = (int64_t)std::max(n_group, 1) * L->batch * L->Hq;
+    if (static_scratch_bytes(rows, a.n_chunks) > (int64_t)kStaticScratchBytes) return MIXATTN_ERR_SCRATCH;
+  }
   HIP_TRY(launch_decode_tiled(a, stream));
   return MIXATTN_OK;
 }
@@ -580,6 +593,14 @@ int mixattn_decode(mixattn_layout* L, int layer, const void* q, void* out, void*
   if (st != MIXATTN_OK) return st;
   Cache& c = L->caches[L->layer_cache[layer]];
   return launch_decode(L, c, layer_attn_window(L, layer), q, out, nullptr, nullptr, (hipStream_t)stream);
+}
+
+int mixattn_decode_noalloc(mixattn_layout* L, int layer, const void* q, void* out, void* stream) {
+  const int st = check_decode(L, layer, q, out);
+  if (st != MIXATTN_OK) return st;
+  if (!L->tiled) return MIXATTN_ERR_LAYOUT;  // the scalar path has no scratch to begin with: mixattn_decode
+  Cache& c = L->caches[L->layer_cache[layer]];
+  return launch_decode(L, c, layer_attn_window(L, layer), q, out, nullptr, nullptr, (hipStream_t)stream, 0, true);
 }
 
 int mixattn_append_decode(mixattn_layout* L, int layer, const void* k, const void* v, const void* q, void* out,

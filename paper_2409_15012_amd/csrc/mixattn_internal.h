@@ -28,6 +28,12 @@ constexpr int kIdle = -1;                             // length of a released se
 constexpr int kMaxChunks = 64;                       // split-K chunks per (sequence, kv head)
 constexpr int kMaxHeadDim = 256;
 constexpr int kDecodeMinChunkBlocks = 4;              // a split-K chunk keeps every wavefront of its workgroup busy
+// Split-K scratch held in the library's device image for mixattn_decode_noalloc (one copy per GPU, 16 MiB)
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+// bytes of split-K partials for `rows` (sequence, query head) rows with `stride` chunk slots each: fp32 accumulators
+// of kTiledDim dims plus (max, sum)
+inline int64_t static_scratch_bytes(int64_t rows, int64_t stride) { return rows * stride * (kTiledDim + 2) * 4; }
+
 __host__ __device__ inline int k_tile_offset(int key, int dim) {
   return (key >> 4) * 2048 + (dim >> 3) * 128 + (key & 15) * 8 + (dim & 7);
 }
@@ -161,6 +167,8 @@ struct DecodeLaunch {
   int chunk_blocks;    // blocks per split-K chunk
   int n_chunks;        // grid.x
   DecodeScratch scratch;
+  bool static_scratch = false;  // partials go to the library's static device area instead (checked to fit by the host)
+  int device = 0;
   // fused append (tiled path): this step's k, v [batch, Hkv, D], the length array (advanced in place by the launch)
   // and the cache's arrival counter; nullptr = none
   const void* k_new = nullptr; const void* v_new = nullptr; int32_t* d_lens_rw = nullptr; uint32_t* arrive = nullptr;
@@ -171,6 +179,9 @@ struct DecodeLaunch {
   int balanced_runs = 0;
 };
 hipError_t launch_decode_tiled(const DecodeLaunch& a, hipStream_t s);
+// address of the static split-K scratch on `device` (looked up with that device current; once per device)
+hipError_t static_scratch_init(int device);
+void* static_scratch_ptr(int device);
 hipError_t launch_decode_rowmajor(const DecodeLaunch& a, hipStream_t s);
 
 // Bulk store of tokens into a cache or the staging area (prompt commit, bulk load, prefill staging).  A sequence
