@@ -39,6 +39,7 @@ def parse():
     ap.add_argument("--workload", default="decode32k", choices=["decode32k", "decode4k", "prefill32k", "ragged64", "variants", "gen31k", "serve"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-keys", type=int, default=0)
+    ap.add_argument("--balanced", type=int, default=-1)
     ap.add_argument("--prefill-waves", type=int, default=0)
     ap.add_argument("--prefill-heads", type=int, default=0)
     ap.add_argument("--chunks", type=int, default=1, help="prefill32k: feed the prompt in this many equal chunks")
@@ -151,6 +152,8 @@ def run_decode(args, mx, wl, torch, w, layers=None, label=None):
                                          args.out_dtype, dev, w.seed, args.page_tokens)
     if args.chunk_keys:
         lay.set_param(mx.PARAM_CHUNK_KEYS, args.chunk_keys)
+    if args.balanced >= 0:
+        lay.set_param(mx.PARAM_BALANCED, args.balanced)
     out = torch.empty((B, Hq, d), dtype=lay.out_torch, device=dev)
     full_layers = [li for li, t in enumerate(layers) if t[0] == wl.FULL]
     kinds = {"": None, "full": wl.FULL, "sliding": wl.SLIDING}[args.only]
@@ -204,7 +207,7 @@ def run_decode(args, mx, wl, torch, w, layers=None, label=None):
     if use_graph:
         # the same step captured once and replayed: every replay appends one token per sequence and attends one
         # position further (lengths live on the device; the host is told with account_replays)
-        lay.reserve_steps(2 * args.warmup + args.steps + 1)
+        lay.reserve_steps(args.warmup + args.steps + 1)
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):

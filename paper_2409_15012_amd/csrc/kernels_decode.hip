@@ -39,7 +39,7 @@ template <>
 __device__ inline void store_out<uint16_t>(uint16_t* p, float v) { *p = (uint16_t)bf16_bits_rn(v); }
 
 
-constexpr int kDecodeWaves = 4;
+constexpr int kDecodeWaves = 4;  // wavefronts per workgroup (8 were measured on launches that leave CUs idle: no gain)
 
 struct TiledDecodeParams {
   const uint16_t* K; const uint16_t* V;
@@ -92,16 +92,17 @@ __device__ inline void merge_partials(const float* p_acc, const float* p_ml, int
 // decode_piece is the work of one workgroup on blocks blk0 .. blk1-1 of (sequence b, kv head h): piece c of the
 // n_chunks_b pieces that (b, h) is cut into.  A workgroup may run it several times (balanced launches): the
 // function ends with every wavefront past its last read of the shared arrays.
-template <typename OutT, bool RING, bool FUSED, bool WINDOWED, bool GROUP, bool BALANCED>
+// n_old, slots_b, base_b: this sequence's entries of the length, slot-count and first-block tables (the caller loads
+// the three together, so that the first K/V loads wait for one round trip, not three in a row).
+template <typename OutT, bool RING, bool FUSED, bool WINDOWED, bool GROUP, bool BALANCED, int NW>
 __device__ __attribute__((always_inline)) void decode_piece(const TiledDecodeParams& a, const int b, const int h,
                                                             const int blk0, const int blk1, const int c,
-                                                            const int n_chunks_b) {
+                                                            const int n_chunks_b, const int n_old, const int slots_b,
+                                                            const int64_t base_b) {
   constexpr int kCols = GROUP ? 16 : kMaxGroup;  // head columns that carry results
-  constexpr int NW = kDecodeWaves;
-  const int n_old = a.d_lens[b];
   // a fused launch sees the sequence one token longer; a full cache that is at capacity takes no token (the host
   // refuses such a call; replays of a captured step beyond the reserved capacity end up here)
-  const bool room = FUSED && (RING || n_old < a.d_slots[b]);
+  const bool room = FUSED && (RING || n_old < slots_b);
   int n = room ? n_old + 1 : n_old;
   if (RING && n > a.window) n = a.window;
   const int new_slot = RING ? n_old % a.window : n_old;  // where a fused launch puts its token
@@ -134,8 +135,8 @@ __device__ __attribute__((always_inline)) void decode_piece(const TiledDecodePar
   // Block blk of this (sequence, kv head) sits at block index block_at(blk) of the cache: consecutive blocks when
   // the cache is contiguous; in a paged full cache the page id is looked up when the wavefront enters a new page
   // (its blocks are 4 apart, so a page of 2^shift blocks serves 2^shift / 4 consecutive iterations).
-  const int64_t nblk = a.d_slots[b] >> 5;
-  const int64_t first_blk = a.d_base[b] + (int64_t)h * nblk;
+  const int64_t nblk = slots_b >> 5;
+  const int64_t first_blk = base_b + (int64_t)h * nblk;
   const bool paged = !RING && a.pages.ids != nullptr;
   int cur_page = -1;
   int64_t cur_page_first = 0;
@@ -252,16 +253,76 @@ __device__ __attribute__((always_inline)) void decode_piece(const TiledDecodePar
     else compute_block(no_tail{}, blk, kd, vd);
   };
 
-  // Software pipeline over this wavefront's blocks blk0 + wave + 4*i, i < cnt.  The steady-state loop issues the
+  // Software pipeline over this wavefront's blocks blk0 + wave + NW*i, i < cnt.  The steady-state loop issues the
   // next block's loads unconditionally before it consumes the current one, so the wait before the MFMAs only
   // covers the older of the two blocks in flight; the last one or two blocks are peeled.
-  // A fused launch takes the block that receives the new token out of this sequence (the wavefront that owns it
-  // handles it after the pipeline, see below), so the steady-state loop stays free of conditional loads.
+  // In a fused launch the wavefront that owns the block receiving the new token visits that block last: its loads
+  // go through the pipeline like any other block's, and the token is patched into the fragments just before they
+  // are consumed (the block as stored is one token short), so the steady-state loop stays free of conditions.
   const int first = blk0 + wave;
   const bool own_new = room && new_blk >= blk0 && new_blk < blk1 && ((new_blk - blk0) & (NW - 1)) == wave;
   const int i_new = own_new ? (new_blk - first) / NW : 0x7fffffff;
-  const int cnt = (blk1 - blk0 - wave + NW - 1) / NW - (own_new ? 1 : 0);  // may be <= 0
-  auto blk_of = [&](int i) { return first + (i + (i >= i_new ? 1 : 0)) * NW; };
+  // (balanced and group launches have no registers to spare for a patch inside the pipeline: they take the block out
+  // of the sequence instead and handle it after the pipeline)
+  constexpr bool kNewInPipeline = FUSED && !BALANCED && !GROUP;
+  const int cnt = (blk1 - blk0 - wave + NW - 1) / NW - ((own_new && !kNewInPipeline) ? 1 : 0);  // may be <= 0
+  auto blk_of = [&](int i) {
+    return (kNewInPipeline && own_new && i == cnt - 1) ? new_blk : first + (i + (i >= i_new ? 1 : 0)) * NW;
+  };
+  // the new token's K pieces and V elements this lane would patch in: requested ahead of the block loads (balanced
+  // launches fetch them when they patch)
+  constexpr bool kTokenAhead = kNewInPipeline;
+  u32x4_t k_tok[4] = {};
+  uint32_t v_tok[8] = {};
+  auto load_token = [&]() {
+    const uint16_t* kn = a.k_new + ((int64_t)b * a.Hkv + h) * kTiledDim;
+    const uint16_t* vn = a.v_new + ((int64_t)b * a.Hkv + h) * kTiledDim;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) k_tok[kk] = *(const u32x4_t*)(kn + kk * 32 + g * 8);
+#pragma unroll
+    for (int nn = 0; nn < 8; ++nn) v_tok[nn] = vn[nn * 16 + col];
+  };
+  if constexpr (kTokenAhead) {
+    if (own_new) load_token();
+  }
+  auto patch_new = [&](u32x4_t* kd, u32x4_t* vd) {
+    if constexpr (!kTokenAhead) load_token();
+    // K fragments: lanes of MFMA row new_key % 16 take the token's dims kk*32 + g*8 .. +7 in key tile new_key / 16
+    {
+      const bool mine = col == (new_key & 15);
+      const bool t1 = (new_key >> 4) != 0;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          kd[kk][w] = (mine && !t1) ? k_tok[kk][w] : kd[kk][w];
+          kd[4 + kk][w] = (mine && t1) ? k_tok[kk][w] : kd[4 + kk][w];
+        }
+      }
+    }
+    // V fragments: lanes of key group (new_key % 16) / 4 hold the token as element j of every dim fragment
+    {
+      const bool mine = g == ((new_key & 15) >> 2);
+      const int j = 4 * (new_key >> 4) + (new_key & 3);
+      const uint32_t half_mask = (j & 1) ? 0xffff0000u : 0x0000ffffu;
+#pragma unroll
+      for (int nn = 0; nn < 8; ++nn) {
+        const uint32_t val = v_tok[nn] << ((j & 1) * 16);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const uint32_t msk = (mine && w == (j >> 1)) ? half_mask : 0u;
+          vd[nn][w] = (vd[nn][w] & ~msk) | (val & msk);
+        }
+      }
+    }
+  };
+  // the last block of this wavefront's sequence
+  auto finish = [&](int blk, u32x4_t* kd, u32x4_t* vd) {
+    if constexpr (kNewInPipeline) {
+      if (own_new) patch_new(kd, vd);
+    }
+    compute_last(blk, kd, vd);
+  };
   if (cnt > 0) {
     load_block(blk_of(0), kr[0], vr[0]);
     int i = 0;
@@ -274,47 +335,23 @@ __device__ __attribute__((always_inline)) void decode_piece(const TiledDecodePar
     if (i + 1 < cnt) {
       load_block(blk_of(i + 1), kr[1], vr[1]);
       compute_block(no_tail{}, blk_of(i), kr[0], vr[0]);
-      compute_last(blk_of(i + 1), kr[1], vr[1]);
+      finish(blk_of(i + 1), kr[1], vr[1]);
     } else {
-      compute_last(blk_of(i), kr[0], vr[0]);
+      finish(blk_of(i), kr[0], vr[0]);
+    }
+  }
+  if constexpr (FUSED && !kNewInPipeline) {
+    if (own_new) {
+      load_block(new_blk, kr[0], vr[0]);
+      patch_new(kr[0], vr[0]);
+      compute_last(new_blk, kr[0], vr[0]);
     }
   }
   if constexpr (FUSED) {
     if (own_new) {
-      load_block(new_blk, kr[0], vr[0]);
+      // the token goes to the cache for the launches that follow (no other wavefront of this launch reads the block)
       const uint16_t* kn = a.k_new + ((int64_t)b * a.Hkv + h) * kTiledDim;
       const uint16_t* vn = a.v_new + ((int64_t)b * a.Hkv + h) * kTiledDim;
-      // K fragments: lanes of MFMA row new_key % 16 take the token's dims kk*32 + g*8 .. +7 in key tile new_key / 16
-      {
-        const bool mine = col == (new_key & 15);
-        const bool t1 = (new_key >> 4) != 0;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          const u32x4_t val = *(const u32x4_t*)(kn + kk * 32 + g * 8);
-#pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            kr[0][kk][w] = (mine && !t1) ? val[w] : kr[0][kk][w];
-            kr[0][4 + kk][w] = (mine && t1) ? val[w] : kr[0][4 + kk][w];
-          }
-        }
-      }
-      // V fragments: lanes of key group (new_key % 16) / 4 hold the token as element j of every dim fragment
-      {
-        const bool mine = g == ((new_key & 15) >> 2);
-        const int j = 4 * (new_key >> 4) + (new_key & 3);
-        const uint32_t half_mask = (j & 1) ? 0xffff0000u : 0x0000ffffu;
-#pragma unroll
-        for (int nn = 0; nn < 8; ++nn) {
-          const uint32_t val = (uint32_t)vn[nn * 16 + col] << ((j & 1) * 16);
-#pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            const uint32_t msk = (mine && w == (j >> 1)) ? half_mask : 0u;
-            vr[0][nn][w] = (vr[0][nn][w] & ~msk) | (val & msk);
-          }
-        }
-      }
-      compute_last(new_blk, kr[0], vr[0]);
-      // the token goes to the cache for the launches that follow (no other wavefront of this launch reads the block)
       const int64_t new_at = block_at(new_blk) * kBlockElems;
       uint16_t* Kd = a.Kw + new_at;
       uint16_t* Vd = a.Vw + new_at;
@@ -418,16 +455,18 @@ __device__ inline void zero_rows(const TiledDecodeParams& a, int b, int h, int l
   }
 }
 
-template <typename OutT, bool RING, bool FUSED, bool WINDOWED = false, bool GROUP = false>
-__global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(TiledDecodeParams a) {
+template <typename OutT, bool RING, bool FUSED, bool WINDOWED = false, bool GROUP = false, int NW = kDecodeWaves>
+__global__ __launch_bounds__(NW * 64, 2) void decode_tiled_kernel(TiledDecodeParams a) {
   static_assert(!(WINDOWED && (RING || FUSED)), "a windowed reader of a full cache never writes it");
   static_assert(!GROUP || RING, "group launches serve ring caches");
   const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int n_held = a.d_lens[b];
+  const int slots_b = a.d_slots[b];
+  const int64_t base_b = a.d_base[b];
   if (n_held < 0) {  // idle sequence: zero rows, stays idle
     if (c == 0) zero_rows<OutT>(a, b, h, GROUP ? a.n_group : 1);
   } else {
-    int n = n_held + ((FUSED && (RING || n_held < a.d_slots[b])) ? 1 : 0);
+    int n = n_held + ((FUSED && (RING || n_held < slots_b)) ? 1 : 0);
     if (RING && n > a.window) n = a.window;
     const int nb_total = (n + kBlockKeys - 1) / kBlockKeys;
     const int lo = (WINDOWED && n > a.attn_window) ? n - a.attn_window : 0;  // first position attended
@@ -441,7 +480,8 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_tiled_kernel(Tile
     if (c < n_chunks_b) {  // uniform for the workgroup
       const int blk0 = fb + (int)(((int64_t)c * nb_read) / n_chunks_b);
       const int blk1 = fb + (int)(((int64_t)(c + 1) * nb_read) / n_chunks_b);
-      decode_piece<OutT, RING, FUSED, WINDOWED, GROUP, false>(a, b, h, blk0, blk1, c, n_chunks_b);
+      decode_piece<OutT, RING, FUSED, WINDOWED, GROUP, false, NW>(a, b, h, blk0, blk1, c, n_chunks_b, n_held, slots_b,
+                                                                  base_b);
     }
   }
   if constexpr (FUSED) arrive_and_advance(a, gridDim.x * gridDim.y * gridDim.z);
@@ -533,9 +573,9 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_balanced_kernel(T
     const int blk0 = off - h * nb;
     const int blk1 = (int)min((int64_t)nb, blk0 + (g1 - g));
     const int64_t gs = g - blk0;
-    decode_piece<OutT, false, FUSED, false, false, true>(a, b, h, blk0, blk1,
-                                                          blockIdx.x - balanced_first_run(gs, share),
-                                                          balanced_pieces(gs, nb, share));
+    decode_piece<OutT, false, FUSED, false, false, true, kDecodeWaves>(
+        a, b, h, blk0, blk1, blockIdx.x - balanced_first_run(gs, share), balanced_pieces(gs, nb, share), a.d_lens[b],
+        a.d_slots[b], a.d_base[b]);
     g += blk1 - blk0;
   }
   if constexpr (FUSED) arrive_and_advance(a, gridDim.x);
