@@ -36,6 +36,19 @@ hipError_t launch_advance_lens(int32_t* lens, const int32_t* src_len, int unifor
   return hipGetLastError();
 }
 
+__global__ void mark_done_kernel(int32_t* done, const int32_t* lens, const int32_t* src_len, int uniform_len, int batch) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= batch) return;
+  const int add = src_len ? src_len[b] : uniform_len;
+  if (add > 0) done[b] = lens[b] < 0 ? 0 : lens[b];
+}
+
+hipError_t launch_mark_done(int32_t* done, const int32_t* lens, const int32_t* src_len, int uniform_len, int batch,
+                            hipStream_t s) {
+  hipLaunchKernelGGL(mark_done_kernel, dim3((batch + 255) / 256), dim3(256), 0, s, done, lens, src_len, uniform_len, batch);
+  return hipGetLastError();
+}
+
 // Per-sequence tables (first packed row, row count) written by a kernel that carries the values in its arguments:
 // stream-ordered, no host synchronisation and no pinned staging buffer to recycle.
 struct SeqTableChunk {
@@ -229,6 +242,8 @@ __global__ __launch_bounds__(256) void store_tiled_kernel(StoreLaunch a) {
   if (blk * kBlockKeys >= live) return;
   // linear store whose old tokens already sit in the destination: blocks made of old tokens only stay as they are
   if (a.old_is_dest && a.window == 0 && blk * kBlockKeys + kBlockKeys <= n_old - off) return;
+  // ... or were brought up to date by an earlier call (fp16 copy of a full cache's V, chunk after chunk)
+  if (a.d_done && a.window == 0 && off == 0 && blk * kBlockKeys + kBlockKeys <= a.d_done[b]) return;
   (void)add;
 
   const int64_t blk_elem = tiled_block_index(a.d_base, a.d_slots, a.pages, a.Hkv, b, h, blk) * kBlockElems;

@@ -52,7 +52,7 @@ int upload(void* dst, const void* src, size_t bytes) {
 }
 
 void free_stage(Stage& st) {
-  void* ptrs[] = {st.K, st.V, st.d_base, st.d_slots};
+  void* ptrs[] = {st.K, st.V, st.d_base, st.d_slots, st.d_done};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   st = Stage();
@@ -354,6 +354,7 @@ int mixattn_reset(mixattn_layout* L, void* stream) {
     for (int b = 0; b < L->batch; ++b) release_pages(c, b);
     c.own_stage.cache = -1;
     c.plan_key = -1;
+    if (c.own_stage.d_done) HIP_TRY(launch_fill_i32(c.own_stage.d_done, 0, L->batch, (hipStream_t)stream));
   }
   return MIXATTN_OK;
 }
@@ -363,6 +364,7 @@ int mixattn_release_sequence(mixattn_layout* L, int b, void* stream) {
   if (b < 0 || b >= L->batch) return MIXATTN_ERR_LAYER;
   for (auto& c : L->caches) {
     HIP_TRY(launch_fill_i32(c.d_lens + b, kIdle, 1, (hipStream_t)stream));
+    if (c.own_stage.d_done) HIP_TRY(launch_fill_i32(c.own_stage.d_done + b, 0, 1, (hipStream_t)stream));
     c.len[b] = kIdle;
     c.plan_key = -1;
     release_pages(c, b);
@@ -706,6 +708,7 @@ static int grow_stage(mixattn_layout* L, Cache& c, int64_t blocks_per_head) {
   int st;
   if (!S.d_base && (st = dev_alloc((void**)&S.d_base, sizeof(int64_t) * L->batch)) != MIXATTN_OK) return st;
   if (!S.d_slots && (st = dev_alloc((void**)&S.d_slots, sizeof(int32_t) * L->batch)) != MIXATTN_OK) return st;
+  if (!S.d_done && (st = dev_alloc((void**)&S.d_done, sizeof(int32_t) * L->batch)) != MIXATTN_OK) return st;
   if (need_k && (st = dev_alloc(&nK, bytes)) != MIXATTN_OK) return st;
   if ((st = dev_alloc(&nV, bytes)) != MIXATTN_OK) {
     if (nK) (void)hipFree(nK);
@@ -728,6 +731,7 @@ static int grow_stage(mixattn_layout* L, Cache& c, int64_t blocks_per_head) {
   for (int b = 0; b < L->batch; ++b) base[b] = (int64_t)b * L->Hkv * blocks_per_head;
   if ((st = upload(S.d_base, base.data(), sizeof(int64_t) * L->batch)) != MIXATTN_OK) return st;
   if ((st = upload(S.d_slots, slots.data(), sizeof(int32_t) * L->batch)) != MIXATTN_OK) return st;
+  if (!hip_ok(hipMemset(S.d_done, 0, sizeof(int32_t) * L->batch))) return MIXATTN_ERR_HIP;  // the new area holds nothing yet
   S.blocks = blocks_per_head;
   return MIXATTN_OK;
 }
@@ -911,7 +915,9 @@ static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void*
       }
       st.batch = L->batch; st.Hkv = L->Hkv; st.D = L->D; st.elem = L->elem;
       st.max_slots = (int)max_new;
+      st.d_done = S.d_done;  // blocks converted by earlier chunks stay as they are
       HIP_TRY(launch_store_tiled(st, s));
+      HIP_TRY(launch_mark_done(S.d_done, c.lens(), d_len, varlen ? 0 : seq_len, L->batch, s));
       remember_stage();
     }
     p.Kt = c.K; p.k_base = c.d_base; p.k_slots = c.d_slots;

@@ -68,6 +68,9 @@ struct Stage {
   std::vector<int32_t> lens;   // that chunk's length per sequence
   int64_t* d_base = nullptr;   // [batch] geometry tables of the area
   int32_t* d_slots = nullptr;  // [batch]
+  // full caches: positions 0 .. d_done[b]-1 of sequence b already have their fp16 copy of V in the area (a prompt fed
+  // in chunks converts every position once, not once per chunk); zero after the area moved, a reset or a release
+  int32_t* d_done = nullptr;   // [batch]
 };
 
 struct Cache {
@@ -205,6 +208,7 @@ struct StoreLaunch {
   PageTable old_pages;         // the old cache is paged
   int old_window = 0;          // ring size of the old cache (0 = full cache)
   int old_is_dest = 0;         // the old cache is the destination itself: blocks without new tokens are skipped
+  const int32_t* d_done = nullptr;  // linear destinations from position 0: blocks wholly below d_done[b] are up to date
   int batch = 0, Hkv = 0, D = 0, elem = 0;
   int max_slots = 0;           // max over b of destination slots that can receive data (grid size)
 };
@@ -225,6 +229,10 @@ hipError_t launch_append_rowmajor(const AppendLaunch& a, hipStream_t s);
 // after a bulk store: lens[b] = tokens held once sequence b has received its new tokens (src_len[b], or uniform_len
 // for every sequence when src_len is nullptr); an idle sequence (negative) given none stays idle
 hipError_t launch_advance_lens(int32_t* lens, const int32_t* src_len, int uniform_len, int batch, hipStream_t s);
+// done[b] = lens[b] for every sequence that received tokens (src_len[b] > 0, or all when src_len is nullptr and
+// uniform_len > 0): the staged copy now covers all the sequence holds
+hipError_t launch_mark_done(int32_t* done, const int32_t* lens, const int32_t* src_len, int uniform_len, int batch,
+                            hipStream_t s);
 hipError_t launch_fill_i32(int32_t* p, int32_t value, int64_t n, hipStream_t s);
 // table[index[i]] = value[i] for i < n (host arrays; the values travel in the kernel arguments)
 hipError_t launch_scatter_i32(int32_t* table, const int64_t* index, const int32_t* value, int n, hipStream_t s);
