@@ -405,9 +405,7 @@ def run_generation(args, mx, wl, torch, layers, label):
             if writer_of[li] == li:
                 lay.prefill(li, q, k, v, out)
             else:
-                # a reader directly after its writer reuses the staged prompt; otherwise it is handed K/V again
-                direct = writer_of[li] == li - 1 or (li > 0 and writer_of[li - 1] == writer_of[li])
-                lay.prefill(li, q, None if direct else k, None if direct else v, out)
+                lay.prefill(li, q, None, None, out)   # readers reuse the prompt copy their cache keeps staged
 
     def decode_step():
         for li in range(len(layers)):
@@ -425,7 +423,8 @@ def run_generation(args, mx, wl, torch, layers, label):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     prefill()
-    torch.cuda.synchronize()
+    staging = lay.staging_bytes()
+    lay.release_prefill()   # the prompt copies are not needed by the generation loop (synchronises)
     t1 = time.perf_counter()
     for _ in range(T):
         decode_step()
@@ -434,7 +433,7 @@ def run_generation(args, mx, wl, torch, layers, label):
     r = {"label": label, "batch": B, "prompt": S, "new_tokens": T, "prefill_s": t1 - t0, "decode_s": t2 - t1,
          "total_s": t2 - t0, "output_tokens_per_s": B * T / (t2 - t0), "decode_only_tokens_per_s": B * T / (t2 - t1),
          "ms_per_decode_step": (t2 - t1) * 1e3 / T, "kv_bytes_resident": lay.kv_bytes_live(),
-         "kv_bytes_allocated": lay.kv_bytes_allocated()}
+         "kv_bytes_allocated": lay.kv_bytes_allocated(), "staging_bytes_during_prefill": staging}
     lay.close()
     return r
 
@@ -473,8 +472,7 @@ def run_serving(args, mx, wl, torch, layers, label):
             if writer_of[li] == li:
                 lay.prefill_varlen(li, q[:n], k[:n], v[:n], lens, out[:n])
             else:
-                direct = writer_of[li] == li - 1 or (li > 0 and writer_of[li - 1] == writer_of[li])
-                lay.prefill_varlen(li, q[:n], None if direct else k[:n], None if direct else v[:n], lens, out[:n])
+                lay.prefill_varlen(li, q[:n], None, None, lens, out[:n])   # the cache's staged copy of the chunk
 
     def decode_step():
         for li in range(len(layers)):
@@ -519,7 +517,7 @@ def run_serving(args, mx, wl, torch, layers, label):
     r = {"label": label, "slots": B, "requests": R, "prompt_tokens": prompt_tokens, "generated_tokens": generated,
          "decode_steps": steps, "prefill_calls": prefills, "total_s": t1 - t0,
          "output_tokens_per_s": generated / (t1 - t0), "requests_per_s": R / (t1 - t0),
-         "kv_bytes_allocated": lay.kv_bytes_allocated(), "page_tokens": page}
+         "kv_bytes_allocated": lay.kv_bytes_allocated(), "staging_bytes": lay.staging_bytes(), "page_tokens": page}
     lay.close()
     del lay
     torch.cuda.empty_cache()
@@ -545,7 +543,9 @@ def ragged_comparison(args, mx, wl, torch, warmup, steps, cycle_caches):
            "mix_tokens_per_s": r_mix["tokens_per_s"], "mix_logical_GBps": r_mix["logical_gbs"],
            "mix_kv_bytes_read_per_step": r_mix["kv_bytes_per_step"], "mix_kv_bytes_resident": r_mix["kv_bytes_resident"],
            "mix_full_layer_ms": r_mix["full_layer_ms"],
-           "mix_full_layer_GBps": r_mix["full_layer_bytes"] / (r_mix["full_layer_ms"] * 1e-3) / 1e9}
+           "mix_full_layer_GBps": r_mix["full_layer_bytes"] / (r_mix["full_layer_ms"] * 1e-3) / 1e9,
+           "mix_full_layer_bytes": r_mix["full_layer_bytes"]}
+    res["mix_full_layer_traffic"], res["mix_full_layer_traffic_source"] = _traffic_from_profiles("decode_full_%s" % w.name)
     if cycle_caches < 0:
         return res
     torch.cuda.empty_cache()
@@ -609,7 +609,7 @@ def main():
         if r["full_layer_ms"]:
             ach = r["full_layer_bytes"] / (r["full_layer_ms"] * 1e-3) / 1e9
             traffic, traffic_note = _traffic_from_profiles("decode_full_%s" % w.name)
-            line["roofline"] = {"kernel": "decode_tiled_kernel<out, full, fused append> (one full-attention layer; plus its combine launch when split)",
+            line["roofline"] = {"kernel": "one full-attention layer with its fused append: decode_tiled_kernel<out, full, fused append>, or decode_balanced_kernel + combine_balanced_kernel when the planner cuts the blocks into equal runs",
                                 "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                 "frac": ach / HBM_PEAK_GBS, "launch_ms": r["full_layer_ms"],
                                 "bytes_per_launch": r["full_layer_bytes"],
@@ -657,6 +657,8 @@ def main():
         # decode step of several layer layouts at the decode32k shape (batch 32, context 32768): how the mix of
         # standard / sliding layers and the amount of sharing move KV bytes and step time (Sections 3, 5.1, 5.2)
         w = wl.config(2)
+        if args.graph < 0:
+            args.graph = 1
         rows = {}
         for name, layers in [("mix24 (2 full unshared + 22 sliding in 6 groups)", wl.layout_mix24()),
                              ("ma-like (1 full cache read by 4 layers, sliding pairs)", wl.layout_variant("ma")),
@@ -722,6 +724,11 @@ def main():
             "config": {"workload": w.name, "batch": w.batch, "context": "uniform[1024,65536] seeded",
                        "sum_context": int(sum(w.seq_lens)), "window": 1024, "out_dtype": args.out_dtype},
             "ragged64": r,
+            "roofline": {"kernel": "one full-attention layer of the ragged batch: decode_balanced_kernel<out, fused append> + combine_balanced_kernel",
+                         "bound": "hbm", "achieved": r["mix_full_layer_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": r["mix_full_layer_GBps"] / HBM_PEAK_GBS, "launch_ms": r["mix_full_layer_ms"],
+                         "bytes_per_launch": r["mix_full_layer_bytes"], "traffic": r["mix_full_layer_traffic"],
+                         "traffic_source": r["mix_full_layer_traffic_source"]},
         })
     print(json.dumps(line))
 

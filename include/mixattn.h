@@ -214,6 +214,13 @@ int mixattn_prefill_varlen(mixattn_layout* L, int layer, const void* q, const vo
    synchronises.  Errors: ORDER (max_chunk_tokens < 1), ALLOC (areas sized so far are kept). */
 int mixattn_reserve_prefill(mixattn_layout* L, int max_chunk_tokens);
 
+/* Frees every staging area (synchronises the device first).  For callers that have finished their prompts and want
+   the memory back for the decode phase: the areas of standard caches are half the size of the cache itself.  A later
+   prefill call sizes them again (and may then allocate); a reader's k = v = NULL call after this returns ORDER.
+   mixattn_staging_bytes: device bytes the staging areas hold at present (not part of mixattn_kv_bytes_allocated). */
+int mixattn_release_prefill(mixattn_layout* L);
+int64_t mixattn_staging_bytes(const mixattn_layout* L);
+
 /* Decode steps captured into a HIP graph (Section 4 measures a serving engine, which replays its decode step this
    way).  All kernel arguments of a decode step are fixed addresses and the kernels take the sequence lengths from
    device memory, so a stream capture around one step (every writer layer's mixattn_append_decode or mixattn_append_kv,

@@ -26,7 +26,7 @@ EXPORTS = [
     "mixattn_validate_config", "mixattn_create_layout", "mixattn_create_layout_paged", "mixattn_destroy_layout",
     "mixattn_reset", "mixattn_release_sequence",
     "mixattn_append_kv", "mixattn_decode", "mixattn_decode_noalloc", "mixattn_append_decode",
-    "mixattn_reserve_prefill", "mixattn_reserve_steps", "mixattn_account_replays", "mixattn_decode_group", "mixattn_prefill", "mixattn_prefill_varlen",
+    "mixattn_reserve_prefill", "mixattn_release_prefill", "mixattn_staging_bytes", "mixattn_reserve_steps", "mixattn_account_replays", "mixattn_decode_group", "mixattn_prefill", "mixattn_prefill_varlen",
     "mixattn_load_kv", "mixattn_n_caches",
     "mixattn_cache_of", "mixattn_seq_len", "mixattn_slot_of", "mixattn_slot_for", "mixattn_read_cache",
     "mixattn_read_device_lens", "mixattn_kv_bytes_allocated", "mixattn_kv_bytes_live", "mixattn_step_read_bytes",
@@ -73,6 +73,7 @@ def load():
     lib.mixattn_decode.argtypes = [vp, i32, vp, vp, vp]
     lib.mixattn_decode_noalloc.argtypes = [vp, i32, vp, vp, vp]
     lib.mixattn_reserve_prefill.argtypes = [vp, i32]
+    lib.mixattn_release_prefill.argtypes = [vp]
     lib.mixattn_reserve_steps.argtypes = [vp, i32, vp]
     lib.mixattn_account_replays.argtypes = [vp, i32]
     lib.mixattn_append_decode.argtypes = [vp, i32, vp, vp, vp, vp, vp]
@@ -87,7 +88,7 @@ def load():
     lib.mixattn_slot_for.argtypes = [i32, i32, i64, C.POINTER(i64)]
     lib.mixattn_read_cache.argtypes = [vp, i32, i32, i32, i64, vp, vp]
     lib.mixattn_read_device_lens.argtypes = [vp, i32, C.POINTER(C.c_int32)]
-    for f in ("mixattn_kv_bytes_allocated", "mixattn_kv_bytes_live"):
+    for f in ("mixattn_kv_bytes_allocated", "mixattn_kv_bytes_live", "mixattn_staging_bytes"):
         getattr(lib, f).argtypes = [vp]
         getattr(lib, f).restype = i64
     lib.mixattn_step_read_bytes.argtypes = [vp, i32]
@@ -218,6 +219,12 @@ class Layout:
 
     def reserve_prefill(self, max_chunk_tokens: int):
         self._check(self.lib.mixattn_reserve_prefill(self.h, int(max_chunk_tokens)), "mixattn_reserve_prefill")
+
+    def release_prefill(self):
+        self._check(self.lib.mixattn_release_prefill(self.h), "mixattn_release_prefill")
+
+    def staging_bytes(self) -> int:
+        return self.lib.mixattn_staging_bytes(self.h)
 
     def reserve_steps(self, steps: int):
         self._check(self.lib.mixattn_reserve_steps(self.h, int(steps), _stream()), "mixattn_reserve_steps")

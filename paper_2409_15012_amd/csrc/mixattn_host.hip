@@ -760,6 +760,26 @@ int mixattn_reserve_prefill(mixattn_layout* L, int max_chunk_tokens) {
   return MIXATTN_OK;
 }
 
+int mixattn_release_prefill(mixattn_layout* L) {
+  if (!L) return MIXATTN_ERR_NULL;
+  // readers of a staged chunk may still be in flight
+  if (!hip_ok(hipDeviceSynchronize())) return MIXATTN_ERR_HIP;
+  for (Cache& c : L->caches) free_stage(c.own_stage);
+  L->reserved_chunk = 0;
+  return MIXATTN_OK;
+}
+
+int64_t mixattn_staging_bytes(const mixattn_layout* L) {
+  if (!L) return MIXATTN_ERR_NULL;
+  int64_t t = 0;
+  for (const Cache& c : L->caches) {
+    const Stage& S = c.own_stage;
+    const int64_t area = (int64_t)L->batch * L->Hkv * S.blocks * kBlockElems * 2;
+    t += (S.K ? area : 0) + (S.V ? area : 0);
+  }
+  return t;
+}
+
 // Prompt attention for a chunk of lens[b] tokens per sequence (varlen) or seq_len tokens for every sequence
 // (lens == nullptr).  In the varlen case seq_len is the longest chunk and q / k / v / out are packed by sequence.
 static int prefill_impl(mixattn_layout* L, int layer, const void* q, const void* k, const void* v, void* out,

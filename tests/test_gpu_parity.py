@@ -396,6 +396,61 @@ def test_failed_prefill_changes_nothing_and_reserved_prefill_never_allocates(mx)
     lay.close()
 
 
+def test_release_prefill_frees_the_staging_areas_and_later_chunks_rebuild_them(mx):
+    """mixattn_release_prefill gives the staged prompt copies back (standard cache: fp16 V for the capacity; ring: K
+    and V for window - 1 + chunk tokens); readers can no longer reuse them, decode goes on unchanged, and a further
+    chunk stages what it needs again, including the fp16 copy of the positions fed before the release."""
+    B, Hq, Hkv, d, W = 2, 8, 2, 128, 48
+    layers = [(0, 0, 0), (0, 0, 0), (1, W, 1), (1, W, 1)]
+    chunks = [70, 45]
+    cap = sum(chunks) + 2
+    lay = mx.Layout(layers, B, Hq, Hkv, d, capacity=[cap] * B, kv_dtype="bf16", out_dtype="f32")
+    ora = OracleStack([LayerSpec(*t) for t in layers], B, Hq, Hkv, d)
+    assert lay.staging_bytes() == 0
+
+    def feed(ci):
+        S = chunks[ci]
+        q = wl.randn(500 + ci, (B, S, Hq, d), torch.bfloat16, DEV)
+        for li in (0, 2):
+            k = wl.randn(600 + 10 * ci + li, (B, S, Hkv, d), torch.bfloat16, DEV)
+            v = wl.randn(700 + 10 * ci + li, (B, S, Hkv, d), torch.bfloat16, DEV)
+            assert_matches(lay.prefill(li, q, k, v), ora.prefill(li, to_f64(q), to_f64(k), to_f64(v)), "bf16",
+                           "chunk %d layer %d" % (ci, li))
+            assert_matches(lay.prefill(li + 1, q, None, None), ora.prefill(li + 1, to_f64(q), None, None), "bf16",
+                           "chunk %d layer %d" % (ci, li + 1))
+        return q
+
+    def blocks(tokens):
+        return (tokens + 31) // 32
+
+    q = feed(0)
+    per_block = B * Hkv * 32 * d * 2
+    # the standard cache's area is sized for the tokens staged so far (no reserve call was made)
+    assert lay.staging_bytes() == per_block * (blocks(chunks[0]) + 2 * blocks(chunks[0]))
+    lay.release_prefill()
+    assert lay.staging_bytes() == 0
+    for li in (1, 3):
+        with pytest.raises(mx.MixAttnError) as ei:
+            lay.prefill(li, q, None, None)
+        assert ei.value.status == -6
+    for t in range(2):
+        for li in range(4):
+            qn = wl.randn(800 + 10 * t + li, (B, Hq, d), torch.bfloat16, DEV)
+            if li in (0, 2):
+                kn = wl.randn(810 + 10 * t + li, (B, Hkv, d), torch.bfloat16, DEV)
+                vn = wl.randn(820 + 10 * t + li, (B, Hkv, d), torch.bfloat16, DEV)
+                ora.append(li, to_f64(kn), to_f64(vn))
+                out = lay.append_decode(li, kn, vn, qn)
+            else:
+                out = lay.decode(li, qn)
+            assert_matches(out, ora.decode(li, to_f64(qn)), "bf16", "decode %d layer %d" % (t, li))
+    feed(1)   # follows 72 held tokens: the standard cache's fp16 V of those is rebuilt from the cache
+    assert lay.staging_bytes() == per_block * (blocks(cap) + 2 * blocks(W - 1 + chunks[1]))
+    for li in (0, 2):
+        _check_cache(lay, ora, li, heads=[1])
+    lay.close()
+
+
 def test_bulk_loads_back_to_back_are_stream_ordered(mx):
     """mixattn_load_kv only enqueues work: loads of several caches with different lengths, issued without any
     synchronisation in between, each see their own per-sequence tables."""
