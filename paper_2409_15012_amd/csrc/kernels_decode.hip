@@ -89,6 +89,44 @@ __device__ inline void merge_partials(const float* p_acc, const float* p_ml, int
 // pass over the ring serves the whole sharing group.  No column is left for the remainders: they go through a
 // second set of P x V products instead, which keeps the arithmetic of a column the same as in a one-layer launch.
 //
+// Fused append: the lengths are advanced in place by the workgroup of the launch that arrives last at a counter.
+// Every workgroup has read all the lengths it uses before it arrives (they steer its loads, whose results it has
+// consumed), so the one that finds every other arrival counted can overwrite them: no workgroup of this launch reads a
+// length again, and the next launch on the stream sees the new values.  The counter is a device-scope atomic
+// (workgroups of one launch run on several XCDs); the last arriver puts it back to zero for the next launch.
+// Two-phase form for launches whose workgroups read the lengths once, at their start: arrive() is called by the first
+// wavefront after a workgroup barrier that every wavefront reaches with its lengths in hand, and only requests the
+// counter and the lengths the last arriver would advance; finish() consumes them after the merge of the wavefronts'
+// results, so neither round trip is waited for at the end of the launch.  (If this workgroup is the last arriver,
+// nobody writes the lengths before it does, so what it requested early is current.)
+struct Arrival {
+  uint32_t prev;   // lane 0 of the first wavefront
+  int32_t len;     // lane bb < batch of the first wavefront: length of sequence bb
+  int32_t slots;   // same, its capacity in slots (full caches)
+  __device__ inline void arrive(const TiledDecodeParams& a) {
+    if (threadIdx.x < 64) {
+      if (threadIdx.x == 0)
+        prev = __hip_atomic_fetch_add(a.arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const bool has = (int)threadIdx.x < a.batch;
+      len = has ? a.d_lens_rw[threadIdx.x] : -1;
+      slots = (has && a.window == 0) ? a.d_slots[threadIdx.x] : 0;
+    }
+  }
+  __device__ inline void finish(const TiledDecodeParams& a, uint32_t total_workgroups) {
+    if (threadIdx.x < 64) {
+      if ((uint32_t)__builtin_amdgcn_readfirstlane((int)prev) == total_workgroups - 1) {
+        if (threadIdx.x == 0) __hip_atomic_store(a.arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // idle sequences (negative) stay idle; a full cache at capacity stays as it is
+        if (len >= 0 && (a.window > 0 || len < slots)) a.d_lens_rw[threadIdx.x] = len + 1;
+        for (int bb = threadIdx.x + 64; bb < a.batch; bb += 64) {
+          const int n = a.d_lens_rw[bb];
+          if (n >= 0 && (a.window > 0 || n < a.d_slots[bb])) a.d_lens_rw[bb] = n + 1;
+        }
+      }
+    }
+  }
+};
+
 // decode_piece is the work of one workgroup on blocks blk0 .. blk1-1 of (sequence b, kv head h): piece c of the
 // n_chunks_b pieces that (b, h) is cut into.  A workgroup may run it several times (balanced launches): the
 // function ends with every wavefront past its last read of the shared arrays.
@@ -98,7 +136,7 @@ template <typename OutT, bool RING, bool FUSED, bool WINDOWED, bool GROUP, bool 
 __device__ __attribute__((always_inline)) void decode_piece(const TiledDecodeParams& a, const int b, const int h,
                                                             const int blk0, const int blk1, const int c,
                                                             const int n_chunks_b, const int n_old, const int slots_b,
-                                                            const int64_t base_b) {
+                                                            const int64_t base_b, Arrival& arrival) {
   constexpr int kCols = GROUP ? 16 : kMaxGroup;  // head columns that carry results
   // a fused launch sees the sequence one token longer; a full cache that is at capacity takes no token (the host
   // refuses such a call; replays of a captured step beyond the reserved capacity end up here)
@@ -385,6 +423,8 @@ __device__ __attribute__((always_inline)) void decode_piece(const TiledDecodePar
     }
   }
   __syncthreads();
+  // every wavefront of the workgroup is past its reads of the length array: the arrival's round trip runs under the merge
+  if constexpr (FUSED && !BALANCED) arrival.arrive(a);
 
   const bool direct = (a.n_chunks == 1);
   // result row of head column hd: the layer's block of rows, then (sequence, query head)
@@ -419,12 +459,8 @@ __device__ __attribute__((always_inline)) void decode_piece(const TiledDecodePar
   if constexpr (BALANCED) __syncthreads();  // the shared arrays are written again by this workgroup's next piece
 }
 
-// Fused append: the lengths are advanced in place by the workgroup of the launch that finishes last.  Every
-// workgroup has read all the lengths it uses before it arrives (they steer its loads, whose results it has consumed),
-// so the one that finds every other arrival counted can overwrite them: no workgroup of this launch reads a length
-// again, and the next launch on the stream sees the new values.  The counter is a device-scope atomic (workgroups of
-// one launch run on several XCDs); the last arriver puts it back to zero for the next launch.  Called by every
-// workgroup of the grid exactly once, from uniform control flow.
+// One-phase form of the arrival (balanced launches, whose workgroups read lengths again for every piece): called by
+// every workgroup of the grid exactly once, at its end, from uniform control flow.
 __device__ inline void arrive_and_advance(const TiledDecodeParams& a, uint32_t total_workgroups) {
   __shared__ int s_is_last;
   __syncthreads();  // every wavefront of this workgroup is past its reads of the length array
@@ -463,6 +499,8 @@ __global__ __launch_bounds__(NW * 64, 2) void decode_tiled_kernel(TiledDecodePar
   const int n_held = a.d_lens[b];
   const int slots_b = a.d_slots[b];
   const int64_t base_b = a.d_base[b];
+  Arrival arrival;
+  bool arrived = false;
   if (n_held < 0) {  // idle sequence: zero rows, stays idle
     if (c == 0) zero_rows<OutT>(a, b, h, GROUP ? a.n_group : 1);
   } else {
@@ -481,10 +519,17 @@ __global__ __launch_bounds__(NW * 64, 2) void decode_tiled_kernel(TiledDecodePar
       const int blk0 = fb + (int)(((int64_t)c * nb_read) / n_chunks_b);
       const int blk1 = fb + (int)(((int64_t)(c + 1) * nb_read) / n_chunks_b);
       decode_piece<OutT, RING, FUSED, WINDOWED, GROUP, false, NW>(a, b, h, blk0, blk1, c, n_chunks_b, n_held, slots_b,
-                                                                  base_b);
+                                                                  base_b, arrival);
+      arrived = true;
     }
   }
-  if constexpr (FUSED) arrive_and_advance(a, gridDim.x * gridDim.y * gridDim.z);
+  if constexpr (FUSED) {
+    if (!arrived) {  // uniform for the workgroup: it had no blocks to read
+      __syncthreads();
+      arrival.arrive(a);
+    }
+    arrival.finish(a, gridDim.x * gridDim.y * gridDim.z);
+  }
 }
 
 // Balanced launch for full caches whose sequences differ in length.  The blocks of all (sequence, kv head) streams,
@@ -565,6 +610,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_balanced_kernel(T
       if ((int64_t)s_first[mid] * a.Hkv <= g0) b = mid; else hi = mid;
     }
   }
+  Arrival unused_arrival;  // balanced launches arrive once per workgroup, after the last piece
   for (int64_t g = g0; g < g1;) {
     while ((int64_t)s_first[b + 1] * a.Hkv <= g) ++b;  // g < total, so b stays below the batch size
     const int nb = s_first[b + 1] - s_first[b];
@@ -575,7 +621,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_balanced_kernel(T
     const int64_t gs = g - blk0;
     decode_piece<OutT, false, FUSED, false, false, true, kDecodeWaves>(
         a, b, h, blk0, blk1, blockIdx.x - balanced_first_run(gs, share), balanced_pieces(gs, nb, share), a.d_lens[b],
-        a.d_slots[b], a.d_base[b]);
+        a.d_slots[b], a.d_base[b], unused_arrival);
     g += blk1 - blk0;
   }
   if constexpr (FUSED) arrive_and_advance(a, gridDim.x);
