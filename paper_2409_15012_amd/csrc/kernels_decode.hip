@@ -132,11 +132,15 @@ struct Arrival {
 // function ends with every wavefront past its last read of the shared arrays.
 // n_old, slots_b, base_b: this sequence's entries of the length, slot-count and first-block tables (the caller loads
 // the three together, so that the first K/V loads wait for one round trip, not three in a row).
+// kr, vr: the two fragment sets of the load pipeline; preloaded (uniform for the wavefront): kr[0], vr[0] already
+// hold, or are about to receive, block blk0 + wave.
 template <typename OutT, bool RING, bool FUSED, bool WINDOWED, bool GROUP, bool BALANCED, int NW>
 __device__ __attribute__((always_inline)) void decode_piece(const TiledDecodeParams& a, const int b, const int h,
                                                             const int blk0, const int blk1, const int c,
                                                             const int n_chunks_b, const int n_old, const int slots_b,
-                                                            const int64_t base_b, Arrival& arrival) {
+                                                            const int64_t base_b, Arrival& arrival,
+                                                            u32x4_t (&kr)[2][8], u32x4_t (&vr)[2][8],
+                                                            const bool preloaded) {
   constexpr int kCols = GROUP ? 16 : kMaxGroup;  // head columns that carry results
   // a fused launch sees the sequence one token longer; a full cache that is at capacity takes no token (the host
   // refuses such a call; replays of a captured step beyond the reserved capacity end up here)
@@ -195,7 +199,6 @@ __device__ __attribute__((always_inline)) void decode_piece(const TiledDecodePar
   for (int nn = 0; nn < 8; ++nn) o[nn] = floatx4_t{0.f, 0.f, 0.f, 0.f};
   float m = -INFINITY, lsum = 0.f;
 
-  u32x4_t kr[2][8], vr[2][8];
   auto load_block = [&](int blk, u32x4_t* kd, u32x4_t* vd) {
     const int64_t at = block_at(blk) * (kBlockElems / 8);
     const u32x4_t* kp = Kb + at;
@@ -362,7 +365,7 @@ __device__ __attribute__((always_inline)) void decode_piece(const TiledDecodePar
     compute_last(blk, kd, vd);
   };
   if (cnt > 0) {
-    load_block(blk_of(0), kr[0], vr[0]);
+    if (!preloaded) load_block(blk_of(0), kr[0], vr[0]);  // else the caller requested it before the length was known
     int i = 0;
     for (; i + 2 < cnt; i += 2) {
       load_block(blk_of(i + 1), kr[1], vr[1]);
@@ -496,9 +499,32 @@ __global__ __launch_bounds__(NW * 64, 2) void decode_tiled_kernel(TiledDecodePar
   static_assert(!(WINDOWED && (RING || FUSED)), "a windowed reader of a full cache never writes it");
   static_assert(!GROUP || RING, "group launches serve ring caches");
   const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  const int n_held = a.d_lens[b];
-  const int slots_b = a.d_slots[b];
-  const int64_t base_b = a.d_base[b];
+  constexpr bool kAhead = RING && !FUSED && !GROUP && !WINDOWED;  // first blocks requested ahead of the length
+  int n_held = 0;
+  if constexpr (!kAhead) n_held = a.d_lens[b];
+  // a ring has the same geometry for every sequence: no table needed
+  const int slots_b = RING ? ((a.window + kBlockKeys - 1) & ~(kBlockKeys - 1)) : a.d_slots[b];
+  const int64_t base_b = RING ? (int64_t)b * a.Hkv * (slots_b >> 5) : a.d_base[b];
+  u32x4_t kr[2][8], vr[2][8];
+  // A reader of a ring that is not split knows where its wavefronts' first blocks are from the kernel arguments
+  // alone: they are requested before the length arrives (a wavefront whose block turns out to be beyond the held
+  // tokens drops what it loaded; the ring's storage is there whatever the length is).
+  bool preloaded = false;
+  if constexpr (kAhead) {
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (gridDim.x == 1 && wave < (slots_b >> 5)) {
+      const int64_t at = (base_b + (int64_t)h * (slots_b >> 5) + wave) * (kBlockElems / 8) + (threadIdx.x & 63);
+      const u32x4_t* kp = (const u32x4_t*)a.K + at;
+      const u32x4_t* vp = (const u32x4_t*)a.V + at;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) kr[0][i] = kp[i * 64];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) vr[0][i] = vp[i * 64];
+      preloaded = true;
+    }
+    __builtin_amdgcn_sched_barrier(0);  // the length is asked for after the loads above are on their way
+    n_held = a.d_lens[b];
+  }
   Arrival arrival;
   bool arrived = false;
   if (n_held < 0) {  // idle sequence: zero rows, stays idle
@@ -519,7 +545,7 @@ __global__ __launch_bounds__(NW * 64, 2) void decode_tiled_kernel(TiledDecodePar
       const int blk0 = fb + (int)(((int64_t)c * nb_read) / n_chunks_b);
       const int blk1 = fb + (int)(((int64_t)(c + 1) * nb_read) / n_chunks_b);
       decode_piece<OutT, RING, FUSED, WINDOWED, GROUP, false, NW>(a, b, h, blk0, blk1, c, n_chunks_b, n_held, slots_b,
-                                                                  base_b, arrival);
+                                                                  base_b, arrival, kr, vr, preloaded);
       arrived = true;
     }
   }
@@ -611,6 +637,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_balanced_kernel(T
     }
   }
   Arrival unused_arrival;  // balanced launches arrive once per workgroup, after the last piece
+  u32x4_t kr[2][8], vr[2][8];
   for (int64_t g = g0; g < g1;) {
     while ((int64_t)s_first[b + 1] * a.Hkv <= g) ++b;  // g < total, so b stays below the batch size
     const int nb = s_first[b + 1] - s_first[b];
@@ -621,7 +648,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void decode_balanced_kernel(T
     const int64_t gs = g - blk0;
     decode_piece<OutT, false, FUSED, false, false, true, kDecodeWaves>(
         a, b, h, blk0, blk1, blockIdx.x - balanced_first_run(gs, share), balanced_pieces(gs, nb, share), a.d_lens[b],
-        a.d_slots[b], a.d_base[b], unused_arrival);
+        a.d_slots[b], a.d_base[b], unused_arrival, kr, vr, false);
     g += blk1 - blk0;
   }
   if constexpr (FUSED) arrive_and_advance(a, gridDim.x);
