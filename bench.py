@@ -71,16 +71,21 @@ def parse():
     return ap.parse_args()
 
 
-def _source_digest(name):
+def _source_digest(names):
+    """sha256 (first 16 hex digits) over the named files of csrc/, in order."""
     import hashlib
-    with open(os.path.join(ROOT, "paper_2409_15012_amd", "csrc", name), "rb") as f:
-        return hashlib.sha256(f.read()).hexdigest()[:16]
+    h = hashlib.sha256()
+    for name in names:
+        with open(os.path.join(ROOT, "paper_2409_15012_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
 
 
-def _traffic_from_profiles(kernel_tag, source="kernels_decode.hip"):
+def _traffic_from_profiles(kernel_tag, source=("kernels_decode.hip", "mixattn_host.hip")):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE) in runs of their own, recorded as
-    text under profiles/ together with a digest of the kernel source they were taken with.  Returns (bytes, note):
-    bytes is None when there is no record or the kernel source has changed since (a stale figure is not reported)."""
+    text under profiles/ together with a digest of the sources they were taken with (the decode kernels and the host
+    side that plans their launches).  Returns (bytes, note): bytes is None when there is no record or a source has
+    changed since (a stale figure is not reported)."""
     path = os.path.join(ROOT, "profiles", "traffic_%s.txt" % kernel_tag)
     value, digest = None, None
     try:
@@ -88,11 +93,11 @@ def _traffic_from_profiles(kernel_tag, source="kernels_decode.hip"):
             if line.startswith("traffic_bytes_per_launch:"):
                 value = float(line.split(":")[1])
             if line.startswith("kernel_source_sha256_16:"):
-                digest = line.split(":")[1].strip()
+                digest = line.split(":")[1].split()[0]
     except OSError:
         return None, "no recorded counter run"
     if digest != _source_digest(source):
-        return None, "recorded counter run (profiles/traffic_%s.txt) is for an older %s" % (kernel_tag, source)
+        return None, "recorded counter run (profiles/traffic_%s.txt) is for older sources (%s)" % (kernel_tag, ", ".join(source))
     return value, "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs recorded in profiles/traffic_%s.txt" % kernel_tag
 
 
