@@ -3,6 +3,8 @@
 Holds no attention arithmetic of its own.
 """
 
+import os
+
 import numpy as np
 import torch
 
@@ -84,9 +86,19 @@ def errors(out: torch.Tensor, ref: np.ndarray):
     return max_abs, rel_l2
 
 
+def _report(what, dtype, out_dtype, max_abs, rel_l2):
+    """With MIXATTN_TEST_REPORT=<file> every comparison appends its errors there (how far the tests are from their
+    bounds; nothing reads the file)."""
+    path = os.environ.get("MIXATTN_TEST_REPORT")
+    if path:
+        with open(path, "a") as f:
+            f.write("%s\t%s\t%s\t%.4g\t%.4g\n" % (what, dtype, out_dtype, max_abs, rel_l2))
+
+
 def assert_matches(out: torch.Tensor, ref: np.ndarray, dtype: str, what: str = ""):
     assert not torch.isnan(out).any(), "NaN in output " + what
     max_abs, rel_l2 = errors(out, ref)
+    _report(what, dtype, str(out.dtype), max_abs, rel_l2)
     if out.dtype == torch.bfloat16:
         base_abs, base_rel = (F32_TOL, F32_TOL) if dtype == "f32" else (BF16_MAX_ABS, BF16_REL_L2)
         excess = np.abs(to_f64(out) - ref) - (base_abs + BF16_OUT_ULP * np.abs(ref))
