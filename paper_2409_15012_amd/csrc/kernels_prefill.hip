@@ -170,40 +170,47 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_tiled_kernel(TiledPrefillP
   const int64_t k_first = k_paged ? 0 : a.k_base[b] + (int64_t)h * (a.k_slots[b] >> 5);
   const int32_t* k_ids = k_paged ? a.k_pages.ids + (int64_t)b * a.k_pages.max_pages : nullptr;
   const int k_shift = a.k_pages.shift, k_mask = (1 << a.k_pages.shift) - 1;
+  // A block past the prompt (the second half of the last tile) is read from the last block that holds keys instead:
+  // finite data for products that the causal mask discards, and no second code path in the tile loop.
   struct TilePages { int pg[2]; };
   auto pages_of = [&](int jt) {
     TilePages t;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      const int kb = jt * 2 + j;
-      t.pg[j] = (k_paged && kb < nblk_valid) ? k_ids[kb >> k_shift] : 0;
+      const int kb = min(jt * 2 + j, nblk_valid - 1);
+      t.pg[j] = (k_paged && kb >= 0) ? k_ids[kb >> k_shift] : 0;
     }
     return t;
   };
+  // block index in the K buffer, kept in scalar registers (everything about it is the same for the whole workgroup)
   auto k_block = [&](int kb, int pg) -> int64_t {
-    return k_paged ? ((((int64_t)pg * a.Hkv + h) << k_shift) + (kb & k_mask)) : k_first + kb;
+    if (!k_paged) return k_first + kb;
+    const int pgs = __builtin_amdgcn_readfirstlane(pg);
+    return (((int64_t)pgs * a.Hkv + h) << k_shift) + (kb & k_mask);
   };
 
-  // Tile jt -> stage buf.  A tile is 1024 16-byte pieces of K and of V (512 per block); piece p = T*i + tid, with
-  // T threads, lands at LDS byte 16*p, which is what a direct load does when the wave-uniform LDS base is that of
-  // the wave's first lane.
+  // Tile jt -> stage buf.  A block is 512 16-byte pieces of K and of V; piece p = T*i + tid, with T threads, lands at
+  // LDS byte 16*p of its block, which is what a direct load does when the wave-uniform LDS base is that of the wave's
+  // first lane.  The global address is a uniform block base plus the lane's 32-bit byte offset, so that per tile only
+  // scalar arithmetic is left.
+  const char* const Kbytes = (const char*)a.Kt;
+  const char* const Vbytes = (const char*)Vg;
   auto issue = [&](int jt, int buf, const TilePages& tp) {
     constexpr int T = NW * 64;
 #pragma unroll
-    for (int i = 0; i < 1024 / T; ++i) {
-      const int kb = jt * 2 + (T * i) / 512;
-      const int in_block = tid + (T * i) % 512;
-      uint16_t* lk = sK(buf) + (T * i + wave * 64) * 8;
-      uint16_t* lv = sV(buf) + (T * i + wave * 64) * 8;
-      if (kb < nblk_valid) {
-        const int64_t k_at = k_block(kb, tp.pg[(T * i) / 512]);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Kt + k_at * 512 + in_block),
+    for (int j = 0; j < 2; ++j) {
+      const int kb = min(jt * 2 + j, nblk_valid - 1);
+      const char* kbase = Kbytes + k_block(kb, tp.pg[j]) * (int64_t)(kBlockElems * 2);
+      const char* vbase = Vbytes + (int64_t)kb * (kBlockElems * 2);
+#pragma unroll
+      for (int i = 0; i < 512 / T; ++i) {
+        const uint32_t off = (uint32_t)(T * i + tid) * 16u;
+        uint16_t* lk = sK(buf) + j * kBlockElems + (T * i + wave * 64) * 8;
+        uint16_t* lv = sV(buf) + j * kBlockElems + (T * i + wave * 64) * 8;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kbase + off),
                                          (__attribute__((address_space(3))) void*)lk, 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Vg + (int64_t)kb * 512 + in_block),
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vbase + off),
                                          (__attribute__((address_space(3))) void*)lv, 16, 0, 0);
-      } else {  // beyond the prompt: zeros (finite data for the masked products)
-        ((u32x4_t*)lk)[lane] = u32x4_t{0u, 0u, 0u, 0u};
-        ((u32x4_t*)lv)[lane] = u32x4_t{0u, 0u, 0u, 0u};
       }
     }
   };
