@@ -73,3 +73,37 @@ def test_noalloc_decode_matches_decode_two_calls_second_smaller(mx, out_dtype):
     for _, l, _ in (big, small):
         l.close()
     lay.close()
+
+
+def test_noalloc_decode_inside_a_captured_graph(mx):
+    """The callers this entry point is for include code under graph capture: the calls of a reader step are captured
+    (nothing in them allocates, synchronises or records a memset) and replayed three times with new queries, with the
+    program's own eager work between the replays; every replay must equal the eager result for the same queries."""
+    Hq, Hkv = 8, 2
+    layers, lay, ora = _stack(mx, 3, Hq, Hkv, 1024, [6000, 2500, 4100], "f32")
+    lay.set_param(mx.PARAM_BALANCED, 0)
+    qs = [torch.zeros((lay.batch, Hq, D), dtype=torch.bfloat16, device=DEV) for _ in layers]
+    outs = [torch.zeros((lay.batch, Hq, D), dtype=torch.float32, device=DEV) for _ in layers]
+
+    def step():
+        for li in range(len(layers)):
+            lay.decode_noalloc(li, qs[li], outs[li])
+
+    step()   # warm-up outside the capture (kernel modules, planner memo)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for r in range(3):
+        for li in range(len(layers)):
+            qs[li].copy_(wl.randn(900 + 10 * r + li, (lay.batch, Hq, D), torch.bfloat16, DEV))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [o.clone() for o in outs]
+        for li in range(len(layers)):
+            want = lay.decode(li, qs[li])          # eager, the layout's own scratch
+            torch.cuda.synchronize()
+            assert torch.equal(got[li], want), "replay %d layer %d differs from the eager call" % (r, li)
+            assert_matches(got[li], ora.decode(li, to_f64(qs[li])), "bf16", "replay %d layer %d" % (r, li))
+    del graph
+    lay.close()
