@@ -21,7 +21,7 @@
  *  - The layout owns its caches and scratch; they are allocated in
  *    mixattn_create_layout and freed in mixattn_destroy_layout.  The one exception is
  *    the staging area of prompt chunks (MFMA path), which mixattn_reserve_prefill sizes
- *    once; a mixattn_prefill* call that finds it too small grows it (this synchronises
+ *    once (and mixattn_release_prefill gives back); a mixattn_prefill* call that finds it too small grows it (this synchronises
  *    the device and allocates) before it changes anything else.  No other hot call
  *    allocates or synchronises.
  *  - Sequence lengths live on the device, at addresses that never change, and are
